@@ -1,0 +1,179 @@
+"""Benchmark of the HDET hot path on one MI355X.
+
+Workload (default): the flat-buffer fan-out + converge case -- N = 8 replicas x P = 1e9
+fp32 parameters, AdamW state per replica, per-replica synthetic gradients ~N(0, (1e-3)^2),
+alpha = 0.1, converge every T = 16 steps fused into the sync-step update, auto-LR controller
+on with injected losses.  A step is one pass of the whole path: hdet_fanout_step, and on
+sync steps hdet_converge + hdet_autolr_update.  All buffers are resident in HBM before the
+timed region starts.
+
+Prints ONE JSON line (see the keys below).  `roofline` is for the update kernel:
+algorithmic bytes (28 B per replica-element: theta, g, m, v read, theta, m, v written)
+divided by the kernel's average duration measured with HIP events on the library's stream.
+`cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+ADAMW_BYTES = 28          # per replica-element per update
+CONVERGE_BYTES = 8        # standalone converge: 4 read + 4 written
+
+
+def oracle_baseline(n, t_sync, p_sample, steps):
+    """The CPU oracle as it stands on a bounded sample: same N, T, optimizer; P = p_sample."""
+    import numpy as np
+    import hdet_inputs as I
+    from oracle import hdet_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    cfg = O.Config(n_replicas=n, total_steps=steps, sync_interval=t_sync, warm_steps=0, lr_max=1e-3,
+                   alpha=0.1, autolr_enabled=True, optimizer=O.ADAMW, weight_decay=0.01,
+                   grad_mode=O.GRAD_PER_REPLICA, seed=7)
+    orc = O.HDETOracle(cfg, I.flat_theta0(n, p_sample, 5))
+    g = I.flat_grads(n, p_sample, 99, 1)
+    t0 = time.perf_counter()
+    for t in range(1, steps + 1):
+        orc.step(g, 1.0 + 0.01 * np.arange(n))
+    dt = time.perf_counter() - t0
+    return dt, cores
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--params", type=float, default=1e9, help="P per replica (default: the benchmark's 1e9)")
+    ap.add_argument("--replicas", type=int, default=8)
+    ap.add_argument("--sync-interval", type=int, default=16)
+    ap.add_argument("--grad-mode", choices=["per_replica", "shared"], default="per_replica")
+    ap.add_argument("--unfused", action="store_true", help="standalone converge kernel on sync steps")
+    ap.add_argument("--replicas-per-thread", type=int, default=0)
+    ap.add_argument("--blocks", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the replicas are an axis in one GPU's memory); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import hdet_inputs as I
+    import paper_2604_24708_amd as H
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    n, P, T = args.replicas, int(args.params), args.sync_interval
+    stride = (P + 3) // 4 * 4
+    total = args.warmup + args.steps
+
+    theta = torch.empty((n, stride), dtype=torch.float32, device=dev)
+    g = torch.empty_like(theta)
+    m = torch.zeros_like(theta)
+    v = torch.zeros_like(theta)
+    I.device_normal_(theta[0], I.SEED_INIT, 0.02)          # identical replicas at t = 0
+    for r in range(1, n):
+        theta[r].copy_(theta[0])
+    I.device_normal_(g, I.SEED_GRADS, 1e-3)                # per-replica gradients, fixed over the run
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+    cfg = H.make_config(n_replicas=n, sync_interval=T, total_steps=total, warm_steps=int(0.3 * total),
+                        lr_max=1e-3, alpha=0.1, autolr_enabled=1, optimizer=H.HDET_ADAMW,
+                        weight_decay=0.01,
+                        grad_mode=H.HDET_GRAD_SHARED if args.grad_mode == "shared" else H.HDET_GRAD_PER_REPLICA,
+                        model_kind=H.HDET_FLAT, n_params=P, seed=I.SEED_PERM, stream=stream.cuda_stream)
+    h = H.hdet_create(cfg, theta, m, v, plane_stride=stride)
+    if args.replicas_per_thread or args.blocks:
+        H.hdet_set_launch_shape(h, args.replicas_per_thread, args.blocks)
+    losses = [1.0 + 0.01 * r for r in range(n)]
+    flags = 0 if args.unfused else H.HDET_FUSE_CONVERGE
+
+    upd_ev, conv_ev = [], []
+
+    def step(t, timed):
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+        H.hdet_fanout_step(h, g, flags)
+        if timed:
+            e1.record(stream)
+            upd_ev.append((e0, e1))
+        if t % T == 0:
+            if timed and args.unfused:
+                c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                c0.record(stream)
+            H.hdet_converge(h)
+            if timed and args.unfused:
+                c1.record(stream)
+                conv_ev.append((c0, c1))
+            H.hdet_autolr_update(h, losses)
+
+    for t in range(1, args.warmup + 1):
+        step(t, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup + 1, total + 1):
+        step(t, True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt / args.steps * 1e3
+    upd_ms = sum(a.elapsed_time(b) for a, b in upd_ev) / len(upd_ev)
+    bytes_per_launch = ADAMW_BYTES * n * P
+    achieved = bytes_per_launch / (upd_ms * 1e-3) / 1e9
+    st = H.hdet_get_state(h)
+    H.hdet_destroy(h)
+
+    out = {
+        "metric": "replica-steps/s at N=8 (fused update+converge, flat buffers)",
+        "value": n * args.steps / dt,
+        "unit": "replica-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"flat fan-out+converge: N={n} replicas x P={P:.3g} fp32, AdamW(0.9,0.999,wd 0.01), "
+                               f"alpha=0.1, T={T}, grads ~N(0,1e-3^2) per replica, {args.grad_mode} gradients, "
+                               f"converge {'standalone' if args.unfused else 'fused into the sync-step update'}, auto-LR on",
+                   "n_replicas": n, "n_params": P, "sync_interval": T, "grad_mode": args.grad_mode,
+                   "controller_updates": int(st.k)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "hdet_update_kernel", "kernel_ms": upd_ms,
+                     "algorithmic_bytes_per_launch": bytes_per_launch},
+    }
+    if conv_ev:
+        cms = sum(a.elapsed_time(b) for a, b in conv_ev) / len(conv_ev)
+        out["converge_standalone"] = {"kernel_ms": cms, "achieved": CONVERGE_BYTES * n * P / (cms * 1e-3) / 1e9,
+                                      "unit": "GB/s"}
+    if not args.no_cpu_baseline:
+        del theta, g, m, v
+        torch.cuda.empty_cache()
+        p_sample, o_steps = 4_000_000, T + 1
+        odt, cores = oracle_baseline(n, T, p_sample, o_steps)
+        out["cpu_baseline"] = {"value": n * o_steps / odt * (p_sample / P), "unit": "replica-steps/s",
+                               "cores": cores, "kind": "oracle",
+                               "sample": f"oracle (numpy, fp64 arithmetic) on N={n} x P={p_sample} for {o_steps} steps "
+                                         f"incl. one converge+controller, {odt:.1f} s; scaled linearly in P to P={P:.3g}"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,207 @@
+/*
+ * hdet.h -- C ABI of the HDET (Hyperparameter-Divergent Ensemble Training) step for one
+ * AMD MI355X (gfx950).
+ *
+ * The N data-parallel replicas of the paper live as a replica axis in one GPU's memory:
+ * every per-replica tensor is an array of N planes, plane r starting `plane_stride`
+ * elements after plane r-1.  The paper's AllReduce calls become reductions along that axis.
+ *
+ * One training step is (Algorithm 1 of the paper):
+ *     hdet_forward_backward   loss and gradient of every replica          (model modes only)
+ *     hdet_fanout_step        update t with per-replica rate eta_r        (Sec. 3.2, Eq. 1-2)
+ *   and, when t mod T == 0,
+ *     hdet_converge           replica mean of the parameters              (Sec. 3.3, Eq. 3)
+ *     hdet_autolr_update      controller on the interval losses           (Sec. 3.4, Eq. 4-9)
+ *
+ * General rules
+ *   - Every pointer named *_dev is DEVICE memory, owned by the caller and borrowed for the
+ *     lifetime of the handle; pointers named *_host are host memory read or written during
+ *     the call only.  The library allocates one small device control block per handle
+ *     (a few KiB) and nothing else on the device.
+ *   - All device work is enqueued on the HIP stream given at creation; calls return without
+ *     waiting for it unless stated otherwise.  Calls on one handle must not overlap.
+ *   - Every function returns 0 (HDET_OK) or a negative HDET_E* code; after a failure
+ *     hdet_last_error() gives a message.  No C++ exception crosses this boundary.
+ *   - There is no CPU fallback: without a HIP device hdet_create fails with HDET_EHIP.
+ */
+#ifndef HDET_H
+#define HDET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HDET_MAX_REPLICAS 64   /* one wavefront holds one replica per lane in the controller */
+#define HDET_MAX_CH       4    /* explored hyperparameter channels (Remark 1)                */
+#define HDET_MAX_LAYERS   16
+
+enum { HDET_OK = 0, HDET_EINVAL = -1, HDET_ESTATE = -2, HDET_EHIP = -3 };
+
+enum { HDET_SGDM = 0, HDET_ADAMW = 1 };                       /* optimizer                   */
+enum { HDET_GRAD_SHARED = 0, HDET_GRAD_PER_REPLICA = 1 };     /* gradient exchange           */
+enum { HDET_FP32 = 0, HDET_BF16_GEMM_FP32_MASTER = 1 };       /* precision of the model GEMMs */
+enum { HDET_FLAT = 0, HDET_MLP = 1 };                         /* model kind                  */
+enum { HDET_CH_LR = 0, HDET_CH_DROPOUT = 1, HDET_CH_WD = 2 }; /* channel kinds               */
+
+/* flags of hdet_fanout_step */
+#define HDET_FUSE_CONVERGE 1u  /* on a sync step, average inside the update kernel (Eq. 3)   */
+
+typedef struct hdet_handle hdet_handle;
+
+/* One explored scalar hyperparameter beside the learning rate (Remark 1): replica r uses
+ * base * rho_{pi(r)} with rho from Eq. 1 at this channel's alpha and its own permutation. */
+typedef struct {
+  int32_t kind;        /* HDET_CH_DROPOUT or HDET_CH_WD                                      */
+  int32_t reserved;
+  double  base;        /* initial centre value h_bar                                         */
+  double  alpha;       /* spread ratio                                                       */
+  double  lambda;      /* step of Eq. 7 for this channel                                     */
+  double  lo, hi;      /* the centre value is clamped to [lo, hi] after each controller step */
+} hdet_channel;
+
+typedef struct {
+  int64_t n_params;                        /* HDET_FLAT: P, parameters per replica           */
+  int32_t n_layers;                        /* HDET_MLP: number of Linear layers              */
+  int32_t widths[HDET_MAX_LAYERS + 1];     /* HDET_MLP: d_in, hidden..., d_out               */
+  int32_t batch;                           /* HDET_MLP: rows per replica and step            */
+} hdet_model_dims;
+
+/* Arguments of Algorithm 1 ("Require") plus what the paper leaves to the optimizer. */
+typedef struct {
+  int32_t  n_replicas;      /* N, 1..HDET_MAX_REPLICAS                                       */
+  int32_t  sync_interval;   /* T >= 1                                                        */
+  int64_t  total_steps;     /* S >= 1; hdet_fanout_step fails with HDET_ESTATE beyond it     */
+  int64_t  warm_steps;      /* S_warm: the controller runs at sync steps with t >= S_warm    */
+  double   lr_max;          /* one-cycle peak eta_max                                        */
+  double   f_div;           /* initial rate = eta_max / f_div                                */
+  double   f_final;         /* final rate   = eta_max / (f_div * f_final)                    */
+  double   pct_start;       /* p: fraction of S spent rising                                 */
+  int32_t  constant_lr;     /* nonzero: base schedule is eta_max at every step               */
+  int32_t  autolr_enabled;  /* nonzero: run the controller of Sec. 3.4                       */
+  double   alpha;           /* spread ratio of the learning rate (Eq. 1)                     */
+  double   beta;            /* velocity momentum (Eq. 7)                                     */
+  double   sigma;           /* softmax temperature (Eq. 4)                                   */
+  double   lambda;          /* step of Eq. 7 for the learning rate                           */
+  double   gamma_override;  /* >= 0 replaces the decay of Eq. 8; < 0 computes it             */
+  int32_t  optimizer;       /* HDET_SGDM or HDET_ADAMW                                       */
+  int32_t  grad_mode;       /* HDET_GRAD_SHARED: every replica applies the replica mean of
+                               the gradients (the paper's gradient AllReduce);
+                               HDET_GRAD_PER_REPLICA: replica r applies its own gradient    */
+  double   momentum;        /* SGDM                                                          */
+  double   beta1, beta2, eps;      /* AdamW                                                  */
+  double   weight_decay;    /* used by all replicas unless a HDET_CH_WD channel exists       */
+  int32_t  precision;       /* HDET_FP32 or HDET_BF16_GEMM_FP32_MASTER                       */
+  int32_t  model_kind;      /* HDET_FLAT or HDET_MLP                                         */
+  hdet_model_dims dims;
+  int32_t  n_extra_channels;           /* 0..HDET_MAX_CH-1                                   */
+  int32_t  reserved;
+  hdet_channel extra[HDET_MAX_CH - 1];
+  uint64_t seed;            /* keys the permutations of Eq. 9                                */
+  void*    stream;          /* hipStream_t, borrowed; NULL = the default stream              */
+} hdet_config;
+
+/* Caller-owned device buffers.  Planes are `plane_stride` elements apart; plane_stride >= P
+ * and a multiple of 4, every pointer 16-byte aligned.  Parameter layout inside a plane for
+ * HDET_MLP: [W_1 (d_out x d_in, row-major), b_1, W_2, b_2, ...].                            */
+typedef struct {
+  float*    params_dev;       /* [N][plane_stride] fp32 master parameters, updated in place  */
+  float*    grads_dev;        /* [N][plane_stride] fp32; written by hdet_forward_backward;
+                                 may be NULL for HDET_FLAT (gradients are passed per step)   */
+  float*    opt_m_dev;        /* [N][plane_stride] AdamW first moment / SGD momentum buffer;
+                                 must be zero at t = 0                                       */
+  float*    opt_v_dev;        /* [N][plane_stride] AdamW second moment; NULL for HDET_SGDM   */
+  uint16_t* params_bf16_dev;  /* [N][plane_stride] bfloat16 copy of the parameters, kept in
+                                 step by the update and converge kernels; NULL unless
+                                 precision == HDET_BF16_GEMM_FP32_MASTER                     */
+  void*     workspace_dev;    /* activations and scratch for hdet_forward_backward           */
+  size_t    workspace_bytes;
+  int64_t   plane_stride;
+} hdet_buffers;
+
+/* Host-side snapshot of the schedule and controller state. */
+typedef struct {
+  int64_t t;                  /* updates done                                                */
+  int64_t k;                  /* controller updates done                                     */
+  int32_t controller_active;  /* the controller has taken the base rate over                 */
+  int32_t nonfinite;          /* controller calls skipped because a loss was not finite      */
+  int32_t n_replicas, n_channels;
+  double  gamma;              /* decay in use for the learning-rate channel                  */
+  double  base[HDET_MAX_CH];  /* centre value per channel; [0] is meaningful once active     */
+  double  vel[HDET_MAX_CH];   /* velocity v of Eq. 7                                         */
+  double  delta[HDET_MAX_CH]; /* last hypergradient (Eq. 6)                                  */
+  double  w[HDET_MAX_REPLICAS];        /* last softmax weights (Eq. 4)                       */
+  double  l_acc[HDET_MAX_REPLICAS];    /* loss accumulated since the last sync step          */
+  double  l_last[HDET_MAX_REPLICAS];   /* interval losses L_r seen by the last sync step     */
+  float   l_step[HDET_MAX_REPLICAS];   /* losses of the last hdet_forward_backward           */
+  float   lr[HDET_MAX_REPLICAS];       /* rates used by the last hdet_fanout_step            */
+  double  rho[HDET_MAX_CH][HDET_MAX_REPLICAS];   /* multipliers of Eq. 1 per channel         */
+  int32_t perm[HDET_MAX_CH][HDET_MAX_REPLICAS];  /* pi_j(r): replica r uses rho_j[perm]      */
+} hdet_state;
+
+/* Bytes the caller must provide: one plane set (N * plane_stride elements) of fp32 for each
+ * of params / grads / opt_m / opt_v, of bf16 for the shadow, and the workspace.  Any out
+ * pointer may be NULL.  Returns HDET_EINVAL for an invalid configuration.                   */
+int hdet_workspace_bytes(const hdet_config* cfg, int64_t plane_stride, size_t* plane_set_bytes,
+                         size_t* shadow_bytes, size_t* workspace_bytes);
+
+/* Validates the configuration, computes rho (Eq. 1) and gamma (Eq. 8), sets pi = identity,
+ * v = 0, L_acc = 0, t = k = 0 (Algorithm 1, initialisation) and allocates the control block.
+ * With HDET_BF16_GEMM_FP32_MASTER the bf16 copy of the parameters is (re)written from
+ * params_dev.  Errors: HDET_EINVAL (bad argument, misaligned pointer), HDET_EHIP.           */
+int hdet_create(const hdet_config* cfg, const hdet_buffers* buffers, hdet_handle** out);
+
+/* Forward, mean cross-entropy and backward of all N replicas on x_dev [N][B][d_in]
+ * (fp32; rounded to bf16 on load in bf16 precision) and labels y_dev [N][B] int32
+ * ("Forward + backward" of Algorithm 1; the loss is the one that Sec. 3.4 averages into
+ * L_r).  Writes grads_dev, the per-replica losses of this step and adds them to L_acc.
+ * If losses_host is not NULL the call waits for the stream and copies the N losses there.
+ * HDET_ESTATE for HDET_FLAT handles.                                                        */
+int hdet_forward_backward(hdet_handle* h, const void* x_dev, const int32_t* y_dev,
+                          float* losses_host);
+
+/* Update t <- t+1 of every replica (Eq. 2 generalised to SGD-momentum / AdamW) with
+ * eta_r = eta_bar * rho_{pi(r)} (Eq. 1, Eq. 9), eta_bar being the one-cycle value of
+ * schedule index t-1 until the controller has taken over and the controller's base
+ * afterwards.  grads_dev: [N][plane_stride] fp32 gradients, or NULL to use the buffer given
+ * at creation.  In shared mode the replica mean of the gradients is formed inside the same
+ * kernel.  With HDET_FUSE_CONVERGE and t mod T == 0 the replica mean of the updated
+ * parameters (Eq. 3) is written to all replicas by the same kernel, and the following
+ * hdet_converge is a no-op.  HDET_ESTATE once t == total_steps.                             */
+int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags);
+
+/* theta_r <- (1/N) sum_r' theta_r' for all r (Eq. 3), summed in the order r' = 0..N-1;
+ * optimizer state is left per replica.  May be called at any t (Algorithm 1 calls it when
+ * t mod T == 0; a caller whose S is not a multiple of T ends with one more call).           */
+int hdet_converge(hdet_handle* h);
+
+/* Sync-step bookkeeping (Algorithm 1, inside "t mod T = 0"): L_r = L_acc / T -- or the N
+ * host values given in interval_losses_host -- then L_acc <- 0; if the controller is
+ * enabled and t >= S_warm: weights (Eq. 4), hypergradient per channel (Eq. 5-6), velocity
+ * and base (Eq. 7-8), fresh permutations (Eq. 9).  Runs on the device in one wavefront.
+ * A non-finite loss leaves the controller state untouched and increments
+ * hdet_state.nonfinite.  HDET_ESTATE off a sync step or twice on the same one.              */
+int hdet_autolr_update(hdet_handle* h, const double* interval_losses_host);
+
+/* Waits for the stream and copies the state out / overwrites it (resume).                   */
+int hdet_get_state(hdet_handle* h, hdet_state* out);
+int hdet_set_state(hdet_handle* h, const hdet_state* in);
+
+/* Tuning knob for measurements: 0 = library default.  `replicas_per_thread` must divide N
+ * and is ignored by kernels that need all replicas in one thread (shared gradients, fused
+ * converge); `blocks` is the grid size of the streaming kernels.                            */
+int hdet_set_launch_shape(hdet_handle* h, int32_t replicas_per_thread, int32_t blocks);
+
+/* Message of the last failure on this handle (or of the last failed hdet_create if h is
+ * NULL); owned by the library.                                                              */
+const char* hdet_last_error(hdet_handle* h);
+
+/* Releases the control block and the handle.  hdet_destroy(NULL) is a no-op.                */
+int hdet_destroy(hdet_handle* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HDET_H */

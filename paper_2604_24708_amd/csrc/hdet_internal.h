@@ -1,0 +1,121 @@
+// Internal declarations shared by the translation units of libhdet.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "hdet.h"
+
+// ---------------------------------------------------------------------------------------
+// Device-resident schedule / controller state (one per handle).  Kernels read the rates
+// from here, so no step needs a host round trip: the host only knows t.
+// ---------------------------------------------------------------------------------------
+struct hdet_ctrl {
+  double base[HDET_MAX_CH];                       // h_bar_j (Eq. 7); [0] valid once active
+  double vel[HDET_MAX_CH];                        // v_j
+  double delta[HDET_MAX_CH];                      // last Delta_j (Eq. 6)
+  double rho[HDET_MAX_CH][HDET_MAX_REPLICAS];     // Eq. 1 per channel
+  double w[HDET_MAX_REPLICAS];                    // last softmax weights (Eq. 4)
+  double l_acc[HDET_MAX_REPLICAS];                // running loss sum of the interval
+  double l_last[HDET_MAX_REPLICAS];               // L_r of the last sync step
+  float l_step[HDET_MAX_REPLICAS];                // losses of the last forward
+  float lr_used[HDET_MAX_REPLICAS];               // rates of the last update
+  int32_t perm[HDET_MAX_CH][HDET_MAX_REPLICAS];   // pi_j
+  long long k;                                    // controller updates done
+  int32_t controller_active;
+  int32_t nonfinite;
+};
+
+// h_{j,r} = h_bar_j * rho_{j, pi_j(r)} in fp64.  Channel 0 (learning rate) follows the host's
+// one-cycle value `eta_sched` until the controller has taken over.
+__device__ __forceinline__ double hdet_channel_value(const hdet_ctrl* c, int j, int r,
+                                                     double eta_sched) {
+  const double b = (j == 0 && !c->controller_active) ? eta_sched : c->base[j];
+  return b * c->rho[j][c->perm[j][r]];
+}
+
+// ---------------------------------------------------------------------------------------
+// Kernel launch parameters
+// ---------------------------------------------------------------------------------------
+struct hdet_update_args {
+  float* theta;
+  const float* grad;
+  float* m;
+  float* v;
+  uint16_t* shadow;        // bf16 copy of theta or nullptr
+  const hdet_ctrl* ctrl;
+  hdet_ctrl* ctrl_out;     // same block, for lr_used
+  int64_t n_params;        // P
+  int64_t stride;          // plane stride in elements
+  int32_t n_replicas;
+  int32_t rg;              // replicas handled per thread (divides N)
+  int32_t wd_channel;      // channel index of a weight-decay channel or -1
+  int32_t first_step;      // SGDM: buf <- g'
+  double eta_sched;        // one-cycle value of this step
+  double wd_const;
+  double inv_bc1;          // 1 / (1 - beta1^t)
+  float inv_sqrt_bc2;      // 1 / sqrt(1 - beta2^t)
+  float beta1, beta2, one_m_beta1, one_m_beta2, eps, momentum;
+};
+
+struct hdet_converge_args {
+  float* theta;
+  uint16_t* shadow;
+  int64_t n_params;
+  int64_t stride;
+  int32_t n_replicas;
+};
+
+struct hdet_controller_args {
+  hdet_ctrl* ctrl;
+  double injected[HDET_MAX_REPLICAS];  // interval losses given by the caller
+  int32_t use_injected;
+  int32_t run_controller;              // enabled and t >= S_warm
+  int32_t n_replicas, n_channels;
+  int32_t sync_interval;
+  double eta_sched;                    // one-cycle value of the sync step (hand-over)
+  double sigma, beta, gamma;
+  double lambda[HDET_MAX_CH], lo[HDET_MAX_CH], hi[HDET_MAX_CH];
+  uint32_t seed_lo, seed_hi;
+};
+
+hipError_t hdet_launch_update(const hdet_update_args& a, int optimizer, bool shared, bool fuse_converge,
+                              int blocks, hipStream_t stream);
+hipError_t hdet_launch_converge(const hdet_converge_args& a, int blocks, hipStream_t stream);
+hipError_t hdet_launch_shadow(const float* theta, uint16_t* shadow, int64_t n_params, int64_t stride,
+                              int n_replicas, int blocks, hipStream_t stream);
+hipError_t hdet_launch_controller(const hdet_controller_args& a, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// MLP forward/backward (hdet_mlp.hip)
+// ---------------------------------------------------------------------------------------
+struct hdet_mlp_plan;
+int hdet_mlp_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err);
+hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, std::string* err);
+void hdet_mlp_destroy(hdet_mlp_plan* p);
+hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
+                                     hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// Host handle
+// ---------------------------------------------------------------------------------------
+struct hdet_handle {
+  hdet_config cfg;
+  hdet_buffers buf;
+  hipStream_t stream;
+  hdet_ctrl* ctrl_dev;
+  int device;
+  int64_t t;
+  int64_t last_autolr_t;     // sync step already processed by hdet_autolr_update
+  int64_t converged_at_t;    // t whose parameters are already averaged
+  double gamma;
+  int n_channels;
+  hdet_channel channels[HDET_MAX_CH];   // [0] = learning rate
+  int wd_channel;
+  int32_t tune_rg, tune_blocks;
+  int n_cu;
+  hdet_mlp_plan* mlp;
+  std::string err;
+};

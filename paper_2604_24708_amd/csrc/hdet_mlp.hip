@@ -1,0 +1,268 @@
+// "Forward + backward" of Algorithm 1 for an MLP, replica-batched: N independent weight sets,
+// one launch per layer and direction with the replica on blockIdx.z.
+//
+// Model: Linear+bias layers, ReLU between layers, none after the last, mean cross-entropy
+// over the B rows of a replica.  Parameters of a replica are one flat plane
+// [W_1 (d_out x d_in, row-major), b_1, W_2, b_2, ...]; gradients use the same layout, so the
+// update kernel can stream both without any gather.
+//
+// This file holds the fp32 path: an LDS-tiled SGEMM with fused bias/ReLU (forward),
+// ReLU-mask (dgrad) epilogues, a column-sum for the bias gradients, and a wavefront-per-row
+// softmax cross-entropy whose per-replica mean is reduced in a fixed order.
+
+#include <vector>
+
+#include "hdet_internal.h"
+
+namespace {
+
+constexpr int BM = 64, BN = 64, BK = 16;
+
+struct gemm_args {
+  const float* a; const float* b; float* c;
+  int m, n, k;
+  int64_t a_rs, a_cs, a_bs;     // A(m,k) = a[z*a_bs + m*a_rs + k*a_cs]
+  int64_t b_rs, b_cs, b_bs;     // B(k,n) = b[z*b_bs + k*b_rs + n*b_cs]
+  int64_t c_rs, c_bs;           // C(m,n) = c[z*c_bs + m*c_rs + n]
+  const float* bias; int64_t bias_bs;   // + bias[z*bias_bs + n]            (EPI_BIAS*)
+  const float* mask; int64_t mask_rs, mask_bs;  // * (mask(m,n) > 0)       (EPI_MASK)
+};
+
+enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_RELU = 2, EPI_MASK = 3 };
+
+// C = A * B with fp32 accumulation; 64x64 tile per 256-thread block, 4x4 per thread.
+template <int EPI>
+__global__ __launch_bounds__(256) void sgemm_kernel(const gemm_args g) {
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const int z = blockIdx.z;
+  const float* A = g.a + (int64_t)z * g.a_bs;
+  const float* B = g.b + (int64_t)z * g.b_bs;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  const bool a_kfast = g.a_cs == 1;      // consecutive threads walk the contiguous axis
+  const bool b_nfast = g.b_cs == 1;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < g.k; k0 += BK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + i * 256;
+      const int mm = a_kfast ? e / BK : e % BM;
+      const int kk = a_kfast ? e % BK : e / BM;
+      const int gm = m0 + mm, gk = k0 + kk;
+      As[kk][mm] = (gm < g.m && gk < g.k) ? A[(int64_t)gm * g.a_rs + (int64_t)gk * g.a_cs] : 0.f;
+      const int nn = b_nfast ? e % BN : e / BK;
+      const int kb = b_nfast ? e / BN : e % BK;
+      const int gn = n0 + nn, gkb = k0 + kb;
+      Bs[kb][nn] = (gn < g.n && gkb < g.k) ? B[(int64_t)gkb * g.b_rs + (int64_t)gn * g.b_cs] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { av[i] = As[kk][ty * 4 + i]; bv[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  float* C = g.c + (int64_t)z * g.c_bs;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int gm = m0 + ty * 4 + i;
+    if (gm >= g.m) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int gn = n0 + tx * 4 + j;
+      if (gn >= g.n) continue;
+      float v = acc[i][j];
+      if (EPI == EPI_BIAS || EPI == EPI_BIAS_RELU) v += g.bias[(int64_t)z * g.bias_bs + gn];
+      if (EPI == EPI_BIAS_RELU) v = v > 0.f ? v : 0.f;
+      if (EPI == EPI_MASK) v = g.mask[(int64_t)z * g.mask_bs + (int64_t)gm * g.mask_rs + gn] > 0.f ? v : 0.f;
+      C[(int64_t)gm * g.c_rs + gn] = v;
+    }
+  }
+}
+
+void launch_sgemm(const gemm_args& g, int epi, int batch, hipStream_t s) {
+  dim3 grid((g.n + BN - 1) / BN, (g.m + BM - 1) / BM, batch);
+  switch (epi) {
+    case EPI_BIAS: hipLaunchKernelGGL(sgemm_kernel<EPI_BIAS>, grid, dim3(256), 0, s, g); break;
+    case EPI_BIAS_RELU: hipLaunchKernelGGL(sgemm_kernel<EPI_BIAS_RELU>, grid, dim3(256), 0, s, g); break;
+    case EPI_MASK: hipLaunchKernelGGL(sgemm_kernel<EPI_MASK>, grid, dim3(256), 0, s, g); break;
+    default: hipLaunchKernelGGL(sgemm_kernel<EPI_NONE>, grid, dim3(256), 0, s, g); break;
+  }
+}
+
+// db[z][o] = sum_b dZ[z][b][o], rows added in ascending order by one thread per column.
+__global__ __launch_bounds__(256) void bias_grad_kernel(const float* dz, int rows, int cols, int64_t dz_bs,
+                                                        float* db, int64_t db_bs) {
+  const int o = blockIdx.x * 256 + threadIdx.x;
+  if (o >= cols) return;
+  const float* p = dz + (int64_t)blockIdx.y * dz_bs + o;
+  float s = 0.f;
+  for (int b = 0; b < rows; ++b) s += p[(int64_t)b * cols];
+  db[(int64_t)blockIdx.y * db_bs + o] = s;
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+// One wavefront per row: loss_b = log(sum exp(z - max)) - (z_y - max);
+// dlogits = (softmax - onehot) / B.  4 rows per 256-thread block.
+__global__ __launch_bounds__(256) void xent_kernel(const float* logits, const int32_t* labels, int rows,
+                                                   int classes, float* dlogits, float* row_loss) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int64_t gr = (int64_t)blockIdx.y * rows + row;
+  const float* z = logits + gr * classes;
+  float mx = -INFINITY;
+  for (int c = lane; c < classes; c += 64) mx = fmaxf(mx, z[c]);
+  mx = wave_max(mx);
+  float se = 0.f;
+  for (int c = lane; c < classes; c += 64) se += expf(z[c] - mx);
+  se = wave_sum(se);
+  const int y = labels[gr];
+  const float inv = 1.f / se, invb = 1.f / (float)rows;
+  float* d = dlogits + gr * classes;
+  for (int c = lane; c < classes; c += 64) d[c] = (expf(z[c] - mx) * inv - (c == y ? 1.f : 0.f)) * invb;
+  if (lane == 0) row_loss[gr] = logf(se) - (z[y] - mx);
+}
+
+// Per-replica mean of the row losses in a fixed tree order (one block per replica), the
+// step loss l(theta_r, B_r) of Algorithm 1, and its accumulation into L_acc (Sec. 3.4).
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float* row_loss, int rows, hdet_ctrl* ctrl) {
+  __shared__ double part[4];
+  const int r = blockIdx.x;
+  double s = 0.0;
+  for (int b = threadIdx.x; b < rows; b += 256) s += (double)row_loss[(int64_t)r * rows + b];
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const double mean = (part[0] + part[1] + part[2] + part[3]) / (double)rows;
+    ctrl->l_step[r] = (float)mean;
+    ctrl->l_acc[r] += mean;
+  }
+}
+
+}  // namespace
+
+struct hdet_mlp_plan {
+  hdet_config cfg;
+  hdet_buffers buf;
+  int n_layers;
+  std::vector<int64_t> w_off, b_off;     // offsets inside a parameter plane
+  std::vector<float*> act;               // act[i]: input of layer i (act[0] is the caller's x)
+  float* logits;
+  float* dz_a; float* dz_b;              // ping-pong activation gradients
+  float* row_loss;
+};
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int hdet_mlp_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err) {
+  if (cfg.precision != HDET_FP32) { *err = "HDET_MLP is built for HDET_FP32 only"; return HDET_EINVAL; }
+  const size_t n = cfg.n_replicas, b = cfg.dims.batch;
+  const int L = cfg.dims.n_layers;
+  size_t total = 0, maxw = 0;
+  for (int i = 1; i <= L; ++i) {
+    total += align_up(n * b * (size_t)cfg.dims.widths[i] * sizeof(float));   // act[1..L-1], logits
+    if ((size_t)cfg.dims.widths[i] > maxw) maxw = cfg.dims.widths[i];
+  }
+  for (int i = 0; i < L; ++i) if ((size_t)cfg.dims.widths[i] > maxw) maxw = cfg.dims.widths[i];
+  total += 2 * align_up(n * b * maxw * sizeof(float));                        // dz ping-pong
+  total += align_up(n * b * sizeof(float));                                   // row losses
+  *bytes = total;
+  return HDET_OK;
+}
+
+hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, std::string* err) {
+  size_t need = 0;
+  if (hdet_mlp_workspace_bytes(cfg, &need, err) != HDET_OK) return nullptr;
+  if (!buf.workspace_dev || buf.workspace_bytes < need) { *err = "workspace_dev is too small"; return nullptr; }
+  hdet_mlp_plan* p = new hdet_mlp_plan();
+  p->cfg = cfg; p->buf = buf; p->n_layers = cfg.dims.n_layers;
+  const size_t n = cfg.n_replicas, b = cfg.dims.batch;
+  const int L = p->n_layers;
+  int64_t off = 0;
+  for (int i = 0; i < L; ++i) {
+    p->w_off.push_back(off); off += (int64_t)cfg.dims.widths[i + 1] * cfg.dims.widths[i];
+    p->b_off.push_back(off); off += cfg.dims.widths[i + 1];
+  }
+  char* ws = (char*)buf.workspace_dev;
+  size_t maxw = 0;
+  for (int i = 0; i <= L; ++i) if ((size_t)cfg.dims.widths[i] > maxw) maxw = cfg.dims.widths[i];
+  p->act.assign(L, nullptr);
+  for (int i = 1; i <= L; ++i) {
+    float* ptr = (float*)ws; ws += align_up(n * b * (size_t)cfg.dims.widths[i] * sizeof(float));
+    if (i < L) p->act[i] = ptr; else p->logits = ptr;
+  }
+  p->dz_a = (float*)ws; ws += align_up(n * b * maxw * sizeof(float));
+  p->dz_b = (float*)ws; ws += align_up(n * b * maxw * sizeof(float));
+  p->row_loss = (float*)ws;
+  return p;
+}
+
+void hdet_mlp_destroy(hdet_mlp_plan* p) { delete p; }
+
+hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
+                                     hipStream_t s) {
+  const hdet_config& c = p->cfg;
+  const int N = c.n_replicas, B = c.dims.batch, L = p->n_layers;
+  const int* w = c.dims.widths;
+  const int64_t ps = p->buf.plane_stride;
+  const float* theta = p->buf.params_dev;
+  float* grads = p->buf.grads_dev;
+  p->act[0] = const_cast<float*>(static_cast<const float*>(x));
+
+  // forward: Y = act(X W^T + b)
+  for (int i = 0; i < L; ++i) {
+    gemm_args g = {};
+    g.a = p->act[i]; g.a_rs = w[i]; g.a_cs = 1; g.a_bs = (int64_t)B * w[i];
+    g.b = theta + p->w_off[i]; g.b_rs = 1; g.b_cs = w[i]; g.b_bs = ps;      // B(k,n) = W[n][k]
+    g.c = i + 1 < L ? p->act[i + 1] : p->logits; g.c_rs = w[i + 1]; g.c_bs = (int64_t)B * w[i + 1];
+    g.m = B; g.n = w[i + 1]; g.k = w[i];
+    g.bias = theta + p->b_off[i]; g.bias_bs = ps;
+    launch_sgemm(g, i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, N, s);
+  }
+  // loss and dlogits
+  float* dz = p->dz_a; float* dz_next = p->dz_b;
+  hipLaunchKernelGGL(xent_kernel, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss);
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
+  // backward
+  for (int i = L - 1; i >= 0; --i) {
+    // dW = dZ^T X
+    gemm_args g = {};
+    g.a = dz; g.a_rs = 1; g.a_cs = w[i + 1]; g.a_bs = (int64_t)B * w[i + 1];     // A(o,b) = dZ[b][o]
+    g.b = p->act[i]; g.b_rs = w[i]; g.b_cs = 1; g.b_bs = (int64_t)B * w[i];      // B(b,k) = X[b][k]
+    g.c = grads + p->w_off[i]; g.c_rs = w[i]; g.c_bs = ps;
+    g.m = w[i + 1]; g.n = w[i]; g.k = B;
+    launch_sgemm(g, EPI_NONE, N, s);
+    hipLaunchKernelGGL(bias_grad_kernel, dim3((w[i + 1] + 255) / 256, N), dim3(256), 0, s, dz, B, w[i + 1],
+                       (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
+    if (i > 0) {
+      // dX = dZ W, masked by the ReLU of the layer below
+      gemm_args d = {};
+      d.a = dz; d.a_rs = w[i + 1]; d.a_cs = 1; d.a_bs = (int64_t)B * w[i + 1];
+      d.b = theta + p->w_off[i]; d.b_rs = w[i]; d.b_cs = 1; d.b_bs = ps;         // B(o,k) = W[o][k]
+      d.c = dz_next; d.c_rs = w[i]; d.c_bs = (int64_t)B * w[i];
+      d.m = B; d.n = w[i]; d.k = w[i + 1];
+      d.mask = p->act[i]; d.mask_rs = w[i]; d.mask_bs = (int64_t)B * w[i];
+      launch_sgemm(d, EPI_MASK, N, s);
+      float* t = dz; dz = dz_next; dz_next = t;
+    }
+  }
+  return hipGetLastError();
+}

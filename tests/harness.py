@@ -1,0 +1,70 @@
+"""Drives the HIP library (through the C ABI binding) and the CPU oracle from one
+description of a run, so that the parity tests feed both the same seeded inputs."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import hdet_oracle as O
+
+
+def rel_err(a: np.ndarray, b: np.ndarray) -> float:
+    """max_i |a_i - b_i| / max(|b_i|, 1e-3 * rms(b)): a relative error with a floor, since a
+    pure ratio is meaningless for parameters that cross zero."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    if a.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(b * b)))
+    floor = max(1e-3 * rms, 1e-30)
+    return float(np.max(np.abs(a - b) / np.maximum(np.abs(b), floor)))
+
+
+def ulp_diff_f32(a, b) -> int:
+    a = np.asarray(a, dtype=np.float32).view(np.int32).astype(np.int64)
+    b = np.asarray(b, dtype=np.float32).view(np.int32).astype(np.int64)
+    return int(np.max(np.abs(a - b))) if a.size else 0
+
+
+def oracle_config(d: dict) -> O.Config:
+    extra = [O.Channel(*ch) for ch in d.get("extra", [])]
+    keys = ["n_replicas", "total_steps", "sync_interval", "warm_steps", "lr_max", "f_div", "f_final",
+            "pct_start", "alpha", "autolr_enabled", "beta", "sigma", "optimizer", "momentum", "beta1",
+            "beta2", "eps", "weight_decay", "grad_mode", "seed", "gamma_override", "constant_lr"]
+    kw = {k: d[k] for k in keys if k in d}
+    if "lambda_" in d:
+        kw["lam"] = d["lambda_"]
+    kw["autolr_enabled"] = bool(d.get("autolr_enabled", False))
+    kw["constant_lr"] = bool(d.get("constant_lr", False))
+    return O.Config(extra=extra, **kw)
+
+
+def library_config(d: dict, **model):
+    import paper_2604_24708_amd as H
+    kw = {k: v for k, v in d.items() if k != "extra"}
+    kw["autolr_enabled"] = int(bool(d.get("autolr_enabled", False)))
+    kw["constant_lr"] = int(bool(d.get("constant_lr", False)))
+    kw.update(model)
+    if d.get("extra"):
+        kw["extra"] = d["extra"]
+    return H.make_config(**kw)
+
+
+def check_state(st, orc: O.HDETOracle, scalar_rtol=1e-12, lr_ulps=1):
+    """Integer state bit-exact; fp64 controller scalars to a few ulp (the device's exp and
+    the host libm's differ in the last place); fp32 rates to `lr_ulps`."""
+    n = orc.cfg.n_replicas
+    assert st.t == orc.t and st.k == orc.k
+    assert bool(st.controller_active) == orc.controller_active
+    assert st.nonfinite == orc.nonfinite
+    assert st.n_channels == orc.n_ch
+    for j in range(orc.n_ch):
+        assert [st.perm[j][r] for r in range(n)] == orc.perm[j].tolist(), f"perm[{j}]"
+        assert np.allclose([st.rho[j][r] for r in range(n)], orc.rho[j], rtol=1e-15, atol=0)
+        if j > 0 or orc.controller_active:
+            assert np.isclose(st.base[j], orc.base[j], rtol=scalar_rtol, atol=1e-300), f"base[{j}]"
+        assert np.isclose(st.vel[j], orc.vel[j], rtol=scalar_rtol, atol=1e-24), f"vel[{j}]"
+        assert np.isclose(st.delta[j], orc.delta[j], rtol=scalar_rtol, atol=1e-24), f"delta[{j}]"
+    assert np.allclose([st.w[r] for r in range(n)], orc.w, rtol=scalar_rtol, atol=0)
+    assert np.isclose(st.gamma, orc.gamma, rtol=1e-14)
+    if orc.t > 0:
+        assert ulp_diff_f32([st.lr[r] for r in range(n)], orc.lr_used) <= lr_ulps

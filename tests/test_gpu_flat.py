@@ -1,0 +1,242 @@
+"""Parity of the HIP path with the CPU oracle on flat parameter buffers: fan-out update
+(SGD-momentum / AdamW, shared and per-replica gradients), converge (standalone and fused
+into the update) and the auto-LR controller, element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import hdet_inputs as I
+import paper_2604_24708_amd as H
+from harness import check_state, library_config, oracle_config, rel_err
+from oracle import hdet_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+TOL_STEP = 1e-5      # max relative error per step on fp32 parameter paths
+TOL_100 = 1e-4       # after 100 steps
+
+
+def base_cfg(**kw):
+    d = dict(n_replicas=4, total_steps=24, sync_interval=4, warm_steps=8, lr_max=0.05, alpha=0.2,
+             autolr_enabled=True, optimizer=O.ADAMW, weight_decay=0.01, grad_mode=O.GRAD_PER_REPLICA,
+             seed=7)
+    d.update(kw)
+    return d
+
+
+class FlatRun:
+    """Same run on both sides; `stride` > P leaves padding that must stay untouched."""
+
+    def __init__(self, d, P, stride=None, rg=0, blocks=0, grad_std=0.1):
+        self.d, self.P = d, P
+        self.n = d["n_replicas"]
+        self.stride = stride or ((P + 3) // 4) * 4
+        self.grad_std = grad_std
+        dev = "cuda:0"
+        th0 = I.flat_theta0(self.n, P, 5)
+        self.orc = O.HDETOracle(oracle_config(d), th0)
+        self.pad = np.float32(123.25)
+        host = np.full((self.n, self.stride), self.pad, dtype=np.float32)
+        host[:, :P] = th0
+        self.theta = torch.from_numpy(host).to(dev)
+        self.m = torch.zeros((self.n, self.stride), device=dev)
+        self.v = torch.zeros((self.n, self.stride), device=dev)
+        self.g = torch.zeros((self.n, self.stride), device=dev)
+        cfg = library_config(d, n_params=P, model_kind=H.HDET_FLAT)
+        self.h = H.hdet_create(cfg, self.theta, self.m, self.v if d["optimizer"] == O.ADAMW else None,
+                               plane_stride=self.stride)
+        if rg or blocks:
+            H.hdet_set_launch_shape(self.h, rg, blocks)
+
+    def step(self, t, fuse):
+        n, P = self.n, self.P
+        g = I.flat_grads(n, P, 99, t, std=self.grad_std)
+        losses = I.flat_losses(n, t)
+        self.g[:, :P] = torch.from_numpy(g).to(self.g.device)
+        H.hdet_fanout_step(self.h, self.g, H.HDET_FUSE_CONVERGE if fuse else 0)
+        self.orc.fanout_step(g, losses)
+        if t % self.d["sync_interval"] == 0:
+            H.hdet_converge(self.h)
+            self.orc.converge()
+            lr_interval = self.orc.l_acc / self.d["sync_interval"]
+            H.hdet_autolr_update(self.h, lr_interval.tolist())
+            self.orc.autolr_update()
+
+    def compare(self, tol):
+        P = self.P
+        th = self.theta.cpu().numpy()
+        assert rel_err(th[:, :P], self.orc.theta) <= tol
+        assert rel_err(self.m.cpu().numpy()[:, :P], self.orc.m) <= tol
+        if self.d["optimizer"] == O.ADAMW:
+            assert rel_err(self.v.cpu().numpy()[:, :P], self.orc.v) <= tol
+        assert np.all(th[:, P:] == self.pad)
+        check_state(H.hdet_get_state(self.h), self.orc)
+
+    def close(self):
+        H.hdet_destroy(self.h)
+
+
+@pytest.mark.parametrize("opt", [O.SGDM, O.ADAMW])
+@pytest.mark.parametrize("mode", [O.GRAD_SHARED, O.GRAD_PER_REPLICA])
+@pytest.mark.parametrize("n,P", [(1, 5), (2, 1), (3, 1023), (4, 4), (4, 70001), (8, 3), (8, 262147), (5, 4099)])
+def test_update_converge_controller_parity(opt, mode, n, P):
+    d = base_cfg(n_replicas=n, optimizer=opt, grad_mode=mode)
+    run = FlatRun(d, P)
+    for t in range(1, 17):
+        run.step(t, fuse=(t % 8 == 0))          # alternate fused and standalone converge
+        run.compare(TOL_STEP * 4 if t > 1 else TOL_STEP)
+    st = H.hdet_get_state(run.h)
+    assert st.k == 3 and st.controller_active == 1
+    run.close()
+
+
+@pytest.mark.parametrize("rg", [1, 2, 4, 8])
+def test_replicas_per_thread_shapes_agree(rg):
+    d = base_cfg(n_replicas=8)
+    run = FlatRun(d, 50003, stride=50176, rg=rg, blocks=7)
+    for t in range(1, 6):
+        run.step(t, fuse=True)
+        run.compare(TOL_STEP * 2)
+    run.close()
+
+
+def test_single_step_error_is_within_1e5():
+    """One update from identical state: the per-step bound itself."""
+    for opt in (O.SGDM, O.ADAMW):
+        d = base_cfg(n_replicas=8, optimizer=opt, total_steps=200)
+        run = FlatRun(d, 100001)
+        for t in range(1, 4):
+            # restart both sides from the oracle's state so that only one step's error shows
+            run.theta[:, :run.P] = torch.from_numpy(run.orc.theta).to(run.theta.device)
+            run.m[:, :run.P] = torch.from_numpy(run.orc.m).to(run.theta.device)
+            run.v[:, :run.P] = torch.from_numpy(run.orc.v).to(run.theta.device)
+            run.step(t, fuse=False)
+            run.compare(TOL_STEP)
+        run.close()
+
+
+def test_hundred_steps_within_1e4():
+    d = base_cfg(n_replicas=4, total_steps=100, sync_interval=5, warm_steps=30, lr_max=3e-3, alpha=0.1)
+    run = FlatRun(d, 20011, grad_std=1e-3)
+    for t in range(1, 101):
+        run.step(t, fuse=(t % 2 == 0))
+        if t % 10 == 0:
+            run.compare(TOL_100)
+    th = run.theta.cpu().numpy()
+    assert all(np.array_equal(th[0, :run.P], th[r, :run.P]) for r in range(4))   # t = 100 is a sync step
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_fanout_step(run.h, run.g, 0)                                      # beyond S
+    assert e.value.code == H.HDET_ESTATE
+    run.close()
+
+
+def test_weight_decay_channel_and_three_permutations():
+    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
+    d = base_cfg(n_replicas=8, extra=extra, lr_max=3e-3, alpha=0.15)
+    run = FlatRun(d, 4099)
+    for t in range(1, 21):
+        run.step(t, fuse=False)
+        run.compare(TOL_STEP * 4)
+    st = H.hdet_get_state(run.h)
+    perms = {tuple(st.perm[j][r] for r in range(8)) for j in range(3)}
+    assert len(perms) == 3
+    run.close()
+
+
+def test_invariants_on_device():
+    """alpha = 0 with identical gradients: replicas stay bit-identical and converge is a
+    bit-exact no-op; fused and standalone converge give identical planes."""
+    d = base_cfg(n_replicas=8, alpha=0.0, autolr_enabled=False)
+    P = 30001
+    run = FlatRun(d, P)
+    g = I.flat_grads(1, P, 99, 1, std=0.1)
+    run.g[:, :P] = torch.from_numpy(np.broadcast_to(g, (8, P)).copy()).to(run.g.device)
+    for t in range(1, 5):
+        H.hdet_fanout_step(run.h, run.g, 0)
+    before = run.theta.clone()
+    H.hdet_converge(run.h)
+    assert torch.equal(before, run.theta)
+    assert all(torch.equal(run.theta[0], run.theta[r]) for r in range(8))
+    run.close()
+
+
+def test_equal_losses_give_zero_delta():
+    d = base_cfg(n_replicas=8, warm_steps=0, gamma_override=0.0)
+    run = FlatRun(d, 64)
+    for t in range(1, 5):
+        H.hdet_fanout_step(run.h, run.g, 0)
+    H.hdet_converge(run.h)
+    H.hdet_autolr_update(run.h, [2.5] * 8)
+    st = H.hdet_get_state(run.h)
+    assert st.delta[0] == 0.0 and st.vel[0] == 0.0 and st.k == 1
+    assert st.base[0] == O.onecycle_lr(3, 24, 0.05, 25.0, 1e4, 0.3)     # untouched at gamma = 0
+    assert abs(sum(st.w[r] for r in range(8)) - 1.0) < 1e-15
+    run.close()
+
+
+def test_call_order_and_argument_errors():
+    d = base_cfg()
+    run = FlatRun(d, 64)
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_autolr_update(run.h, [1.0] * 4)        # t = 0: not a sync step
+    assert e.value.code == H.HDET_ESTATE
+    for t in range(1, 5):
+        H.hdet_fanout_step(run.h, run.g, 0)
+    H.hdet_autolr_update(run.h, [1.0] * 4)
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_autolr_update(run.h, [1.0] * 4)        # twice on one sync step
+    assert e.value.code == H.HDET_ESTATE
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_fanout_step(run.h, run.g.data_ptr() + 4, 0)      # misaligned gradients
+    assert e.value.code == H.HDET_EINVAL
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_forward_backward(run.h, run.g, run.g)            # flat handle
+    assert e.value.code == H.HDET_ESTATE
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_set_launch_shape(run.h, 3, 0)                    # 3 does not divide 4
+    assert e.value.code == H.HDET_EINVAL
+    assert "divide" in H.hdet_last_error(run.h)
+    run.close()
+    cfg = library_config(d, n_params=64, model_kind=H.HDET_FLAT)
+    with pytest.raises(H.HdetError):
+        H.hdet_create(cfg, run.theta, run.m, None, plane_stride=64)       # AdamW without v
+    with pytest.raises(H.HdetError):
+        H.hdet_create(cfg, run.theta.data_ptr() + 4, run.m, run.v, plane_stride=64)
+
+
+def test_nonfinite_loss_skips_the_controller():
+    d = base_cfg(warm_steps=0)
+    run = FlatRun(d, 64)
+    for t in range(1, 5):
+        H.hdet_fanout_step(run.h, run.g, 0)
+        run.orc.fanout_step(np.zeros((4, 64), np.float32), [0.0] * 4)
+    H.hdet_autolr_update(run.h, [1.0, float("nan"), 1.0, 1.0])
+    run.orc.autolr_update([1.0, float("nan"), 1.0, 1.0])
+    st = H.hdet_get_state(run.h)
+    assert st.nonfinite == 1 and st.k == 0 and st.controller_active == 0
+    check_state(st, run.orc)
+    run.close()
+
+
+def test_state_round_trip_resumes_bit_exactly():
+    d = base_cfg(n_replicas=4)
+    a = FlatRun(d, 1001)
+    for t in range(1, 13):
+        a.step(t, fuse=False)
+    st = H.hdet_get_state(a.h)
+    b = FlatRun(d, 1001)
+    b.theta.copy_(a.theta); b.m.copy_(a.m); b.v.copy_(a.v)
+    H.hdet_set_state(b.h, st)
+    for t in range(13, 21):
+        a.step(t, fuse=False)
+        g = I.flat_grads(4, 1001, 99, t, std=0.1)
+        b.g[:, :1001] = torch.from_numpy(g).to(b.g.device)
+        H.hdet_fanout_step(b.h, b.g, 0)
+        if t % 4 == 0:
+            H.hdet_converge(b.h)
+            H.hdet_autolr_update(b.h, [H.hdet_get_state(a.h).l_last[r] for r in range(4)])
+    assert torch.equal(a.theta, b.theta) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v)
+    sa, sb = H.hdet_get_state(a.h), H.hdet_get_state(b.h)
+    assert sa.k == sb.k and sa.base[0] == sb.base[0] and sa.vel[0] == sb.vel[0]
+    assert [sa.perm[0][r] for r in range(4)] == [sb.perm[0][r] for r in range(4)]
+    a.close(); b.close()
