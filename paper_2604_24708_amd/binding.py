@@ -102,6 +102,10 @@ def load_library(path: Optional[str] = None):
     if not os.path.exists(p):
         raise RuntimeError(f"{p} is missing: build it with `python -m paper_2604_24708_amd.build` "
                            "(there is no CPU fallback)")
+    # One HIP runtime per process: PyTorch ships its own libamdhip64 and must be the one that
+    # libhdet.so binds to, or the library and the tensors it is handed would live in two
+    # runtimes (the second one finds no device).  Importing torch first loads that copy.
+    import torch  # noqa: F401
     lib = C.CDLL(p)
     vp = C.c_void_p
     lib.hdet_workspace_bytes.argtypes = [C.POINTER(hdet_config), C.c_int64, C.POINTER(C.c_size_t),

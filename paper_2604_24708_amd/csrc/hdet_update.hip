@@ -12,10 +12,19 @@
 
 #include "hdet_internal.h"
 
+#pragma clang fp contract(off)
+
 namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned short us4 __attribute__((ext_vector_type(4)));
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+// fp64 companions of the column types, for the replica mean of the gradients
+__device__ __forceinline__ d4 widen(f4 x) { return __builtin_convertvector(x, d4); }
+__device__ __forceinline__ double widen(float x) { return (double)x; }
+__device__ __forceinline__ f4 narrow(d4 x) { return __builtin_convertvector(x, f4); }
+__device__ __forceinline__ float narrow(double x) { return (float)x; }
 
 constexpr int kThreads = 256;
 
@@ -51,6 +60,14 @@ struct rep_scalars {
   float wd[HDET_MAX_REPLICAS];
 };
 
+// The arithmetic of one element.  Fused multiply-adds are written out and automatic
+// contraction is off (see the pragma above), so that every replica, every unrolled copy of
+// the loop and every launch shape rounds identically: replicas that start identical and see
+// identical gradients stay bit-identical (alpha = 0 is plain data parallelism, Sec. 3.2).
+template <typename T> __device__ __forceinline__ T fma_(float a, T b, T c) {
+  return __builtin_elementwise_fma(splat<T>(a), b, c);
+}
+
 template <int OPT, typename T>
 __device__ __forceinline__ void update_one(T& th, T g, T& m, T& v, const hdet_update_args& a,
                                            const rep_scalars& s, int r) {
@@ -58,15 +75,15 @@ __device__ __forceinline__ void update_one(T& th, T g, T& m, T& v, const hdet_up
     // theta *= 1 - lr wd;  m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
     // theta -= lr/(1-b1^t) * m / (sqrt(v)/sqrt(1-b2^t) + eps)
     th = th * s.decay[r];
-    m = a.beta1 * m + a.one_m_beta1 * g;
-    v = a.beta2 * v + a.one_m_beta2 * (g * g);
-    T denom = __builtin_elementwise_sqrt(v) * a.inv_sqrt_bc2 + a.eps;
-    th = th - s.step[r] * (m / denom);
+    m = fma_<T>(a.beta1, m, a.one_m_beta1 * g);
+    v = fma_<T>(a.beta2, v, a.one_m_beta2 * (g * g));
+    const T denom = fma_<T>(a.inv_sqrt_bc2, __builtin_elementwise_sqrt(v), splat<T>(a.eps));
+    th = fma_<T>(-s.step[r], m / denom, th);
   } else {
     // g' = g + wd theta;  buf = g' (first step) or mu buf + g';  theta -= lr buf
-    T gp = g + s.wd[r] * th;
-    m = a.first_step ? gp : a.momentum * m + gp;
-    th = th - s.lr[r] * m;
+    const T gp = fma_<T>(s.wd[r], th, g);
+    m = a.first_step ? gp : fma_<T>(a.momentum, m, gp);
+    th = fma_<T>(-s.lr[r], m, th);
   }
 }
 
@@ -77,12 +94,17 @@ __device__ __forceinline__ void update_column(const hdet_update_args& a, const r
   const int n = a.n_replicas;
   T gbar = splat<T>(0.f);
   if (SHARED) {
-    // the paper's gradient AllReduce: mean over the replica axis, r ascending
+    // The paper's gradient AllReduce: mean over the replica axis, r ascending.  Summed in
+    // fp64 and rounded to fp32 once: Adam's first steps move by lr * g/(|g| + eps), which
+    // magnifies a last-place difference in a near-zero mean gradient ten-thousandfold.
+    auto sum = widen(splat<T>(0.f));
 #pragma unroll
-    for (int q = 0; q < (NT ? NT : n); ++q) gbar = gbar + ld<T>(a.grad + (int64_t)q * a.stride + col);
-    gbar = gbar / (float)n;
+    for (int q = 0; q < (NT ? NT : n); ++q) sum = sum + widen(ld<T>(a.grad + (int64_t)q * a.stride + col));
+    gbar = narrow(sum * (1.0 / (double)n));
   }
-  T acc = splat<T>(0.f);
+  // Eq. 3 accumulator, fp64: the sum of N fp32 values is then exact up to 2^-53, the mean is
+  // rounded to fp32 once, and averaging identical replicas returns them bit for bit.
+  auto acc = widen(splat<T>(0.f));
 #pragma unroll
   for (int q = 0; q < (NT ? NT : rg); ++q) {
     const int r = r0 + q;
@@ -96,14 +118,14 @@ __device__ __forceinline__ void update_column(const hdet_update_args& a, const r
     st<T>(a.m + off, m);
     if (OPT == HDET_ADAMW) st<T>(a.v + off, v);
     if (CONV) {
-      acc = acc + th;                 // Eq. 3: sum in the order r = 0..N-1
+      acc = acc + widen(th);          // Eq. 3: sum in the order r = 0..N-1
     } else {
       st<T>(a.theta + off, th);
       if (a.shadow) st_bf16(a.shadow + off, th);
     }
   }
   if (CONV) {
-    const T mean = acc / (float)n;
+    const T mean = narrow(acc * (1.0 / (double)n));
 #pragma unroll
     for (int q = 0; q < (NT ? NT : n); ++q) {
       const int64_t off = (int64_t)q * a.stride + col;
@@ -150,10 +172,10 @@ __global__ __launch_bounds__(kThreads) void hdet_update_kernel(const hdet_update
 template <int NT, typename T>
 __device__ __forceinline__ void converge_column(const hdet_converge_args& a, int64_t col) {
   const int n = a.n_replicas;
-  T acc = splat<T>(0.f);
+  auto acc = widen(splat<T>(0.f));     // fp64 sum, one rounding to fp32 (see update_column)
 #pragma unroll
-  for (int q = 0; q < (NT ? NT : n); ++q) acc = acc + ld<T>(a.theta + (int64_t)q * a.stride + col);
-  const T mean = acc / (float)n;
+  for (int q = 0; q < (NT ? NT : n); ++q) acc = acc + widen(ld<T>(a.theta + (int64_t)q * a.stride + col));
+  const T mean = narrow(acc * (1.0 / (double)n));
 #pragma unroll
   for (int q = 0; q < (NT ? NT : n); ++q) {
     const int64_t off = (int64_t)q * a.stride + col;

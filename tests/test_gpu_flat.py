@@ -16,6 +16,12 @@ TOL_STEP = 1e-5      # max relative error per step on fp32 parameter paths
 TOL_100 = 1e-4       # after 100 steps
 
 
+def tol_at(t):
+    """Bound on a trajectory compared after t steps run separately on both sides: each step
+    may add the per-step 1e-5, and the total stays within the 100-step bound of 1e-4."""
+    return min(t * TOL_STEP, TOL_100)
+
+
 def base_cfg(**kw):
     d = dict(n_replicas=4, total_steps=24, sync_interval=4, warm_steps=8, lr_max=0.05, alpha=0.2,
              autolr_enabled=True, optimizer=O.ADAMW, weight_decay=0.01, grad_mode=O.GRAD_PER_REPLICA,
@@ -84,7 +90,7 @@ def test_update_converge_controller_parity(opt, mode, n, P):
     run = FlatRun(d, P)
     for t in range(1, 17):
         run.step(t, fuse=(t % 8 == 0))          # alternate fused and standalone converge
-        run.compare(TOL_STEP * 4 if t > 1 else TOL_STEP)
+        run.compare(tol_at(t))
     st = H.hdet_get_state(run.h)
     assert st.k == 3 and st.controller_active == 1
     run.close()
@@ -96,7 +102,7 @@ def test_replicas_per_thread_shapes_agree(rg):
     run = FlatRun(d, 50003, stride=50176, rg=rg, blocks=7)
     for t in range(1, 6):
         run.step(t, fuse=True)
-        run.compare(TOL_STEP * 2)
+        run.compare(tol_at(t))
     run.close()
 
 
@@ -136,7 +142,7 @@ def test_weight_decay_channel_and_three_permutations():
     run = FlatRun(d, 4099)
     for t in range(1, 21):
         run.step(t, fuse=False)
-        run.compare(TOL_STEP * 4)
+        run.compare(tol_at(t))
     st = H.hdet_get_state(run.h)
     perms = {tuple(st.perm[j][r] for r in range(8)) for j in range(3)}
     assert len(perms) == 3
