@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--sync-interval", type=int, default=16)
     ap.add_argument("--grad-mode", choices=["per_replica", "shared"], default="per_replica")
     ap.add_argument("--unfused", action="store_true", help="standalone converge kernel on sync steps")
-    ap.add_argument("--replicas-per-thread", type=int, default=0)
+    ap.add_argument("--variant", type=int, default=0, help="update kernel selection (0 = default)")
     ap.add_argument("--blocks", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -100,8 +100,8 @@ def main():
                         grad_mode=H.HDET_GRAD_SHARED if args.grad_mode == "shared" else H.HDET_GRAD_PER_REPLICA,
                         model_kind=H.HDET_FLAT, n_params=P, seed=I.SEED_PERM, stream=stream.cuda_stream)
     h = H.hdet_create(cfg, theta, m, v, plane_stride=stride)
-    if args.replicas_per_thread or args.blocks:
-        H.hdet_set_launch_shape(h, args.replicas_per_thread, args.blocks)
+    if args.variant or args.blocks:
+        H.hdet_set_launch_shape(h, args.variant, args.blocks)
     losses = [1.0 + 0.01 * r for r in range(n)]
     flags = 0 if args.unfused else H.HDET_FUSE_CONVERGE
 

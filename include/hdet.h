@@ -189,10 +189,12 @@ int hdet_autolr_update(hdet_handle* h, const double* interval_losses_host);
 int hdet_get_state(hdet_handle* h, hdet_state* out);
 int hdet_set_state(hdet_handle* h, const hdet_state* in);
 
-/* Tuning knob for measurements: 0 = library default.  `replicas_per_thread` must divide N
- * and is ignored by kernels that need all replicas in one thread (shared gradients, fused
- * converge); `blocks` is the grid size of the streaming kernels.                            */
-int hdet_set_launch_shape(hdet_handle* h, int32_t replicas_per_thread, int32_t blocks);
+/* Kernel selection, for measurements and tests.  variant 0 (default): the fastest update
+ * kernel for the case (one thread per replica column, or -- when gradients or parameters
+ * must cross the replica axis and N <= 16 -- one wavefront per replica with an LDS
+ * exchange); variant 1: the general kernel in which one thread walks the replica axis (any
+ * N).  `blocks` > 0 sets the grid of the grid-stride kernels (0: library default).          */
+int hdet_set_launch_shape(hdet_handle* h, int32_t variant, int32_t blocks);
 
 /* Message of the last failure on this handle (or of the last failed hdet_create if h is
  * NULL); owned by the library.                                                              */

@@ -232,8 +232,8 @@ def hdet_set_state(h, st: hdet_state):
     _check(load_library().hdet_set_state(h, C.byref(st)), h)
 
 
-def hdet_set_launch_shape(h, replicas_per_thread: int = 0, blocks: int = 0):
-    _check(load_library().hdet_set_launch_shape(h, replicas_per_thread, blocks), h)
+def hdet_set_launch_shape(h, variant: int = 0, blocks: int = 0):
+    _check(load_library().hdet_set_launch_shape(h, variant, blocks), h)
 
 
 def hdet_last_error(h=None) -> str:

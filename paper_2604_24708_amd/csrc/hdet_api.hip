@@ -197,7 +197,7 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
   h->last_autolr_t = 0;
   h->converged_at_t = -1;
   h->gamma = decay_gamma(*cfg);
-  h->tune_rg = 0;
+  h->tune_variant = 0;
   h->tune_blocks = 0;
   h->mlp = nullptr;
   h->ctrl_dev = nullptr;
@@ -273,7 +273,6 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   a.n_params = param_count(c);
   a.stride = h->buf.plane_stride;
   a.n_replicas = c.n_replicas;
-  a.rg = h->tune_rg > 0 ? h->tune_rg : c.n_replicas;
   a.wd_channel = h->wd_channel;
   a.first_step = t == 1;
   a.eta_sched = onecycle(c, t - 1);        // update t uses schedule index t-1
@@ -290,7 +289,7 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   a.momentum = (float)c.momentum;
 
   const bool fuse = (flags & HDET_FUSE_CONVERGE) && (t % c.sync_interval == 0);
-  hipError_t e = hdet_launch_update(a, c.optimizer, c.grad_mode == HDET_GRAD_SHARED, fuse, default_blocks(h), h->stream);
+  hipError_t e = hdet_launch_update(a, c.optimizer, c.grad_mode == HDET_GRAD_SHARED, fuse, h->tune_variant, default_blocks(h), h->stream);
   if (e != hipSuccess) return hip_fail(h, e, "update kernel");
   h->t = t;
   if (fuse) h->converged_at_t = t;
@@ -306,7 +305,8 @@ int hdet_converge(hdet_handle* h) {
   a.n_params = param_count(h->cfg);
   a.stride = h->buf.plane_stride;
   a.n_replicas = h->cfg.n_replicas;
-  hipError_t e = hdet_launch_converge(a, default_blocks(h), h->stream);
+  a.tail_only = 0;
+  hipError_t e = hdet_launch_converge(a, h->tune_variant, default_blocks(h), h->stream);
   if (e != hipSuccess) return hip_fail(h, e, "converge kernel");
   h->converged_at_t = h->t;
   return HDET_OK;
@@ -407,11 +407,11 @@ int hdet_set_state(hdet_handle* h, const hdet_state* in) {
   return write_shadow(h);
 }
 
-int hdet_set_launch_shape(hdet_handle* h, int32_t replicas_per_thread, int32_t blocks) {
+int hdet_set_launch_shape(hdet_handle* h, int32_t variant, int32_t blocks) {
   if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
-  if (replicas_per_thread < 0 || blocks < 0) return fail(h, HDET_EINVAL, "negative launch shape");
-  if (replicas_per_thread > 0 && h->cfg.n_replicas % replicas_per_thread != 0) return fail(h, HDET_EINVAL, "replicas_per_thread must divide N");
-  h->tune_rg = replicas_per_thread;
+  if (variant < 0 || variant > 1) return fail(h, HDET_EINVAL, "variant must be 0 or 1");
+  if (blocks < 0) return fail(h, HDET_EINVAL, "negative block count");
+  h->tune_variant = variant;
   h->tune_blocks = blocks;
   return HDET_OK;
 }

@@ -50,7 +50,6 @@ struct hdet_update_args {
   int64_t n_params;        // P
   int64_t stride;          // plane stride in elements
   int32_t n_replicas;
-  int32_t rg;              // replicas handled per thread (divides N)
   int32_t wd_channel;      // channel index of a weight-decay channel or -1
   int32_t first_step;      // SGDM: buf <- g'
   double eta_sched;        // one-cycle value of this step
@@ -66,6 +65,7 @@ struct hdet_converge_args {
   int64_t n_params;
   int64_t stride;
   int32_t n_replicas;
+  int32_t tail_only;       // loop kernel: only the P mod 4 trailing parameters
 };
 
 struct hdet_controller_args {
@@ -81,9 +81,10 @@ struct hdet_controller_args {
   uint32_t seed_lo, seed_hi;
 };
 
+// variant 0: fastest kernel for the case; 1: the general loop kernel for everything
 hipError_t hdet_launch_update(const hdet_update_args& a, int optimizer, bool shared, bool fuse_converge,
-                              int blocks, hipStream_t stream);
-hipError_t hdet_launch_converge(const hdet_converge_args& a, int blocks, hipStream_t stream);
+                              int variant, int blocks, hipStream_t stream);
+hipError_t hdet_launch_converge(const hdet_converge_args& a, int variant, int blocks, hipStream_t stream);
 hipError_t hdet_launch_shadow(const float* theta, uint16_t* shadow, int64_t n_params, int64_t stride,
                               int n_replicas, int blocks, hipStream_t stream);
 hipError_t hdet_launch_controller(const hdet_controller_args& a, hipStream_t stream);
@@ -114,7 +115,7 @@ struct hdet_handle {
   int n_channels;
   hdet_channel channels[HDET_MAX_CH];   // [0] = learning rate
   int wd_channel;
-  int32_t tune_rg, tune_blocks;
+  int32_t tune_variant, tune_blocks;
   int n_cu;
   hdet_mlp_plan* mlp;
   std::string err;

@@ -33,7 +33,7 @@ def base_cfg(**kw):
 class FlatRun:
     """Same run on both sides; `stride` > P leaves padding that must stay untouched."""
 
-    def __init__(self, d, P, stride=None, rg=0, blocks=0, grad_std=0.1):
+    def __init__(self, d, P, stride=None, variant=0, blocks=0, grad_std=0.1):
         self.d, self.P = d, P
         self.n = d["n_replicas"]
         self.stride = stride or ((P + 3) // 4) * 4
@@ -51,8 +51,8 @@ class FlatRun:
         cfg = library_config(d, n_params=P, model_kind=H.HDET_FLAT)
         self.h = H.hdet_create(cfg, self.theta, self.m, self.v if d["optimizer"] == O.ADAMW else None,
                                plane_stride=self.stride)
-        if rg or blocks:
-            H.hdet_set_launch_shape(self.h, rg, blocks)
+        if variant or blocks:
+            H.hdet_set_launch_shape(self.h, variant, blocks)
 
     def step(self, t, fuse):
         n, P = self.n, self.P
@@ -96,14 +96,20 @@ def test_update_converge_controller_parity(opt, mode, n, P):
     run.close()
 
 
-@pytest.mark.parametrize("rg", [1, 2, 4, 8])
-def test_replicas_per_thread_shapes_agree(rg):
-    d = base_cfg(n_replicas=8)
-    run = FlatRun(d, 50003, stride=50176, rg=rg, blocks=7)
+@pytest.mark.parametrize("mode", [O.GRAD_SHARED, O.GRAD_PER_REPLICA])
+@pytest.mark.parametrize("n", [3, 8, 16, 17, 64])
+def test_kernel_variants_agree_bit_for_bit(n, mode):
+    """The general loop kernel (forced, small grid) and the default kernels (plane / wave for
+    N <= 16, loop beyond) must give identical bits, and both match the oracle."""
+    d = base_cfg(n_replicas=n, grad_mode=mode)
+    a = FlatRun(d, 50003, stride=50176, variant=1, blocks=7)
+    b = FlatRun(d, 50003, stride=50176)
     for t in range(1, 6):
-        run.step(t, fuse=True)
-        run.compare(tol_at(t))
-    run.close()
+        a.step(t, fuse=(t == 4))
+        b.step(t, fuse=(t == 4))
+        a.compare(tol_at(t))
+        assert torch.equal(a.theta, b.theta) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v)
+    a.close(); b.close()
 
 
 def test_single_step_error_is_within_1e5():
@@ -199,9 +205,9 @@ def test_call_order_and_argument_errors():
         H.hdet_forward_backward(run.h, run.g, run.g)            # flat handle
     assert e.value.code == H.HDET_ESTATE
     with pytest.raises(H.HdetError) as e:
-        H.hdet_set_launch_shape(run.h, 3, 0)                    # 3 does not divide 4
+        H.hdet_set_launch_shape(run.h, 3, 0)                    # no such kernel variant
     assert e.value.code == H.HDET_EINVAL
-    assert "divide" in H.hdet_last_error(run.h)
+    assert "variant" in H.hdet_last_error(run.h)
     run.close()
     cfg = library_config(d, n_params=64, model_kind=H.HDET_FLAT)
     with pytest.raises(H.HdetError):
