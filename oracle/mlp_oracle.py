@@ -59,8 +59,13 @@ def softmax_xent(logits: np.ndarray, labels: np.ndarray) -> Tuple[float, np.ndar
 
 
 def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Sequence[int],
-                      bf16: bool = False) -> Tuple[float, np.ndarray]:
-    """Loss and flat fp32 gradient for one replica.  x: [B, d_in], y: [B] int."""
+                      bf16: bool = False, info: dict = None) -> Tuple[float, np.ndarray]:
+    """Loss and flat fp32 gradient for one replica.  x: [B, d_in], y: [B] int.
+
+    If `info` is given, info["relu_margin"] receives the smallest |pre-activation| over all
+    hidden units: the gradient is discontinuous where a pre-activation is zero, so a
+    comparison against an implementation in another precision is only meaningful when this
+    margin exceeds that implementation's rounding error."""
     def q(a):
         return round_bf16(a.astype(np.float32)).astype(np.float64) if bf16 else a.astype(np.float64)
 
@@ -73,6 +78,8 @@ def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Se
         pre.append(zi)
         if i + 1 < n_layers:
             acts.append(q(np.maximum(zi, 0.0)))
+    if info is not None:
+        info["relu_margin"] = min([float(np.min(np.abs(p))) for p in pre[:-1]] + [float("inf")])
     loss, dz = softmax_xent(pre[-1], y.astype(np.int64))
     grads: List[np.ndarray] = [None] * (2 * n_layers)
     for i in range(n_layers - 1, -1, -1):

@@ -68,9 +68,16 @@ def check_state(st, orc: O.HDETOracle, scalar_rtol=1e-12, lr_ulps=1):
         assert np.allclose([st.rho[j][r] for r in range(n)], orc.rho[j], rtol=1e-15, atol=0)
         if j > 0 or orc.controller_active:
             assert np.isclose(st.base[j], orc.base[j], rtol=scalar_rtol, atol=1e-300), f"base[{j}]"
-        assert np.isclose(st.vel[j], orc.vel[j], rtol=scalar_rtol, atol=1e-24), f"vel[{j}]"
-        assert np.isclose(st.delta[j], orc.delta[j], rtol=scalar_rtol, atol=1e-24), f"delta[{j}]"
+        # Delta and v are differences of nearly equal terms of the size of the base value:
+        # their error is measured against that size
+        scale = scalar_rtol * abs(orc.base[j]) + 1e-24
+        assert np.isclose(st.vel[j], orc.vel[j], rtol=scalar_rtol, atol=scale), f"vel[{j}]"
+        assert np.isclose(st.delta[j], orc.delta[j], rtol=scalar_rtol, atol=scale), f"delta[{j}]"
     assert np.allclose([st.w[r] for r in range(n)], orc.w, rtol=scalar_rtol, atol=0)
     assert np.isclose(st.gamma, orc.gamma, rtol=1e-14)
     if orc.t > 0:
-        assert ulp_diff_f32([st.lr[r] for r in range(n)], orc.lr_used) <= lr_ulps
+        lr = np.array([st.lr[r] for r in range(n)], dtype=np.float32)
+        if lr_ulps is not None:
+            assert ulp_diff_f32(lr, orc.lr_used) <= lr_ulps
+        else:       # base rate known only to scalar_rtol (losses reduced in fp32 on the device)
+            assert np.allclose(lr, orc.lr_used, rtol=2 * scalar_rtol, atol=0)

@@ -1,0 +1,230 @@
+"""Parity of the whole HDET loop on an MLP (forward, cross-entropy, backward, fan-out
+update, converge, controller) between the HIP path and the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import hdet_inputs as I
+import paper_2604_24708_amd as H
+from harness import check_state, library_config, oracle_config, rel_err
+from oracle import hdet_oracle as O
+from oracle import mlp_oracle as M
+
+pytestmark = pytest.mark.gpu
+
+TOL_STEP, TOL_100 = 1e-5, 1e-4
+# Gradients are an intermediate (the stated bounds are on the parameters).  An entry is a dot
+# product of K = batch or layer-width fp32 terms, accumulated in fp32 on the device and in fp64
+# by the oracle: the difference is up to about sqrt(K) * 2^-24 of the sum of magnitudes, which
+# after cancellation is up to 1e-4 of the entry itself for K up to a few hundred (three chained products).
+TOL_GRAD = 2e-4
+
+
+def tol_at(t):
+    return min(t * TOL_STEP, TOL_100)
+
+
+class MlpRun:
+    def __init__(self, d, widths, batch, identical_batches=False, bf16=False):
+        self.d, self.widths, self.batch = d, widths, batch
+        self.n = n = d["n_replicas"]
+        self.identical = identical_batches
+        self.bf16 = bf16
+        self.relu_tau = 2e-2 if bf16 else 2e-6     # rounding error of a device pre-activation
+        self.resyncs = 0
+        self.P = P = I.mlp_param_count(widths)
+        self.stride = (P + 3) // 4 * 4
+        th0 = I.mlp_init(n, widths, I.SEED_INIT)
+        self.orc = O.HDETOracle(oracle_config(d), th0)
+        dev = "cuda:0"
+        host = np.zeros((n, self.stride), np.float32)
+        host[:, :P] = th0
+        self.theta = torch.from_numpy(host).to(dev)
+        self.m = torch.zeros_like(self.theta)
+        self.v = torch.zeros_like(self.theta)
+        self.g = torch.zeros_like(self.theta)
+        self.shadow = torch.zeros((n, self.stride), dtype=torch.bfloat16, device=dev) if bf16 else None
+        cfg = library_config(d, widths=widths, batch=batch, model_kind=H.HDET_MLP,
+                             precision=H.HDET_BF16_GEMM_FP32_MASTER if bf16 else H.HDET_FP32)
+        _, _, ws = H.hdet_workspace_bytes(cfg, self.stride)
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
+        self.h = H.hdet_create(cfg, self.theta, self.m, self.v if d["optimizer"] == O.ADAMW else None,
+                               grads=self.g, params_bf16=self.shadow, workspace=self.ws,
+                               plane_stride=self.stride)
+
+    def step(self, t, fuse=False, check_grads=False):
+        n, P = self.n, self.P
+        x, y = I.mlp_batch(n, self.batch, self.widths[0], I.SEED_DATA, t, self.widths, I.SEED_TEACHER,
+                           identical=self.identical)
+        xd, yd = torch.from_numpy(x).to("cuda:0"), torch.from_numpy(y).to("cuda:0")
+        out = H.hdet_forward_backward(self.h, xd, yd, want_losses=True)
+        gpu_losses = np.array([out[r] for r in range(n)])
+        losses = np.zeros(n)
+        grads = np.zeros((n, P), np.float32)
+        margin = float("inf")
+        th_dev = self.theta.cpu().numpy()[:, :P]
+        for r in range(n):
+            info = {}
+            losses[r], grads[r] = M.mlp_loss_and_grad(self.orc.theta[r], x[r], y[r], self.widths,
+                                                      bf16=self.bf16, info=info)
+            margin = min(margin, info["relu_margin"])
+        self.loss_err = float(np.max(np.abs(gpu_losses - losses)))
+        if check_grads:
+            # gradient parity proper: the oracle's gradient at the device's own parameters
+            # (the trajectories of the two sides differ by up to the parameter tolerance)
+            at_dev = []
+            for r in range(n):
+                info = {}
+                at_dev.append(M.mlp_loss_and_grad(th_dev[r], x[r], y[r], self.widths, bf16=self.bf16, info=info)[1])
+                margin = min(margin, info["relu_margin"])
+            self.grad_err = rel_err(self.g.cpu().numpy()[:, :P], np.stack(at_dev))
+        # A ReLU whose pre-activation is within the device's rounding error of zero may open on
+        # one side and stay shut on the other; both gradients are valid (sub)gradients.  Such a
+        # step is not compared, and the oracle continues from the device's state.
+        self.borderline = margin < self.relu_tau
+        H.hdet_fanout_step(self.h, None, H.HDET_FUSE_CONVERGE if fuse else 0)
+        self.orc.fanout_step(grads, losses)
+        if self.borderline:
+            self.resyncs += 1
+            assert not fuse, "borderline step on a fused sync step: rerun with another seed"
+            self.orc.theta = self.theta.cpu().numpy()[:, :P].copy()
+            self.orc.m = self.m.cpu().numpy()[:, :P].copy()
+            self.orc.v = self.v.cpu().numpy()[:, :P].copy()
+            self.grad_err = self.loss_err = 0.0
+        if t % self.d["sync_interval"] == 0:
+            H.hdet_converge(self.h)
+            self.orc.converge()
+            H.hdet_autolr_update(self.h, None)        # device-accumulated losses
+            self.orc.autolr_update()
+        return gpu_losses, losses
+
+    def param_err(self):
+        return rel_err(self.theta.cpu().numpy()[:, :self.P], self.orc.theta)
+
+    def close(self):
+        H.hdet_destroy(self.h)
+
+
+def cfg0(**kw):
+    """N=4, MLP 64->128->10, batch 32, SGD momentum 0.9, one-cycle peak 0.05 over 40 steps,
+    alpha 0.2, T=4, auto-LR on (S_warm = 12 = end of the rising phase)."""
+    d = dict(n_replicas=4, total_steps=40, sync_interval=4, warm_steps=12, lr_max=0.05, alpha=0.2,
+             autolr_enabled=True, optimizer=O.SGDM, momentum=0.9, weight_decay=0.0,
+             grad_mode=O.GRAD_PER_REPLICA, seed=I.SEED_PERM)
+    d.update(kw)
+    return d
+
+
+@pytest.mark.parametrize("steps", [40, 100])
+def test_cfg0_full_trajectory(steps):
+    d = cfg0(total_steps=steps, warm_steps=int(0.3 * steps))
+    run = MlpRun(d, [64, 128, 10], 32)
+    first = last = None
+    for t in range(1, steps + 1):
+        gl, ol = run.step(t, fuse=(t % 8 == 0), check_grads=True)
+        first = ol.mean() if first is None else first
+        last = ol.mean()
+        assert run.loss_err <= 2e-6 * max(1.0, abs(ol).max())
+        assert run.grad_err <= TOL_GRAD
+        assert run.param_err() <= tol_at(t)
+        # controller scalars now depend on device-reduced fp32 losses: 1e-6, integers exact
+        check_state(H.hdet_get_state(run.h), run.orc, scalar_rtol=2e-6, lr_ulps=None)
+    assert last < first                      # it trains
+    assert run.resyncs <= steps // 20
+    st = H.hdet_get_state(run.h)
+    assert st.controller_active == 1 and st.k == (steps - int(0.3 * steps)) // 4 + 1
+    th = run.theta.cpu().numpy()
+    assert all(np.array_equal(th[0], th[r]) for r in range(4))     # Algorithm 1: identical at the end
+    run.close()
+
+
+def adamw_step_from_device_state(run, t):
+    """One AdamW step compared from identical state.  Adam's first steps move an entry by
+    lr * g / (|g| + eps): where |g| is of the size of eps the step is ill-conditioned in g,
+    so the allowed deviation of an entry is the per-step 1e-5 plus what the oracle itself
+    moves when its gradient is perturbed by the gradient tolerance."""
+    import copy
+    n, P = run.n, run.P
+    run.orc.theta = run.theta.cpu().numpy()[:, :P].copy()
+    run.orc.m = run.m.cpu().numpy()[:, :P].copy()
+    run.orc.v = run.v.cpu().numpy()[:, :P].copy()
+    x, y = I.mlp_batch(n, run.batch, run.widths[0], I.SEED_DATA, t, run.widths, I.SEED_TEACHER)
+    out = H.hdet_forward_backward(run.h, torch.from_numpy(x).to("cuda:0"), torch.from_numpy(y).to("cuda:0"),
+                                  want_losses=True)
+    losses, grads, margin = np.zeros(n), np.zeros((n, P), np.float32), float("inf")
+    for r in range(n):
+        info = {}
+        losses[r], grads[r] = M.mlp_loss_and_grad(run.orc.theta[r], x[r], y[r], run.widths, info=info)
+        margin = min(margin, info["relu_margin"])
+    borderline = margin < run.relu_tau
+    if not borderline:
+        assert np.max(np.abs(np.array([out[r] for r in range(n)]) - losses)) <= 1e-5
+        assert rel_err(run.g.cpu().numpy()[:, :P], grads) <= TOL_GRAD
+    pert = TOL_GRAD * np.maximum(np.abs(grads), np.sqrt(np.mean(grads.astype(np.float64) ** 2)) / 32).astype(np.float32)
+    hi, lo = copy.deepcopy(run.orc), copy.deepcopy(run.orc)
+    H.hdet_fanout_step(run.h, None, 0)
+    run.orc.fanout_step(grads, losses)
+    hi.fanout_step(grads + pert, losses)
+    lo.fanout_step(grads - pert, losses)
+    if not borderline:
+        ref = run.orc.theta.astype(np.float64)
+        dev = run.theta.cpu().numpy()[:, :P].astype(np.float64)
+        floor = np.sqrt(np.mean(ref * ref)) / 32
+        allowed = TOL_STEP * np.maximum(np.abs(ref), floor) + np.maximum(np.abs(hi.theta - ref), np.abs(lo.theta - ref))
+        assert np.all(np.abs(dev - ref) <= allowed)
+    if t % run.d["sync_interval"] == 0:
+        H.hdet_converge(run.h)
+        run.orc.converge()
+        H.hdet_autolr_update(run.h, None)
+        run.orc.autolr_update()
+        assert rel_err(run.theta.cpu().numpy()[:, :P], run.orc.theta) <= 1e-5 or borderline
+
+
+@pytest.mark.parametrize("widths,batch,n", [([7, 5, 6, 3], 9, 3), ([200, 300, 70], 130, 2), ([65, 64, 63, 129, 5], 67, 5),
+                                            ([16, 4], 1, 8)])
+def test_ragged_shapes_adamw(widths, batch, n):
+    d = cfg0(n_replicas=n, optimizer=O.ADAMW, weight_decay=0.01, lr_max=3e-3, total_steps=12, warm_steps=4)
+    run = MlpRun(d, widths, batch)
+    for t in range(1, 13):
+        adamw_step_from_device_state(run, t)
+    st = H.hdet_get_state(run.h)
+    assert st.t == 12 and st.k == 3
+    run.close()
+
+
+@pytest.mark.parametrize("widths,batch,n", [([7, 5, 6, 3], 9, 3), ([200, 300, 70], 130, 2), ([65, 64, 63, 129, 5], 67, 5)])
+def test_ragged_shapes_sgdm_trajectory(widths, batch, n):
+    d = cfg0(n_replicas=n, total_steps=12, warm_steps=4)
+    run = MlpRun(d, widths, batch)
+    for t in range(1, 13):
+        run.step(t, check_grads=True)
+        assert run.loss_err <= 1e-5
+        assert run.grad_err <= TOL_GRAD
+        assert run.param_err() <= tol_at(t)
+    run.close()
+
+
+def test_alpha_zero_identical_batches_stay_identical():
+    d = cfg0(alpha=0.0, autolr_enabled=False)
+    run = MlpRun(d, [64, 128, 10], 32, identical_batches=True)
+    for t in range(1, 9):
+        run.step(t)
+        th = run.theta.cpu().numpy()
+        assert all(np.array_equal(th[0], th[r]) for r in range(4))
+    run.close()
+
+
+def test_shared_gradients_sgd_t1_follow_single_model_at_base_rate():
+    """Plain SGD, T = 1, shared gradients: the averaged model takes one step at the base rate
+    on the mean gradient (sum of rho is N)."""
+    d = cfg0(momentum=0.0, sync_interval=1, grad_mode=O.GRAD_SHARED, autolr_enabled=False)
+    run = MlpRun(d, [64, 128, 10], 32)
+    ref = run.orc.theta[0].astype(np.float64).copy()
+    for t in range(1, 11):
+        x, y = I.mlp_batch(4, 32, 64, I.SEED_DATA, t, [64, 128, 10], I.SEED_TEACHER)
+        gbar = np.mean([M.mlp_loss_and_grad(ref.astype(np.float32), x[r], y[r], [64, 128, 10])[1].astype(np.float64)
+                        for r in range(4)], axis=0)
+        ref = ref - O.onecycle_lr(t - 1, 40, 0.05, 25.0, 1e4, 0.3) * gbar
+        run.step(t, fuse=True)
+        assert rel_err(run.theta.cpu().numpy()[0, :run.P], ref) <= 1e-5 * t
+    run.close()
