@@ -28,6 +28,24 @@ HBM_PEAK_GBS = 8000.0
 ADAMW_BYTES = 28          # per replica-element per update
 CONVERGE_BYTES = 8        # standalone converge: 4 read + 4 written
 
+# HBM bytes per launch of the update kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by
+# what the same counters read for a plain 4e9-byte copy: x2.000 and x1.000), measured on the
+# default workload; valid only for the kernel source it was taken with.
+TRAFFIC_KERNEL_SHA = "fed40120815a0bbe"
+TRAFFIC_BYTES_PER_REPLICA_ELEMENT = 224.000e9 / 8e9
+
+
+def measured_traffic(n, p):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2604_24708_amd", "csrc", "hdet_update.hip")
+    try:
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    if sha != TRAFFIC_KERNEL_SHA or (n, p) != (8, 1_000_000_000):
+        return None      # kernel or workload changed since the counters were taken
+    return TRAFFIC_BYTES_PER_REPLICA_ELEMENT * n * p
+
 
 def oracle_baseline(n, t_sync, p_sample, steps):
     """The CPU oracle as it stands on a bounded sample: same N, T, optimizer; P = p_sample."""
@@ -64,6 +82,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="update kernel selection (0 = default)")
     ap.add_argument("--blocks", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of known size (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the replicas are an axis in one GPU's memory); "
@@ -125,6 +145,12 @@ def main():
                 conv_ev.append((c0, c1))
             H.hdet_autolr_update(h, losses)
 
+    if args.copy_calibration:
+        # 3 x (4 GiB read + 4 GiB written) by a plain elementwise copy kernel
+        src, dst = g[0].view(-1)[:1 << 30], m[0].view(-1)[:1 << 30]
+        for _ in range(3):
+            dst.copy_(src)
+        dst.zero_()
     for t in range(1, args.warmup + 1):
         step(t, False)
     torch.cuda.synchronize()
@@ -155,7 +181,7 @@ def main():
                    "n_replicas": n, "n_params": P, "sync_interval": T, "grad_mode": args.grad_mode,
                    "controller_updates": int(st.k)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(n, P),
                      "kernel": "hdet_update_kernel", "kernel_ms": upd_ms,
                      "algorithmic_bytes_per_launch": bytes_per_launch},
     }
