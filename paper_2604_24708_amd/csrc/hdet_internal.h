@@ -90,6 +90,27 @@ hipError_t hdet_launch_shadow(const float* theta, uint16_t* shadow, int64_t n_pa
 hipError_t hdet_launch_controller(const hdet_controller_args& a, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
+// Replica-batched bf16 GEMM on the matrix cores (hdet_gemm_bf16.hip)
+// ---------------------------------------------------------------------------------------
+enum { HDET_EPI_F32 = 0, HDET_EPI_BIAS_F32 = 1, HDET_EPI_BIAS_RELU_BF16 = 2, HDET_EPI_MASK_BF16 = 3 };
+
+struct hdet_bgemm_args {
+  const uint16_t* a;       // bf16
+  const uint16_t* b;       // bf16
+  void* c;                 // fp32 or bf16, row-major [m][ldc]
+  int m, n, k;
+  int64_t lda, ldb, ldc;   // leading dimensions in elements
+  int64_t a_bs, b_bs, c_bs;            // replica strides in elements
+  const float* bias; int64_t bias_bs;  // bias[n] per replica
+  const uint16_t* mask; int64_t mask_ld, mask_bs;   // bf16 activations gating the gradient
+};
+
+// a_kmajor: A(m,k) at a[m*lda + k], else at a[k*lda + m]; b_kmajor: B(k,n) at b[n*ldb + k], else
+// at b[k*ldb + n].  (true,true) forward, (true,false) dgrad, (false,false) wgrad.
+hipError_t hdet_launch_bgemm(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi, int batch,
+                             hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
 // MLP forward/backward (hdet_mlp.hip)
 // ---------------------------------------------------------------------------------------
 struct hdet_mlp_plan;

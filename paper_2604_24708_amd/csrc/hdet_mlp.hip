@@ -6,8 +6,11 @@
 // [W_1 (d_out x d_in, row-major), b_1, W_2, b_2, ...]; gradients use the same layout, so the
 // update kernel can stream both without any gather.
 //
-// This file holds the fp32 path: an LDS-tiled SGEMM with fused bias/ReLU (forward),
-// ReLU-mask (dgrad) epilogues, a column-sum for the bias gradients, and a wavefront-per-row
+// fp32 precision: an LDS-tiled SGEMM with fused bias/ReLU (forward) and ReLU-mask (dgrad)
+// epilogues.  bf16 precision (fp32 master weights): the matrix-core GEMM of
+// hdet_gemm_bf16.hip on the bf16 copy of the parameters; every activation and activation
+// gradient that goes to memory is bf16 except the logits; biases, loss and parameter
+// gradients are fp32.  Both: a column-sum for the bias gradients and a wavefront-per-row
 // softmax cross-entropy whose per-replica mean is reduced in a fixed order.
 
 #include <vector>
@@ -99,14 +102,31 @@ void launch_sgemm(const gemm_args& g, int epi, int batch, hipStream_t s) {
 }
 
 // db[z][o] = sum_b dZ[z][b][o], rows added in ascending order by one thread per column.
-__global__ __launch_bounds__(256) void bias_grad_kernel(const float* dz, int rows, int cols, int64_t dz_bs,
+__device__ __forceinline__ float as_float(float x) { return x; }
+__device__ __forceinline__ float as_float(uint16_t h) { return __uint_as_float((unsigned)h << 16); }
+__device__ __forceinline__ void put(float* p, float x) { *p = x; }
+__device__ __forceinline__ void put(uint16_t* p, float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) { *p = (uint16_t)((u >> 16) | 0x0040u); return; }
+  u += 0x7fffu + ((u >> 16) & 1u);
+  *p = (uint16_t)(u >> 16);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bias_grad_kernel(const T* dz, int rows, int cols, int64_t dz_bs,
                                                         float* db, int64_t db_bs) {
   const int o = blockIdx.x * 256 + threadIdx.x;
   if (o >= cols) return;
-  const float* p = dz + (int64_t)blockIdx.y * dz_bs + o;
+  const T* p = dz + (int64_t)blockIdx.y * dz_bs + o;
   float s = 0.f;
-  for (int b = 0; b < rows; ++b) s += p[(int64_t)b * cols];
+  for (int b = 0; b < rows; ++b) s += as_float(p[(int64_t)b * cols]);
   db[(int64_t)blockIdx.y * db_bs + o] = s;
+}
+
+// x (fp32) -> bf16, round to nearest even: the input batch as the first GEMM sees it
+__global__ __launch_bounds__(256) void to_bf16_kernel(const float* x, uint16_t* y, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) put(y + i, x[i]);
 }
 
 __device__ __forceinline__ float wave_max(float x) {
@@ -120,8 +140,9 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 // One wavefront per row: loss_b = log(sum exp(z - max)) - (z_y - max);
 // dlogits = (softmax - onehot) / B.  4 rows per 256-thread block.
+template <typename T>
 __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const int32_t* labels, int rows,
-                                                   int classes, float* dlogits, float* row_loss) {
+                                                   int classes, T* dlogits, float* row_loss) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -135,8 +156,8 @@ __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const in
   se = wave_sum(se);
   const int y = labels[gr];
   const float inv = 1.f / se, invb = 1.f / (float)rows;
-  float* d = dlogits + gr * classes;
-  for (int c = lane; c < classes; c += 64) d[c] = (expf(z[c] - mx) * inv - (c == y ? 1.f : 0.f)) * invb;
+  T* d = dlogits + gr * classes;
+  for (int c = lane; c < classes; c += 64) put(d + c, (expf(z[c] - mx) * inv - (c == y ? 1.f : 0.f)) * invb);
   if (lane == 0) row_loss[gr] = logf(se) - (z[y] - mx);
 }
 
@@ -164,25 +185,30 @@ struct hdet_mlp_plan {
   hdet_buffers buf;
   int n_layers;
   std::vector<int64_t> w_off, b_off;     // offsets inside a parameter plane
-  std::vector<float*> act;               // act[i]: input of layer i (act[0] is the caller's x)
+  std::vector<void*> act;                // act[i]: input of layer i, fp32 or bf16 by precision
+                                         // (fp32: act[0] is the caller's x; bf16: its bf16 copy)
   float* logits;
-  float* dz_a; float* dz_b;              // ping-pong activation gradients
+  void* dz_a; void* dz_b;                // ping-pong activation gradients, fp32 or bf16
   float* row_loss;
+  bool bf16;
 };
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 int hdet_mlp_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err) {
-  if (cfg.precision != HDET_FP32) { *err = "HDET_MLP is built for HDET_FP32 only"; return HDET_EINVAL; }
+  (void)err;
   const size_t n = cfg.n_replicas, b = cfg.dims.batch;
   const int L = cfg.dims.n_layers;
+  const bool bf16 = cfg.precision == HDET_BF16_GEMM_FP32_MASTER;
+  const size_t esz = bf16 ? sizeof(uint16_t) : sizeof(float);
   size_t total = 0, maxw = 0;
-  for (int i = 1; i <= L; ++i) {
-    total += align_up(n * b * (size_t)cfg.dims.widths[i] * sizeof(float));   // act[1..L-1], logits
+  if (bf16) total += align_up(n * b * (size_t)cfg.dims.widths[0] * esz);      // bf16 copy of x
+  for (int i = 1; i <= L; ++i) {                                              // act[1..L-1], logits
+    total += align_up(n * b * (size_t)cfg.dims.widths[i] * (i < L ? esz : sizeof(float)));
     if ((size_t)cfg.dims.widths[i] > maxw) maxw = cfg.dims.widths[i];
   }
   for (int i = 0; i < L; ++i) if ((size_t)cfg.dims.widths[i] > maxw) maxw = cfg.dims.widths[i];
-  total += 2 * align_up(n * b * maxw * sizeof(float));                        // dz ping-pong
+  total += 2 * align_up(n * b * maxw * esz);                                  // dz ping-pong
   total += align_up(n * b * sizeof(float));                                   // row losses
   *bytes = total;
   return HDET_OK;
@@ -204,53 +230,56 @@ hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, 
   char* ws = (char*)buf.workspace_dev;
   size_t maxw = 0;
   for (int i = 0; i <= L; ++i) if ((size_t)cfg.dims.widths[i] > maxw) maxw = cfg.dims.widths[i];
+  p->bf16 = cfg.precision == HDET_BF16_GEMM_FP32_MASTER;
+  const size_t esz = p->bf16 ? sizeof(uint16_t) : sizeof(float);
   p->act.assign(L, nullptr);
+  if (p->bf16) { p->act[0] = ws; ws += align_up(n * b * (size_t)cfg.dims.widths[0] * esz); }
   for (int i = 1; i <= L; ++i) {
-    float* ptr = (float*)ws; ws += align_up(n * b * (size_t)cfg.dims.widths[i] * sizeof(float));
-    if (i < L) p->act[i] = ptr; else p->logits = ptr;
+    void* ptr = ws; ws += align_up(n * b * (size_t)cfg.dims.widths[i] * (i < L ? esz : sizeof(float)));
+    if (i < L) p->act[i] = ptr; else p->logits = (float*)ptr;
   }
-  p->dz_a = (float*)ws; ws += align_up(n * b * maxw * sizeof(float));
-  p->dz_b = (float*)ws; ws += align_up(n * b * maxw * sizeof(float));
+  p->dz_a = ws; ws += align_up(n * b * maxw * esz);
+  p->dz_b = ws; ws += align_up(n * b * maxw * esz);
   p->row_loss = (float*)ws;
   return p;
 }
 
 void hdet_mlp_destroy(hdet_mlp_plan* p) { delete p; }
 
-hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
-                                     hipStream_t s) {
+static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
+                                       hipStream_t s) {
   const hdet_config& c = p->cfg;
   const int N = c.n_replicas, B = c.dims.batch, L = p->n_layers;
   const int* w = c.dims.widths;
   const int64_t ps = p->buf.plane_stride;
   const float* theta = p->buf.params_dev;
   float* grads = p->buf.grads_dev;
-  p->act[0] = const_cast<float*>(static_cast<const float*>(x));
+  p->act[0] = const_cast<void*>(x);
 
   // forward: Y = act(X W^T + b)
   for (int i = 0; i < L; ++i) {
     gemm_args g = {};
-    g.a = p->act[i]; g.a_rs = w[i]; g.a_cs = 1; g.a_bs = (int64_t)B * w[i];
+    g.a = (const float*)p->act[i]; g.a_rs = w[i]; g.a_cs = 1; g.a_bs = (int64_t)B * w[i];
     g.b = theta + p->w_off[i]; g.b_rs = 1; g.b_cs = w[i]; g.b_bs = ps;      // B(k,n) = W[n][k]
-    g.c = i + 1 < L ? p->act[i + 1] : p->logits; g.c_rs = w[i + 1]; g.c_bs = (int64_t)B * w[i + 1];
+    g.c = i + 1 < L ? (float*)p->act[i + 1] : p->logits; g.c_rs = w[i + 1]; g.c_bs = (int64_t)B * w[i + 1];
     g.m = B; g.n = w[i + 1]; g.k = w[i];
     g.bias = theta + p->b_off[i]; g.bias_bs = ps;
     launch_sgemm(g, i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, N, s);
   }
   // loss and dlogits
-  float* dz = p->dz_a; float* dz_next = p->dz_b;
-  hipLaunchKernelGGL(xent_kernel, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss);
+  float* dz = (float*)p->dz_a; float* dz_next = (float*)p->dz_b;
+  hipLaunchKernelGGL(xent_kernel<float>, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss);
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   // backward
   for (int i = L - 1; i >= 0; --i) {
     // dW = dZ^T X
     gemm_args g = {};
     g.a = dz; g.a_rs = 1; g.a_cs = w[i + 1]; g.a_bs = (int64_t)B * w[i + 1];     // A(o,b) = dZ[b][o]
-    g.b = p->act[i]; g.b_rs = w[i]; g.b_cs = 1; g.b_bs = (int64_t)B * w[i];      // B(b,k) = X[b][k]
+    g.b = (const float*)p->act[i]; g.b_rs = w[i]; g.b_cs = 1; g.b_bs = (int64_t)B * w[i];   // B(b,k) = X[b][k]
     g.c = grads + p->w_off[i]; g.c_rs = w[i]; g.c_bs = ps;
     g.m = w[i + 1]; g.n = w[i]; g.k = B;
     launch_sgemm(g, EPI_NONE, N, s);
-    hipLaunchKernelGGL(bias_grad_kernel, dim3((w[i + 1] + 255) / 256, N), dim3(256), 0, s, dz, B, w[i + 1],
+    hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 255) / 256, N), dim3(256), 0, s, dz, B, w[i + 1],
                        (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
     if (i > 0) {
       // dX = dZ W, masked by the ReLU of the layer below
@@ -259,10 +288,68 @@ hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int3
       d.b = theta + p->w_off[i]; d.b_rs = w[i]; d.b_cs = 1; d.b_bs = ps;         // B(o,k) = W[o][k]
       d.c = dz_next; d.c_rs = w[i]; d.c_bs = (int64_t)B * w[i];
       d.m = B; d.n = w[i]; d.k = w[i + 1];
-      d.mask = p->act[i]; d.mask_rs = w[i]; d.mask_bs = (int64_t)B * w[i];
+      d.mask = (const float*)p->act[i]; d.mask_rs = w[i]; d.mask_bs = (int64_t)B * w[i];
       launch_sgemm(d, EPI_MASK, N, s);
       float* t = dz; dz = dz_next; dz_next = t;
     }
   }
   return hipGetLastError();
+}
+
+static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
+                                        hipStream_t s) {
+  const hdet_config& c = p->cfg;
+  const int N = c.n_replicas, B = c.dims.batch, L = p->n_layers;
+  const int* w = c.dims.widths;
+  const int64_t ps = p->buf.plane_stride;
+  const float* theta = p->buf.params_dev;           // biases (fp32)
+  const uint16_t* wbf = p->buf.params_bf16_dev;     // weights as the GEMMs see them
+  float* grads = p->buf.grads_dev;
+  hipError_t e;
+
+  const int64_t nx = (int64_t)N * B * w[0];
+  int cb = (int)((nx + 255) / 256); if (cb > 4096) cb = 4096;
+  hipLaunchKernelGGL(to_bf16_kernel, dim3(cb), dim3(256), 0, s, (const float*)x, (uint16_t*)p->act[0], nx);
+
+  for (int i = 0; i < L; ++i) {                      // forward: Y = act(X W^T + b)
+    hdet_bgemm_args g = {};
+    g.a = (const uint16_t*)p->act[i]; g.lda = w[i]; g.a_bs = (int64_t)B * w[i];
+    g.b = wbf + p->w_off[i]; g.ldb = w[i]; g.b_bs = ps;
+    g.c = i + 1 < L ? p->act[i + 1] : (void*)p->logits; g.ldc = w[i + 1]; g.c_bs = (int64_t)B * w[i + 1];
+    g.m = B; g.n = w[i + 1]; g.k = w[i];
+    g.bias = theta + p->b_off[i]; g.bias_bs = ps;
+    e = hdet_launch_bgemm(g, true, true, i + 1 < L ? HDET_EPI_BIAS_RELU_BF16 : HDET_EPI_BIAS_F32, N, s);
+    if (e != hipSuccess) return e;
+  }
+  uint16_t* dz = (uint16_t*)p->dz_a; uint16_t* dz_next = (uint16_t*)p->dz_b;
+  hipLaunchKernelGGL(xent_kernel<uint16_t>, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss);
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
+  for (int i = L - 1; i >= 0; --i) {
+    hdet_bgemm_args g = {};                          // dW = dZ^T X
+    g.a = dz; g.lda = w[i + 1]; g.a_bs = (int64_t)B * w[i + 1];               // A(o,b) = dZ[b][o]
+    g.b = (const uint16_t*)p->act[i]; g.ldb = w[i]; g.b_bs = (int64_t)B * w[i];   // B(b,k) = X[b][k]
+    g.c = grads + p->w_off[i]; g.ldc = w[i]; g.c_bs = ps;
+    g.m = w[i + 1]; g.n = w[i]; g.k = B;
+    e = hdet_launch_bgemm(g, false, false, HDET_EPI_F32, N, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(bias_grad_kernel<uint16_t>, dim3((w[i + 1] + 255) / 256, N), dim3(256), 0, s, dz, B, w[i + 1],
+                       (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
+    if (i > 0) {                                     // dX = dZ W, through the ReLU below
+      hdet_bgemm_args d = {};
+      d.a = dz; d.lda = w[i + 1]; d.a_bs = (int64_t)B * w[i + 1];
+      d.b = wbf + p->w_off[i]; d.ldb = w[i]; d.b_bs = ps;                       // B(o,k) = W[o][k]
+      d.c = dz_next; d.ldc = w[i]; d.c_bs = (int64_t)B * w[i];
+      d.m = B; d.n = w[i]; d.k = w[i + 1];
+      d.mask = (const uint16_t*)p->act[i]; d.mask_ld = w[i]; d.mask_bs = (int64_t)B * w[i];
+      e = hdet_launch_bgemm(d, true, false, HDET_EPI_MASK_BF16, N, s);
+      if (e != hipSuccess) return e;
+      uint16_t* t = dz; dz = dz_next; dz_next = t;
+    }
+  }
+  return hipGetLastError();
+}
+
+hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
+                                     hipStream_t s) {
+  return p->bf16 ? forward_backward_bf16(p, x, y, ctrl, s) : forward_backward_f32(p, x, y, ctrl, s);
 }
