@@ -69,6 +69,83 @@ def oracle_baseline(n, t_sync, p_sample, steps):
     return dt, cores
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def mlp_workload(args):
+    """N = 8 replicas of the 4-layer MLP 1024-4096-4096-4096-1000, batch 256 per replica, bf16
+    GEMMs with fp32 master weights, AdamW, one-cycle 1000 steps peak 3e-4, alpha 0.1, T = 16,
+    auto-LR on.  A step = forward/backward + fan-out update (+ converge + controller on sync
+    steps).  Returns a dict of measurements."""
+    import numpy as np
+    import torch
+    import hdet_inputs as I
+    import paper_2604_24708_amd as H
+    dev = torch.device("cuda:0")
+    n, B, T = 8, 256, 16
+    widths = [1024, 4096, 4096, 4096, 1000]
+    P = I.mlp_param_count(widths)
+    stride = (P + 3) // 4 * 4
+    total = max(1000, args.warmup + args.steps)
+    theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
+    theta[:, :P] = torch.from_numpy(I.mlp_init(1, widths, I.SEED_INIT)).to(dev)
+    m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.zeros_like(theta)
+    shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
+    x = torch.empty((n, B, widths[0]), dtype=torch.float32, device=dev)
+    I.device_normal_(x, I.SEED_DATA, 1.0)
+    y = torch.randint(0, widths[-1], (n, B), dtype=torch.int32, device=dev,
+                      generator=torch.Generator(device=dev).manual_seed(I.SEED_TEACHER))
+    stream = torch.cuda.current_stream()
+    cfg = H.make_config(n_replicas=n, sync_interval=T, total_steps=total, warm_steps=int(0.3 * total),
+                        lr_max=3e-4, alpha=0.1, autolr_enabled=1, optimizer=H.HDET_ADAMW, weight_decay=0.01,
+                        grad_mode=H.HDET_GRAD_PER_REPLICA, precision=H.HDET_BF16_GEMM_FP32_MASTER,
+                        model_kind=H.HDET_MLP, widths=widths, batch=B, seed=I.SEED_PERM,
+                        stream=stream.cuda_stream)
+    _, _, ws_bytes = H.hdet_workspace_bytes(cfg, stride)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    h = H.hdet_create(cfg, theta, m, v, grads=g, params_bf16=shadow, workspace=ws, plane_stride=stride)
+    ev = []
+
+    def step(t, timed):
+        if timed:
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(stream)
+        H.hdet_forward_backward(h, x, y)
+        if timed:
+            e[1].record(stream)
+        H.hdet_fanout_step(h, None, H.HDET_FUSE_CONVERGE)
+        if timed:
+            e[2].record(stream)
+            ev.append(e)
+        if t % T == 0:
+            H.hdet_converge(h)
+            H.hdet_autolr_update(h, None)
+
+    for t in range(1, args.warmup + 1):
+        step(t, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup + 1, args.warmup + args.steps + 1):
+        step(t, True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    fb_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / len(ev)
+    up_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
+    st = H.hdet_get_state(h)
+    H.hdet_destroy(h)
+    fwd_flop = sum(2.0 * B * widths[i] * widths[i + 1] for i in range(len(widths) - 1))
+    dgrad_flop = sum(2.0 * B * widths[i] * widths[i + 1] for i in range(1, len(widths) - 1))
+    gemm_flop = n * (2 * fwd_flop + dgrad_flop)          # forward + wgrad + dgrad (none for layer 1)
+    tflops = gemm_flop / (fb_ms * 1e-3) / 1e12
+    return {"workload": "N=8 x MLP 1024-4096-4096-4096-1000, batch 256/replica, bf16 GEMM + fp32 master, AdamW, T=16",
+            "replica_steps_per_s": n * args.steps / dt, "ms_per_step": dt / args.steps * 1e3,
+            "forward_backward_ms": fb_ms, "update_ms": up_ms,
+            "update_GBps": 30.0 * n * P / (up_ms * 1e-3) / 1e9,
+            "gemm_flop_per_step": gemm_flop, "forward_backward_TFLOPs": tflops,
+            "mfma_frac_of_bf16_peak": tflops / MFMA_BF16_PEAK_TFLOPS,
+            "loss_first_replica": float(st.l_step[0])}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +159,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="update kernel selection (0 = default)")
     ap.add_argument("--blocks", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=["flat", "mlp", "both"], default="both",
+                    help="flat: the headline flat-buffer case only; mlp: only the bf16 MLP case (printed as its own "
+                         "JSON line); both: the headline line with the MLP figures attached as `mlp_bf16`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of known size (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -99,6 +179,9 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "mlp":
+        print(json.dumps(mlp_workload(args)))
+        return
     n, P, T = args.replicas, int(args.params), args.sync_interval
     stride = (P + 3) // 4 * 4
     total = args.warmup + args.steps
@@ -189,9 +272,11 @@ def main():
         cms = sum(a.elapsed_time(b) for a, b in conv_ev) / len(conv_ev)
         out["converge_standalone"] = {"kernel_ms": cms, "achieved": CONVERGE_BYTES * n * P / (cms * 1e-3) / 1e9,
                                       "unit": "GB/s"}
+    del theta, g, m, v
+    torch.cuda.empty_cache()
+    if args.workload == "both":
+        out["mlp_bf16"] = mlp_workload(args)
     if not args.no_cpu_baseline:
-        del theta, g, m, v
-        torch.cuda.empty_cache()
         p_sample, o_steps = 4_000_000, T + 1
         odt, cores = oracle_baseline(n, T, p_sample, o_steps)
         out["cpu_baseline"] = {"value": n * o_steps / odt * (p_sample / P), "unit": "replica-steps/s",

@@ -9,13 +9,17 @@
 //   forward  Y  = X  W^T : A = X [b][k]  (k contiguous)   B(k,n) = W[n][k]  (k contiguous)
 //   dgrad    dX = dY W   : A = dY[b][o]  (k=o contiguous) B(k,n) = W[k][n]  (n contiguous)
 //   wgrad    dW = dY^T X : A(m,k) = dY[k][m] (m contiguous) B(k,n) = X[k][n] (n contiguous)
-// Tiles are staged through LDS in one layout -- rows of the output dimension, the
-// contraction index contiguous -- so that every MFMA operand is a single 128-bit LDS read;
-// an operand whose memory is contiguous along the other axis is transposed on its way into
-// LDS (128-bit coalesced global loads, 16-bit LDS stores).
+// Tiles are staged through LDS with 128-bit coalesced global loads and 128-bit LDS stores in
+// the operand's own memory order, and read back as MFMA operands (8 consecutive contraction
+// elements per lane):
+//   * contraction-contiguous operand: LDS tile [128 rows][32 k], one ds_read_b128 per fragment;
+//   * operand contiguous along the output axis: LDS tile [32 k][128 rows], read with the
+//     transposing LDS load of gfx950 (ds_read_b64_tr_b16, two per fragment), so that no
+//     transposed copy of weights or activations ever exists in HBM.
 //
 // Tiling: 128x128 output tile per 256-thread block (4 wavefronts, 2x2, 64x64 each as 2x2
-// v_mfma_f32_32x32x16_bf16), K step 32, next tile's global loads in flight during the MFMAs.
+// v_mfma_f32_32x32x16_bf16), K step 32, LDS double-buffered (one barrier per K step), global
+// loads prefetched two K steps ahead through a ring of registers.
 
 #include "hdet_internal.h"
 
@@ -24,9 +28,18 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+typedef short s4 __attribute__((ext_vector_type(4)));
+typedef short s8 __attribute__((ext_vector_type(8)));
 
 constexpr int TM = 128, TN = 128, TK = 32;
-constexpr int LDK = TK + 8;           // LDS row pitch in elements: 80 B, keeps rows 16-byte aligned
+constexpr int LDK = TK;          // pitch of a [row][k] tile: 64 B, no padding; the four 16-byte chunks of a
+                                 // row are stored XOR-swizzled by (row / 4) % 4, which makes both the
+                                 // staging stores (4 rows x 4 chunks per 16 lanes) and the fragment
+                                 // loads (16 rows x 1 chunk per 16 lanes) free of bank conflicts
+constexpr int LDR = TM + 32;     // pitch of a [k][row] tile: 320 B = 80 banks, so the 4 k-rows that a
+                                 // 16-lane group of a transposing read touches fall on disjoint banks
+constexpr int TILE_ELEMS = 5120; // max(128 * LDK, 32 * LDR)
+constexpr int PF = 2;            // K steps of global loads in flight (even)
 
 __device__ __forceinline__ unsigned short f2bf(float x) {
   unsigned u = __float_as_uint(x);
@@ -37,7 +50,16 @@ __device__ __forceinline__ unsigned short f2bf(float x) {
 __device__ __forceinline__ float bf2f(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
 
 // 8 consecutive elements starting at src[idx], of which the first `valid` exist (others 0).
+// FAST: the host has checked that every chunk is 16-byte aligned and either whole or absent
+// (leading dimensions, extents along the chunk axis and replica strides multiples of 8), so the
+// load is one branch-free 128-bit access -- an absent chunk reads src[0..7] and is zeroed.
+template <bool FAST>
 __device__ __forceinline__ us8 load8(const uint16_t* src, int64_t idx, int valid, bool vec_ok) {
+  if (FAST) {
+    const us8 v = *reinterpret_cast<const us8*>(src + (valid > 0 ? idx : 0));
+    const us8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    return valid > 0 ? v : zero;
+  }
   if (valid >= 8 && vec_ok) return *reinterpret_cast<const us8*>(src + idx);
   us8 r = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -46,10 +68,11 @@ __device__ __forceinline__ us8 load8(const uint16_t* src, int64_t idx, int valid
   return r;
 }
 
-// Stages one operand tile (128 rows of the output dimension x 32 of the contraction).
-// KMAJOR: element (row, k) at src[row * ld + k]; otherwise at src[k * ld + row].
-template <bool KMAJOR>
-struct stager {
+// One operand tile: 128 rows of the output dimension x 32 of the contraction.
+// KMAJOR: element (row, k) at src[row * ld + k], LDS tile[row][k];
+// otherwise at src[k * ld + row], LDS tile[k][row].
+template <bool KMAJOR, bool FAST>
+struct operand {
   us8 reg[2];
   __device__ __forceinline__ void fetch(const uint16_t* src, int64_t ld, int row0, int rows, int k0, int kdim,
                                         bool vec_ok, int tid) {
@@ -58,36 +81,47 @@ struct stager {
       const int c = tid + i * 256;
       if (KMAJOR) {
         const int row = row0 + (c >> 2), k = k0 + ((c & 3) << 3);
-        const int valid = row < rows ? kdim - k : 0;
-        reg[i] = load8(src, (int64_t)row * ld + k, valid, vec_ok);
+        reg[i] = load8<FAST>(src, (int64_t)row * ld + k, row < rows ? kdim - k : 0, vec_ok);
       } else {
         const int k = k0 + (c >> 4), row = row0 + ((c & 15) << 3);
-        const int valid = k < kdim ? rows - row : 0;
-        reg[i] = load8(src, (int64_t)k * ld + row, valid, vec_ok);
+        reg[i] = load8<FAST>(src, (int64_t)k * ld + row, k < kdim ? rows - row : 0, vec_ok);
       }
     }
   }
-  __device__ __forceinline__ void commit(uint16_t (*tile)[LDK], int tid) const {
+  __device__ __forceinline__ void commit(uint16_t* tile, int tid) const {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int c = tid + i * 256;
-      if (KMAJOR) {
-        *reinterpret_cast<us8*>(&tile[c >> 2][(c & 3) << 3]) = reg[i];
-      } else {
-        const int k = c >> 4, row = (c & 15) << 3;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) tile[row + j][k] = reg[i][j];
-      }
+      if (KMAJOR) *reinterpret_cast<us8*>(tile + (c >> 2) * LDK + ((((c & 3) ^ (c >> 4)) & 3) << 3)) = reg[i];
+      else *reinterpret_cast<us8*>(tile + (c >> 4) * LDR + ((c & 15) << 3)) = reg[i];
     }
+  }
+  // MFMA 32x32x16 operand fragment: lane l gets (row = r0 + l % 32, k = ks + 8 * (l / 32) + 0..7).
+  static __device__ __forceinline__ bf16x8 fragment(const uint16_t* tile, int r0, int ks, int lane) {
+    if (KMAJOR) {
+      const int row = r0 + (lane & 31);
+      const int chunk = ((ks >> 3) + (lane >> 5)) ^ ((row >> 2) & 3);
+      return *reinterpret_cast<const bf16x8*>(tile + row * LDK + (chunk << 3));
+    }
+    // Transposing read: within a 16-lane group, lane p points at the 4 elements
+    // (k = kb + p / 4, rows rb + 4 * (p % 4) .. + 3) and lane i receives (k = kb .. kb + 3, row rb + i).
+    const int p = lane & 15;
+    const int rb = r0 + (((lane >> 4) & 1) << 4);
+    const int kb = ks + ((lane >> 5) << 3);
+    const uint16_t* q = tile + (kb + (p >> 2)) * LDR + rb + ((p & 3) << 2);
+    const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)(q));
+    const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)(q + 4 * LDR));
+    const s8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, both);
   }
 };
 
 }  // namespace
 
-template <bool A_KMAJOR, bool B_KMAJOR, int EPI>
+template <bool A_KMAJOR, bool B_KMAJOR, int EPI, bool FAST>
 __global__ __launch_bounds__(256) void hdet_bgemm_kernel(const hdet_bgemm_args g) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[TM][LDK];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[TN][LDK];
+  __shared__ __attribute__((aligned(16))) uint16_t As[2][TILE_ELEMS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][TILE_ELEMS];
   const int z = blockIdx.z;
   const uint16_t* A = g.a + (int64_t)z * g.a_bs;
   const uint16_t* B = g.b + (int64_t)z * g.b_bs;
@@ -105,33 +139,51 @@ __global__ __launch_bounds__(256) void hdet_bgemm_kernel(const hdet_bgemm_args g
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  stager<A_KMAJOR> sa;
-  stager<B_KMAJOR> sb;
-  sa.fetch(A, g.lda, m0, g.m, 0, g.k, a_vec, tid);
-  sb.fetch(B, g.ldb, n0, g.n, 0, g.k, b_vec, tid);
-  for (int k0 = 0; k0 < g.k; k0 += TK) {
-    sa.commit(As, tid);
-    sb.commit(Bs, tid);
-    __syncthreads();
-    if (k0 + TK < g.k) {
-      sa.fetch(A, g.lda, m0, g.m, k0 + TK, g.k, a_vec, tid);
-      sb.fetch(B, g.ldb, n0, g.n, k0 + TK, g.k, b_vec, tid);
-    }
+  // Ring of PF register stages: the global loads of K step kt + PF are issued while step kt
+  // is computed, so that about PF x 16 KB per block is in flight -- one step's MFMAs (about
+  // 0.1 us) are far shorter than an HBM round trip.
+  operand<A_KMAJOR, FAST> oa[PF];
+  operand<B_KMAJOR, FAST> ob[PF];
+  // The loop body is free of conditions: K steps past the end of the contraction load zeros
+  // (absent chunks) and multiply them, so the count is simply rounded up to a multiple of PF.
+  const int nk = ((g.k + TK - 1) / TK + PF - 1) / PF * PF;
 #pragma unroll
-    for (int ks = 0; ks < TK; ks += 16) {
-      bf16x8 af[2], bfr[2];
+  for (int d = 0; d < PF; ++d) {
+    oa[d].fetch(A, g.lda, m0, g.m, d * TK, g.k, a_vec, tid);
+    ob[d].fetch(B, g.ldb, n0, g.n, d * TK, g.k, b_vec, tid);
+  }
+  oa[0].commit(As[0], tid);
+  ob[0].commit(Bs[0], tid);
+  __syncthreads();
+  oa[0].fetch(A, g.lda, m0, g.m, PF * TK, g.k, a_vec, tid);
+  ob[0].fetch(B, g.ldb, n0, g.n, PF * TK, g.k, b_vec, tid);
+  for (int kt0 = 0; kt0 < nk; kt0 += PF) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8*>(&As[wm + i * 32 + (lane & 31)][ks + ((lane >> 5) << 3)]);
-        bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[wn + i * 32 + (lane & 31)][ks + ((lane >> 5) << 3)]);
+    for (int d = 0; d < PF; ++d) {
+      const int buf = d & 1;                 // PF is even, so (kt0 + d) & 1 == d & 1
+#pragma unroll
+      for (int ks = 0; ks < TK; ks += 16) {
+        bf16x8 af[2], bfr[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          af[i] = operand<A_KMAJOR, FAST>::fragment(As[buf], wm + i * 32, ks, lane);
+          bfr[i] = operand<B_KMAJOR, FAST>::fragment(Bs[buf], wn + i * 32, ks, lane);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
       }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      // stage tile kt0 + d + 1 into the other LDS buffer (last read before the previous
+      // barrier) and refill its ring slot with tile kt0 + d + 1 + PF
+      const int r = (d + 1) % PF;
+      oa[r].commit(As[buf ^ 1], tid);
+      ob[r].commit(Bs[buf ^ 1], tid);
+      oa[r].fetch(A, g.lda, m0, g.m, (kt0 + d + 1 + PF) * TK, g.k, a_vec, tid);
+      ob[r].fetch(B, g.ldb, n0, g.n, (kt0 + d + 1 + PF) * TK, g.k, b_vec, tid);
+      __syncthreads();
     }
-    __syncthreads();
   }
 
   // epilogue: accumulator element e of lane l is C(row, col) with
@@ -165,10 +217,21 @@ __global__ __launch_bounds__(256) void hdet_bgemm_kernel(const hdet_bgemm_args g
     }
 }
 
+static bool chunk_regular(const void* base, int64_t ld, int64_t bs, int chunk_extent) {
+  return (ld & 7) == 0 && (bs & 7) == 0 && (chunk_extent & 7) == 0 && (reinterpret_cast<uintptr_t>(base) & 15) == 0;
+}
+
 hipError_t hdet_launch_bgemm(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi, int batch,
                              hipStream_t s) {
   dim3 grid((g.n + TN - 1) / TN, (g.m + TM - 1) / TM, batch);
-#define HDET_BGEMM(AK, BK, E) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E>), grid, dim3(256), 0, s, g)
+  // a chunk is 8 elements along the operand's contiguous axis: k if k-major, else the row axis
+  const bool fast = chunk_regular(g.a, g.lda, g.a_bs, a_kmajor ? g.k : g.m) &&
+                    chunk_regular(g.b, g.ldb, g.b_bs, b_kmajor ? g.k : g.n);
+#define HDET_BGEMM(AK, BK, E)                                                                          \
+  do {                                                                                                 \
+    if (fast) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, true>), grid, dim3(256), 0, s, g);      \
+    else hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, false>), grid, dim3(256), 0, s, g);          \
+  } while (0)
   if (a_kmajor && b_kmajor) {            // forward
     if (epi == HDET_EPI_BIAS_RELU_BF16) HDET_BGEMM(true, true, HDET_EPI_BIAS_RELU_BF16);
     else HDET_BGEMM(true, true, HDET_EPI_BIAS_F32);

@@ -101,7 +101,6 @@ void launch_sgemm(const gemm_args& g, int epi, int batch, hipStream_t s) {
   }
 }
 
-// db[z][o] = sum_b dZ[z][b][o], rows added in ascending order by one thread per column.
 __device__ __forceinline__ float as_float(float x) { return x; }
 __device__ __forceinline__ float as_float(uint16_t h) { return __uint_as_float((unsigned)h << 16); }
 __device__ __forceinline__ void put(float* p, float x) { *p = x; }
@@ -112,15 +111,22 @@ __device__ __forceinline__ void put(uint16_t* p, float x) {
   *p = (uint16_t)(u >> 16);
 }
 
+// db[z][o] = sum_b dZ[z][b][o].  Block = 64 columns x 4 row phases: thread (c, q) adds rows
+// q, q+4, ... in ascending order, the four partial sums are then added in the order q = 0..3.
 template <typename T>
 __global__ __launch_bounds__(256) void bias_grad_kernel(const T* dz, int rows, int cols, int64_t dz_bs,
                                                         float* db, int64_t db_bs) {
-  const int o = blockIdx.x * 256 + threadIdx.x;
-  if (o >= cols) return;
-  const T* p = dz + (int64_t)blockIdx.y * dz_bs + o;
+  __shared__ float part[4][64];
+  const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int o = blockIdx.x * 64 + c;
   float s = 0.f;
-  for (int b = 0; b < rows; ++b) s += as_float(p[(int64_t)b * cols]);
-  db[(int64_t)blockIdx.y * db_bs + o] = s;
+  if (o < cols) {
+    const T* p = dz + (int64_t)blockIdx.y * dz_bs + o;
+    for (int b = q; b < rows; b += 4) s += as_float(p[(int64_t)b * cols]);
+  }
+  part[q][c] = s;
+  __syncthreads();
+  if (q == 0 && o < cols) db[(int64_t)blockIdx.y * db_bs + o] = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
 }
 
 // x (fp32) -> bf16, round to nearest even: the input batch as the first GEMM sees it
@@ -279,7 +285,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
     g.c = grads + p->w_off[i]; g.c_rs = w[i]; g.c_bs = ps;
     g.m = w[i + 1]; g.n = w[i]; g.k = B;
     launch_sgemm(g, EPI_NONE, N, s);
-    hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 255) / 256, N), dim3(256), 0, s, dz, B, w[i + 1],
+    hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 63) / 64, N), dim3(256), 0, s, dz, B, w[i + 1],
                        (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
     if (i > 0) {
       // dX = dZ W, masked by the ReLU of the layer below
@@ -332,7 +338,7 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
     g.m = w[i + 1]; g.n = w[i]; g.k = B;
     e = hdet_launch_bgemm(g, false, false, HDET_EPI_F32, N, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bias_grad_kernel<uint16_t>, dim3((w[i + 1] + 255) / 256, N), dim3(256), 0, s, dz, B, w[i + 1],
+    hipLaunchKernelGGL(bias_grad_kernel<uint16_t>, dim3((w[i + 1] + 63) / 64, N), dim3(256), 0, s, dz, B, w[i + 1],
                        (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
     if (i > 0) {                                     // dX = dZ W, through the ReLU below
       hdet_bgemm_args d = {};
