@@ -9,6 +9,7 @@ and merely has the shapes and value distributions the benchmark configurations n
 """
 from .flat import flat_theta0, flat_grads, flat_losses, device_normal_  # noqa: F401
 from .mlp import mlp_param_count, mlp_init, mlp_teacher_labels, mlp_batch  # noqa: F401
+from .transformer import transformer_shapes, transformer_param_count, transformer_init, zipf_tokens  # noqa: F401
 
 SEED_DATA = 1234
 SEED_TEACHER = 4321
