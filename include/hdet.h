@@ -43,7 +43,7 @@ enum { HDET_OK = 0, HDET_EINVAL = -1, HDET_ESTATE = -2, HDET_EHIP = -3 };
 enum { HDET_SGDM = 0, HDET_ADAMW = 1 };                       /* optimizer                   */
 enum { HDET_GRAD_SHARED = 0, HDET_GRAD_PER_REPLICA = 1 };     /* gradient exchange           */
 enum { HDET_FP32 = 0, HDET_BF16_GEMM_FP32_MASTER = 1 };       /* precision of the model GEMMs */
-enum { HDET_FLAT = 0, HDET_MLP = 1 };                         /* model kind                  */
+enum { HDET_FLAT = 0, HDET_MLP = 1, HDET_TRANSFORMER = 2 };   /* model kind                  */
 enum { HDET_CH_LR = 0, HDET_CH_DROPOUT = 1, HDET_CH_WD = 2 }; /* channel kinds               */
 
 /* flags of hdet_fanout_step */
@@ -66,7 +66,11 @@ typedef struct {
   int64_t n_params;                        /* HDET_FLAT: P, parameters per replica           */
   int32_t n_layers;                        /* HDET_MLP: number of Linear layers              */
   int32_t widths[HDET_MAX_LAYERS + 1];     /* HDET_MLP: d_in, hidden..., d_out               */
-  int32_t batch;                           /* HDET_MLP: rows per replica and step            */
+  int32_t batch;                           /* HDET_MLP: rows per replica and step;
+                                              HDET_TRANSFORMER: sequences per replica and step */
+  /* HDET_TRANSFORMER: decoder-only, pre-LayerNorm, learned positions, tanh-GELU MLP, causal
+   * attention, biases on every Linear, untied output head, final LayerNorm (eps 1e-5).      */
+  int32_t n_blocks, d_model, n_heads, d_ff, seq_len, vocab;
 } hdet_model_dims;
 
 /* Arguments of Algorithm 1 ("Require") plus what the paper leaves to the optimizer. */
@@ -94,7 +98,7 @@ typedef struct {
   double   beta1, beta2, eps;      /* AdamW                                                  */
   double   weight_decay;    /* used by all replicas unless a HDET_CH_WD channel exists       */
   int32_t  precision;       /* HDET_FP32 or HDET_BF16_GEMM_FP32_MASTER                       */
-  int32_t  model_kind;      /* HDET_FLAT or HDET_MLP                                         */
+  int32_t  model_kind;      /* HDET_FLAT, HDET_MLP or HDET_TRANSFORMER                       */
   hdet_model_dims dims;
   int32_t  n_extra_channels;           /* 0..HDET_MAX_CH-1                                   */
   int32_t  reserved;
@@ -105,7 +109,11 @@ typedef struct {
 
 /* Caller-owned device buffers.  Planes are `plane_stride` elements apart; plane_stride >= P
  * and a multiple of 4, every pointer 16-byte aligned.  Parameter layout inside a plane for
- * HDET_MLP: [W_1 (d_out x d_in, row-major), b_1, W_2, b_2, ...].                            */
+ * HDET_MLP: [W_1 (d_out x d_in, row-major), b_1, W_2, b_2, ...].  For HDET_TRANSFORMER (all
+ * row-major): tok_emb [V][d], pos_emb [S][d], then per block ln1_g, ln1_b [d], w_qkv [3d][d],
+ * b_qkv [3d], w_o [d][d], b_o [d], ln2_g, ln2_b [d], w_1 [ff][d], b_1 [ff], w_2 [d][ff],
+ * b_2 [d], then lnf_g, lnf_b [d], w_head [V][d], b_head [V]; rows 0..d-1 of w_qkv give q,
+ * d..2d-1 k, 2d..3d-1 v and head h owns columns h*d/heads .. of each.                       */
 typedef struct {
   float*    params_dev;       /* [N][plane_stride] fp32 master parameters, updated in place  */
   float*    grads_dev;        /* [N][plane_stride] fp32; written by hdet_forward_backward;
@@ -154,9 +162,13 @@ int hdet_workspace_bytes(const hdet_config* cfg, int64_t plane_stride, size_t* p
 int hdet_create(const hdet_config* cfg, const hdet_buffers* buffers, hdet_handle** out);
 
 /* Forward, mean cross-entropy and backward of all N replicas on x_dev [N][B][d_in]
- * (fp32; rounded to bf16 on load in bf16 precision) and labels y_dev [N][B] int32
+ * (fp32; rounded to bf16 on load in bf16 precision) and labels y_dev [N][B] int32 -- for
+ * HDET_TRANSFORMER x_dev is token ids [N][B][S] int32 and y_dev the next-token targets
+ * [N][B][S] int32, the loss being the mean over the B*S positions
  * ("Forward + backward" of Algorithm 1; the loss is the one that Sec. 3.4 averages into
- * L_r).  Writes grads_dev, the per-replica losses of this step and adds them to L_acc.
+ * L_r).  With a HDET_CH_DROPOUT channel (Remark 1) replica r drops the two residual
+ * branches of every transformer block at its own rate; the mask is a pure function of
+ * (seed, step, replica, site, element) from Philox-4x32-10.  Writes grads_dev, the per-replica losses of this step and adds them to L_acc.
  * If losses_host is not NULL the call waits for the stream and copies the N losses there.
  * HDET_ESTATE for HDET_FLAT handles.                                                        */
 int hdet_forward_backward(hdet_handle* h, const void* x_dev, const int32_t* y_dev,

@@ -19,7 +19,7 @@ HDET_OK, HDET_EINVAL, HDET_ESTATE, HDET_EHIP = 0, -1, -2, -3
 HDET_SGDM, HDET_ADAMW = 0, 1
 HDET_GRAD_SHARED, HDET_GRAD_PER_REPLICA = 0, 1
 HDET_FP32, HDET_BF16_GEMM_FP32_MASTER = 0, 1
-HDET_FLAT, HDET_MLP = 0, 1
+HDET_FLAT, HDET_MLP, HDET_TRANSFORMER = 0, 1, 2
 HDET_CH_LR, HDET_CH_DROPOUT, HDET_CH_WD = 0, 1, 2
 HDET_FUSE_CONVERGE = 1
 
@@ -38,7 +38,9 @@ class hdet_channel(C.Structure):
 
 class hdet_model_dims(C.Structure):
     _fields_ = [("n_params", C.c_int64), ("n_layers", C.c_int32),
-                ("widths", C.c_int32 * (HDET_MAX_LAYERS + 1)), ("batch", C.c_int32)]
+                ("widths", C.c_int32 * (HDET_MAX_LAYERS + 1)), ("batch", C.c_int32),
+                ("n_blocks", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("d_ff", C.c_int32), ("seq_len", C.c_int32), ("vocab", C.c_int32)]
 
 
 class hdet_config(C.Structure):
@@ -157,7 +159,7 @@ def make_config(**kw) -> hdet_config:
     cfg.seed = 7
     widths = kw.pop("widths", None)
     extra = kw.pop("extra", None)
-    for key in ("n_params", "batch"):
+    for key in ("n_params", "batch", "n_blocks", "d_model", "n_heads", "d_ff", "seq_len", "vocab"):
         if key in kw:
             setattr(cfg.dims, key, kw.pop(key))
     if widths is not None:

@@ -63,6 +63,7 @@ void spread(int n, double alpha, double* rho) {
 
 int64_t param_count(const hdet_config& c) {
   if (c.model_kind == HDET_FLAT) return c.dims.n_params;
+  if (c.model_kind == HDET_TRANSFORMER) return hdet_tf_param_count(c);
   int64_t p = 0;
   for (int i = 0; i < c.dims.n_layers; ++i)
     p += (int64_t)c.dims.widths[i + 1] * c.dims.widths[i] + c.dims.widths[i + 1];
@@ -92,6 +93,9 @@ int validate(const hdet_config* c, std::string* why) {
     if (c->dims.batch < 1) return bad("batch must be >= 1");
     for (int i = 0; i <= c->dims.n_layers; ++i)
       if (c->dims.widths[i] < 1) return bad("layer widths must be >= 1");
+  } else if (c->model_kind == HDET_TRANSFORMER) {
+    const int rc = hdet_tf_validate(*c, why);
+    if (rc != HDET_OK) return rc;
   } else {
     return bad("unknown model_kind");
   }
@@ -154,10 +158,9 @@ int hdet_workspace_bytes(const hdet_config* cfg, int64_t plane_stride, size_t* p
   if (plane_set_bytes) *plane_set_bytes = elems * sizeof(float);
   if (shadow_bytes) *shadow_bytes = cfg->precision == HDET_BF16_GEMM_FP32_MASTER ? elems * sizeof(uint16_t) : 0;
   size_t ws = 0;
-  if (cfg->model_kind == HDET_MLP) {
-    rc = hdet_mlp_workspace_bytes(*cfg, &ws, &why);
-    if (rc != HDET_OK) return fail(nullptr, rc, why);
-  }
+  if (cfg->model_kind == HDET_MLP) rc = hdet_mlp_workspace_bytes(*cfg, &ws, &why);
+  if (cfg->model_kind == HDET_TRANSFORMER) rc = hdet_tf_workspace_bytes(*cfg, &ws, &why);
+  if (rc != HDET_OK) return fail(nullptr, rc, why);
   if (workspace_bytes) *workspace_bytes = ws;
   return HDET_OK;
 }
@@ -200,6 +203,8 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
   h->tune_variant = 0;
   h->tune_blocks = 0;
   h->mlp = nullptr;
+  h->tf = nullptr;
+  h->drop_channel = -1;
   h->ctrl_dev = nullptr;
   h->n_channels = 1 + cfg->n_extra_channels;
   h->wd_channel = -1;
@@ -213,6 +218,7 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
   for (int j = 0; j < cfg->n_extra_channels; ++j) {
     h->channels[j + 1] = cfg->extra[j];
     if (cfg->extra[j].kind == HDET_CH_WD) h->wd_channel = j + 1;
+    if (cfg->extra[j].kind == HDET_CH_DROPOUT) h->drop_channel = j + 1;
   }
 
   e = hipMalloc((void**)&h->ctrl_dev, sizeof(hdet_ctrl));
@@ -224,6 +230,10 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
   if (rc == HDET_OK && cfg->model_kind == HDET_MLP) {
     h->mlp = hdet_mlp_create(h->cfg, h->buf, &why);
     if (!h->mlp) { h->err = why; rc = HDET_EINVAL; }
+  }
+  if (rc == HDET_OK && cfg->model_kind == HDET_TRANSFORMER) {
+    h->tf = hdet_tf_create(h->cfg, h->buf, h->drop_channel, &why);
+    if (!h->tf) { h->err = why; rc = HDET_EINVAL; }
   }
   if (rc != HDET_OK) {
     g_create_error = h->err;
@@ -237,10 +247,11 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
 
 int hdet_forward_backward(hdet_handle* h, const void* x_dev, const int32_t* y_dev, float* losses_host) {
   if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
-  if (h->cfg.model_kind == HDET_FLAT || !h->mlp) return fail(h, HDET_ESTATE, "flat handles have no forward/backward");
+  if (h->cfg.model_kind == HDET_FLAT || (!h->mlp && !h->tf)) return fail(h, HDET_ESTATE, "flat handles have no forward/backward");
   if (!x_dev || !y_dev) return fail(h, HDET_EINVAL, "x_dev and y_dev are required");
   if (!aligned16(x_dev)) return fail(h, HDET_EINVAL, "x_dev must be 16-byte aligned");
-  hipError_t e = hdet_mlp_forward_backward(h->mlp, x_dev, y_dev, h->ctrl_dev, h->stream);
+  hipError_t e = h->tf ? hdet_tf_forward_backward(h->tf, (const int32_t*)x_dev, y_dev, h->ctrl_dev, (uint32_t)(h->t + 1), h->stream)
+                       : hdet_mlp_forward_backward(h->mlp, x_dev, y_dev, h->ctrl_dev, h->stream);
   if (e != hipSuccess) return hip_fail(h, e, "forward/backward kernels");
   if (losses_host) {
     e = hipMemcpyAsync(losses_host, h->ctrl_dev->l_step, sizeof(float) * h->cfg.n_replicas,
@@ -424,6 +435,7 @@ int hdet_destroy(hdet_handle* h) {
   hipError_t e = hipStreamSynchronize(h->stream);
   if (e != hipSuccess) rc = HDET_EHIP;
   if (h->mlp) hdet_mlp_destroy(h->mlp);
+  if (h->tf) hdet_tf_destroy(h->tf);
   if (h->ctrl_dev && hipFree(h->ctrl_dev) != hipSuccess) rc = HDET_EHIP;
   delete h;
   return rc;

@@ -122,9 +122,11 @@ template <bool A_KMAJOR, bool B_KMAJOR, int EPI, bool FAST>
 __global__ __launch_bounds__(256) void hdet_bgemm_kernel(const hdet_bgemm_args g) {
   __shared__ __attribute__((aligned(16))) uint16_t As[2][TILE_ELEMS];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[2][TILE_ELEMS];
-  const int z = blockIdx.z;
-  const uint16_t* A = g.a + (int64_t)z * g.a_bs;
-  const uint16_t* B = g.b + (int64_t)z * g.b_bs;
+  const hdet_batch_index bi = hdet_split_batch(blockIdx.z, g.n1, g.n2);
+  const int z = bi.z0;            // replica: bias and mask are per replica
+  const uint16_t* A = g.a + hdet_batch_offset(bi, g.a_s);
+  const uint16_t* B = g.b + hdet_batch_offset(bi, g.b_s);
+  const int64_t c_base = hdet_batch_offset(bi, g.c_s);
   const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -195,17 +197,22 @@ __global__ __launch_bounds__(256) void hdet_bgemm_kernel(const hdet_bgemm_args g
       const int col = n0 + wn + j * 32 + (lane & 31);
       if (col >= g.n) continue;
       float bias = 0.f;
-      if (EPI == HDET_EPI_BIAS_RELU_BF16 || EPI == HDET_EPI_BIAS_F32) bias = g.bias[(int64_t)z * g.bias_bs + col];
+      if (EPI == HDET_EPI_BIAS_RELU_BF16 || EPI == HDET_EPI_BIAS_F32 || EPI == HDET_EPI_BIAS_BF16)
+        bias = g.bias[(int64_t)z * g.bias_bs + col];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int row = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
         if (row >= g.m) continue;
         float v = acc[i][j][e];
-        const int64_t off = (int64_t)z * g.c_bs + (int64_t)row * g.ldc + col;
+        const int64_t off = c_base + (int64_t)row * g.ldc + col;
         if (EPI == HDET_EPI_F32) {
           reinterpret_cast<float*>(g.c)[off] = v;
         } else if (EPI == HDET_EPI_BIAS_F32) {
           reinterpret_cast<float*>(g.c)[off] = v + bias;
+        } else if (EPI == HDET_EPI_BF16) {
+          reinterpret_cast<uint16_t*>(g.c)[off] = f2bf(v);
+        } else if (EPI == HDET_EPI_BIAS_BF16) {
+          reinterpret_cast<uint16_t*>(g.c)[off] = f2bf(v + bias);
         } else if (EPI == HDET_EPI_BIAS_RELU_BF16) {
           v += bias;
           reinterpret_cast<uint16_t*>(g.c)[off] = f2bf(v > 0.f ? v : 0.f);
@@ -217,31 +224,40 @@ __global__ __launch_bounds__(256) void hdet_bgemm_kernel(const hdet_bgemm_args g
     }
 }
 
-static bool chunk_regular(const void* base, int64_t ld, int64_t bs, int chunk_extent) {
-  return (ld & 7) == 0 && (bs & 7) == 0 && (chunk_extent & 7) == 0 && (reinterpret_cast<uintptr_t>(base) & 15) == 0;
+static bool chunk_regular(const void* base, int64_t ld, const int64_t* bs, int chunk_extent) {
+  return (ld & 7) == 0 && ((bs[0] | bs[1] | bs[2]) & 7) == 0 && (chunk_extent & 7) == 0 &&
+         (reinterpret_cast<uintptr_t>(base) & 15) == 0;
 }
 
-hipError_t hdet_launch_bgemm(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi, int batch,
+hipError_t hdet_launch_bgemm(const hdet_bgemm_args& g_in, bool a_kmajor, bool b_kmajor, int epi, int batch,
                              hipStream_t s) {
+  hdet_bgemm_args g = g_in;
+  if (g.n1 < 1) g.n1 = 1;
+  if (g.n2 < 1) g.n2 = 1;
   dim3 grid((g.n + TN - 1) / TN, (g.m + TM - 1) / TM, batch);
   // a chunk is 8 elements along the operand's contiguous axis: k if k-major, else the row axis
-  const bool fast = chunk_regular(g.a, g.lda, g.a_bs, a_kmajor ? g.k : g.m) &&
-                    chunk_regular(g.b, g.ldb, g.b_bs, b_kmajor ? g.k : g.n);
+  const bool fast = chunk_regular(g.a, g.lda, g.a_s, a_kmajor ? g.k : g.m) &&
+                    chunk_regular(g.b, g.ldb, g.b_s, b_kmajor ? g.k : g.n);
 #define HDET_BGEMM(AK, BK, E)                                                                          \
   do {                                                                                                 \
     if (fast) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, true>), grid, dim3(256), 0, s, g);      \
     else hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, false>), grid, dim3(256), 0, s, g);          \
   } while (0)
-  if (a_kmajor && b_kmajor) {            // forward
-    if (epi == HDET_EPI_BIAS_RELU_BF16) HDET_BGEMM(true, true, HDET_EPI_BIAS_RELU_BF16);
-    else HDET_BGEMM(true, true, HDET_EPI_BIAS_F32);
-  } else if (a_kmajor && !b_kmajor) {    // dgrad
-    HDET_BGEMM(true, false, HDET_EPI_MASK_BF16);
-  } else if (!a_kmajor && !b_kmajor) {   // wgrad
-    HDET_BGEMM(false, false, HDET_EPI_F32);
-  } else {
-    return hipErrorInvalidValue;
+#define HDET_BGEMM_EPI(AK, BK)                                                                         \
+  switch (epi) {                                                                                       \
+    case HDET_EPI_F32: HDET_BGEMM(AK, BK, HDET_EPI_F32); break;                                        \
+    case HDET_EPI_BIAS_F32: HDET_BGEMM(AK, BK, HDET_EPI_BIAS_F32); break;                              \
+    case HDET_EPI_BIAS_RELU_BF16: HDET_BGEMM(AK, BK, HDET_EPI_BIAS_RELU_BF16); break;                  \
+    case HDET_EPI_MASK_BF16: HDET_BGEMM(AK, BK, HDET_EPI_MASK_BF16); break;                            \
+    case HDET_EPI_BF16: HDET_BGEMM(AK, BK, HDET_EPI_BF16); break;                                      \
+    case HDET_EPI_BIAS_BF16: HDET_BGEMM(AK, BK, HDET_EPI_BIAS_BF16); break;                            \
+    default: return hipErrorInvalidValue;                                                              \
   }
+  if (a_kmajor && b_kmajor) { HDET_BGEMM_EPI(true, true) }            // forward
+  else if (a_kmajor && !b_kmajor) { HDET_BGEMM_EPI(true, false) }     // dgrad
+  else if (!a_kmajor && !b_kmajor) { HDET_BGEMM_EPI(false, false) }   // wgrad
+  else return hipErrorInvalidValue;
+#undef HDET_BGEMM_EPI
 #undef HDET_BGEMM
   return hipGetLastError();
 }

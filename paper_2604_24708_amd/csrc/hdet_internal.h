@@ -90,19 +90,51 @@ hipError_t hdet_launch_shadow(const float* theta, uint16_t* shadow, int64_t n_pa
 hipError_t hdet_launch_controller(const hdet_controller_args& a, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
-// Replica-batched bf16 GEMM on the matrix cores (hdet_gemm_bf16.hip)
+// Replica-batched GEMMs.  The batch index z of a launch is split into up to three levels,
+//   z = (z0 * n1 + z1) * n2 + z2      (z0: replica; z1, z2: e.g. sequence and head),
+// and an operand's base offset is z0*s[0] + z1*s[1] + z2*s[2] elements.
 // ---------------------------------------------------------------------------------------
-enum { HDET_EPI_F32 = 0, HDET_EPI_BIAS_F32 = 1, HDET_EPI_BIAS_RELU_BF16 = 2, HDET_EPI_MASK_BF16 = 3 };
+struct hdet_batch_index { int z0, z1, z2; };
+__host__ __device__ __forceinline__ hdet_batch_index hdet_split_batch(int z, int n1, int n2) {
+  hdet_batch_index b;
+  b.z2 = z % n2;
+  const int t = z / n2;
+  b.z1 = t % n1;
+  b.z0 = t / n1;
+  return b;
+}
+__host__ __device__ __forceinline__ int64_t hdet_batch_offset(const hdet_batch_index& b, const int64_t* s) {
+  return (int64_t)b.z0 * s[0] + (int64_t)b.z1 * s[1] + (int64_t)b.z2 * s[2];
+}
+
+// fp32 GEMM with element strides (hdet_gemm_f32.hip): C(m,n) = sum_k A(m,k) B(k,n)
+enum { HDET_SEPI_NONE = 0, HDET_SEPI_BIAS = 1, HDET_SEPI_BIAS_RELU = 2, HDET_SEPI_MASK = 3 };
+struct hdet_sgemm_args {
+  const float* a; const float* b; float* c;
+  int m, n, k;
+  int n1, n2;                   // batch split (0 is read as 1)
+  int64_t a_rs, a_cs, a_s[3];   // A(m,k) = a[batch + m*a_rs + k*a_cs]
+  int64_t b_rs, b_cs, b_s[3];   // B(k,n) = b[batch + k*b_rs + n*b_cs]
+  int64_t c_rs, c_s[3];         // C(m,n) = c[batch + m*c_rs + n]
+  const float* bias; int64_t bias_bs;            // + bias[z0*bias_bs + n]
+  const float* mask; int64_t mask_rs, mask_bs;   // * (mask[z0*mask_bs + m*mask_rs + n] > 0)
+};
+hipError_t hdet_launch_sgemm(const hdet_sgemm_args& g, int epi, int batch, hipStream_t stream);
+
+// bf16 GEMM on the matrix cores (hdet_gemm_bf16.hip)
+enum { HDET_EPI_F32 = 0, HDET_EPI_BIAS_F32 = 1, HDET_EPI_BIAS_RELU_BF16 = 2, HDET_EPI_MASK_BF16 = 3,
+       HDET_EPI_BF16 = 4, HDET_EPI_BIAS_BF16 = 5 };
 
 struct hdet_bgemm_args {
   const uint16_t* a;       // bf16
   const uint16_t* b;       // bf16
   void* c;                 // fp32 or bf16, row-major [m][ldc]
   int m, n, k;
+  int n1, n2;              // batch split (0 is read as 1)
   int64_t lda, ldb, ldc;   // leading dimensions in elements
-  int64_t a_bs, b_bs, c_bs;            // replica strides in elements
-  const float* bias; int64_t bias_bs;  // bias[n] per replica
-  const uint16_t* mask; int64_t mask_ld, mask_bs;   // bf16 activations gating the gradient
+  int64_t a_s[3], b_s[3], c_s[3];      // batch strides in elements
+  const float* bias; int64_t bias_bs;  // bias[z0*bias_bs + n]
+  const uint16_t* mask; int64_t mask_ld, mask_bs;   // bf16 activations gating the gradient (per replica)
 };
 
 // a_kmajor: A(m,k) at a[m*lda + k], else at a[k*lda + m]; b_kmajor: B(k,n) at b[n*ldb + k], else
@@ -119,6 +151,19 @@ hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, 
 void hdet_mlp_destroy(hdet_mlp_plan* p);
 hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
                                      hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// Transformer forward/backward (hdet_transformer.hip)
+// ---------------------------------------------------------------------------------------
+struct hdet_tf_plan;
+int64_t hdet_tf_param_count(const hdet_config& cfg);
+int hdet_tf_validate(const hdet_config& cfg, std::string* err);
+int hdet_tf_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err);
+hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, int drop_channel, std::string* err);
+void hdet_tf_destroy(hdet_tf_plan* p);
+// `step`: the update this gradient is for (keys the dropout masks)
+hipError_t hdet_tf_forward_backward(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl,
+                                    uint32_t step, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
 // Host handle
@@ -139,5 +184,7 @@ struct hdet_handle {
   int32_t tune_variant, tune_blocks;
   int n_cu;
   hdet_mlp_plan* mlp;
+  hdet_tf_plan* tf;
+  int drop_channel;
   std::string err;
 };

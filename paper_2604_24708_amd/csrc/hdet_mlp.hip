@@ -19,88 +19,6 @@
 
 namespace {
 
-constexpr int BM = 64, BN = 64, BK = 16;
-
-struct gemm_args {
-  const float* a; const float* b; float* c;
-  int m, n, k;
-  int64_t a_rs, a_cs, a_bs;     // A(m,k) = a[z*a_bs + m*a_rs + k*a_cs]
-  int64_t b_rs, b_cs, b_bs;     // B(k,n) = b[z*b_bs + k*b_rs + n*b_cs]
-  int64_t c_rs, c_bs;           // C(m,n) = c[z*c_bs + m*c_rs + n]
-  const float* bias; int64_t bias_bs;   // + bias[z*bias_bs + n]            (EPI_BIAS*)
-  const float* mask; int64_t mask_rs, mask_bs;  // * (mask(m,n) > 0)       (EPI_MASK)
-};
-
-enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_RELU = 2, EPI_MASK = 3 };
-
-// C = A * B with fp32 accumulation; 64x64 tile per 256-thread block, 4x4 per thread.
-template <int EPI>
-__global__ __launch_bounds__(256) void sgemm_kernel(const gemm_args g) {
-  __shared__ float As[BK][BM + 4];
-  __shared__ float Bs[BK][BN + 4];
-  const int z = blockIdx.z;
-  const float* A = g.a + (int64_t)z * g.a_bs;
-  const float* B = g.b + (int64_t)z * g.b_bs;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int tid = threadIdx.x;
-  const int tx = tid & 15, ty = tid >> 4;
-  const bool a_kfast = g.a_cs == 1;      // consecutive threads walk the contiguous axis
-  const bool b_nfast = g.b_cs == 1;
-  float acc[4][4] = {};
-  for (int k0 = 0; k0 < g.k; k0 += BK) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int e = tid + i * 256;
-      const int mm = a_kfast ? e / BK : e % BM;
-      const int kk = a_kfast ? e % BK : e / BM;
-      const int gm = m0 + mm, gk = k0 + kk;
-      As[kk][mm] = (gm < g.m && gk < g.k) ? A[(int64_t)gm * g.a_rs + (int64_t)gk * g.a_cs] : 0.f;
-      const int nn = b_nfast ? e % BN : e / BK;
-      const int kb = b_nfast ? e / BN : e % BK;
-      const int gn = n0 + nn, gkb = k0 + kb;
-      Bs[kb][nn] = (gn < g.n && gkb < g.k) ? B[(int64_t)gkb * g.b_rs + (int64_t)gn * g.b_cs] : 0.f;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int kk = 0; kk < BK; ++kk) {
-      float av[4], bv[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { av[i] = As[kk][ty * 4 + i]; bv[i] = Bs[kk][tx * 4 + i]; }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
-    }
-    __syncthreads();
-  }
-  float* C = g.c + (int64_t)z * g.c_bs;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int gm = m0 + ty * 4 + i;
-    if (gm >= g.m) continue;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int gn = n0 + tx * 4 + j;
-      if (gn >= g.n) continue;
-      float v = acc[i][j];
-      if (EPI == EPI_BIAS || EPI == EPI_BIAS_RELU) v += g.bias[(int64_t)z * g.bias_bs + gn];
-      if (EPI == EPI_BIAS_RELU) v = v > 0.f ? v : 0.f;
-      if (EPI == EPI_MASK) v = g.mask[(int64_t)z * g.mask_bs + (int64_t)gm * g.mask_rs + gn] > 0.f ? v : 0.f;
-      C[(int64_t)gm * g.c_rs + gn] = v;
-    }
-  }
-}
-
-void launch_sgemm(const gemm_args& g, int epi, int batch, hipStream_t s) {
-  dim3 grid((g.n + BN - 1) / BN, (g.m + BM - 1) / BM, batch);
-  switch (epi) {
-    case EPI_BIAS: hipLaunchKernelGGL(sgemm_kernel<EPI_BIAS>, grid, dim3(256), 0, s, g); break;
-    case EPI_BIAS_RELU: hipLaunchKernelGGL(sgemm_kernel<EPI_BIAS_RELU>, grid, dim3(256), 0, s, g); break;
-    case EPI_MASK: hipLaunchKernelGGL(sgemm_kernel<EPI_MASK>, grid, dim3(256), 0, s, g); break;
-    default: hipLaunchKernelGGL(sgemm_kernel<EPI_NONE>, grid, dim3(256), 0, s, g); break;
-  }
-}
-
 __device__ __forceinline__ float as_float(float x) { return x; }
 __device__ __forceinline__ float as_float(uint16_t h) { return __uint_as_float((unsigned)h << 16); }
 __device__ __forceinline__ void put(float* p, float x) { *p = x; }
@@ -199,6 +117,19 @@ struct hdet_mlp_plan {
   bool bf16;
 };
 
+hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* labels, int rows, int classes, void* dlogits,
+                            float* row_loss, int n_replicas, hipStream_t s) {
+  const dim3 grid((rows + 3) / 4, n_replicas);
+  if (bf16) hipLaunchKernelGGL(xent_kernel<uint16_t>, grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
+  else hipLaunchKernelGGL(xent_kernel<float>, grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
+  return hipGetLastError();
+}
+
+hipError_t hdet_launch_loss_reduce(const float* row_loss, int rows, hdet_ctrl* ctrl, int n_replicas, hipStream_t s) {
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(n_replicas), dim3(256), 0, s, row_loss, rows, ctrl);
+  return hipGetLastError();
+}
+
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 int hdet_mlp_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err) {
@@ -264,13 +195,13 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
 
   // forward: Y = act(X W^T + b)
   for (int i = 0; i < L; ++i) {
-    gemm_args g = {};
-    g.a = (const float*)p->act[i]; g.a_rs = w[i]; g.a_cs = 1; g.a_bs = (int64_t)B * w[i];
-    g.b = theta + p->w_off[i]; g.b_rs = 1; g.b_cs = w[i]; g.b_bs = ps;      // B(k,n) = W[n][k]
-    g.c = i + 1 < L ? (float*)p->act[i + 1] : p->logits; g.c_rs = w[i + 1]; g.c_bs = (int64_t)B * w[i + 1];
+    hdet_sgemm_args g = {};
+    g.a = (const float*)p->act[i]; g.a_rs = w[i]; g.a_cs = 1; g.a_s[0] = (int64_t)B * w[i];
+    g.b = theta + p->w_off[i]; g.b_rs = 1; g.b_cs = w[i]; g.b_s[0] = ps;      // B(k,n) = W[n][k]
+    g.c = i + 1 < L ? (float*)p->act[i + 1] : p->logits; g.c_rs = w[i + 1]; g.c_s[0] = (int64_t)B * w[i + 1];
     g.m = B; g.n = w[i + 1]; g.k = w[i];
     g.bias = theta + p->b_off[i]; g.bias_bs = ps;
-    launch_sgemm(g, i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, N, s);
+    (void)hdet_launch_sgemm(g, i + 1 < L ? HDET_SEPI_BIAS_RELU : HDET_SEPI_BIAS, N, s);
   }
   // loss and dlogits
   float* dz = (float*)p->dz_a; float* dz_next = (float*)p->dz_b;
@@ -279,23 +210,23 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
   // backward
   for (int i = L - 1; i >= 0; --i) {
     // dW = dZ^T X
-    gemm_args g = {};
-    g.a = dz; g.a_rs = 1; g.a_cs = w[i + 1]; g.a_bs = (int64_t)B * w[i + 1];     // A(o,b) = dZ[b][o]
-    g.b = (const float*)p->act[i]; g.b_rs = w[i]; g.b_cs = 1; g.b_bs = (int64_t)B * w[i];   // B(b,k) = X[b][k]
-    g.c = grads + p->w_off[i]; g.c_rs = w[i]; g.c_bs = ps;
+    hdet_sgemm_args g = {};
+    g.a = dz; g.a_rs = 1; g.a_cs = w[i + 1]; g.a_s[0] = (int64_t)B * w[i + 1];     // A(o,b) = dZ[b][o]
+    g.b = (const float*)p->act[i]; g.b_rs = w[i]; g.b_cs = 1; g.b_s[0] = (int64_t)B * w[i];   // B(b,k) = X[b][k]
+    g.c = grads + p->w_off[i]; g.c_rs = w[i]; g.c_s[0] = ps;
     g.m = w[i + 1]; g.n = w[i]; g.k = B;
-    launch_sgemm(g, EPI_NONE, N, s);
+    (void)hdet_launch_sgemm(g, HDET_SEPI_NONE, N, s);
     hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 63) / 64, N), dim3(256), 0, s, dz, B, w[i + 1],
                        (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
     if (i > 0) {
       // dX = dZ W, masked by the ReLU of the layer below
-      gemm_args d = {};
-      d.a = dz; d.a_rs = w[i + 1]; d.a_cs = 1; d.a_bs = (int64_t)B * w[i + 1];
-      d.b = theta + p->w_off[i]; d.b_rs = w[i]; d.b_cs = 1; d.b_bs = ps;         // B(o,k) = W[o][k]
-      d.c = dz_next; d.c_rs = w[i]; d.c_bs = (int64_t)B * w[i];
+      hdet_sgemm_args d = {};
+      d.a = dz; d.a_rs = w[i + 1]; d.a_cs = 1; d.a_s[0] = (int64_t)B * w[i + 1];
+      d.b = theta + p->w_off[i]; d.b_rs = w[i]; d.b_cs = 1; d.b_s[0] = ps;         // B(o,k) = W[o][k]
+      d.c = dz_next; d.c_rs = w[i]; d.c_s[0] = (int64_t)B * w[i];
       d.m = B; d.n = w[i]; d.k = w[i + 1];
       d.mask = (const float*)p->act[i]; d.mask_rs = w[i]; d.mask_bs = (int64_t)B * w[i];
-      launch_sgemm(d, EPI_MASK, N, s);
+      (void)hdet_launch_sgemm(d, HDET_SEPI_MASK, N, s);
       float* t = dz; dz = dz_next; dz_next = t;
     }
   }
@@ -319,9 +250,9 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
 
   for (int i = 0; i < L; ++i) {                      // forward: Y = act(X W^T + b)
     hdet_bgemm_args g = {};
-    g.a = (const uint16_t*)p->act[i]; g.lda = w[i]; g.a_bs = (int64_t)B * w[i];
-    g.b = wbf + p->w_off[i]; g.ldb = w[i]; g.b_bs = ps;
-    g.c = i + 1 < L ? p->act[i + 1] : (void*)p->logits; g.ldc = w[i + 1]; g.c_bs = (int64_t)B * w[i + 1];
+    g.a = (const uint16_t*)p->act[i]; g.lda = w[i]; g.a_s[0] = (int64_t)B * w[i];
+    g.b = wbf + p->w_off[i]; g.ldb = w[i]; g.b_s[0] = ps;
+    g.c = i + 1 < L ? p->act[i + 1] : (void*)p->logits; g.ldc = w[i + 1]; g.c_s[0] = (int64_t)B * w[i + 1];
     g.m = B; g.n = w[i + 1]; g.k = w[i];
     g.bias = theta + p->b_off[i]; g.bias_bs = ps;
     e = hdet_launch_bgemm(g, true, true, i + 1 < L ? HDET_EPI_BIAS_RELU_BF16 : HDET_EPI_BIAS_F32, N, s);
@@ -332,9 +263,9 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   for (int i = L - 1; i >= 0; --i) {
     hdet_bgemm_args g = {};                          // dW = dZ^T X
-    g.a = dz; g.lda = w[i + 1]; g.a_bs = (int64_t)B * w[i + 1];               // A(o,b) = dZ[b][o]
-    g.b = (const uint16_t*)p->act[i]; g.ldb = w[i]; g.b_bs = (int64_t)B * w[i];   // B(b,k) = X[b][k]
-    g.c = grads + p->w_off[i]; g.ldc = w[i]; g.c_bs = ps;
+    g.a = dz; g.lda = w[i + 1]; g.a_s[0] = (int64_t)B * w[i + 1];               // A(o,b) = dZ[b][o]
+    g.b = (const uint16_t*)p->act[i]; g.ldb = w[i]; g.b_s[0] = (int64_t)B * w[i];   // B(b,k) = X[b][k]
+    g.c = grads + p->w_off[i]; g.ldc = w[i]; g.c_s[0] = ps;
     g.m = w[i + 1]; g.n = w[i]; g.k = B;
     e = hdet_launch_bgemm(g, false, false, HDET_EPI_F32, N, s);
     if (e != hipSuccess) return e;
@@ -342,9 +273,9 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
                        (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
     if (i > 0) {                                     // dX = dZ W, through the ReLU below
       hdet_bgemm_args d = {};
-      d.a = dz; d.lda = w[i + 1]; d.a_bs = (int64_t)B * w[i + 1];
-      d.b = wbf + p->w_off[i]; d.ldb = w[i]; d.b_bs = ps;                       // B(o,k) = W[o][k]
-      d.c = dz_next; d.ldc = w[i]; d.c_bs = (int64_t)B * w[i];
+      d.a = dz; d.lda = w[i + 1]; d.a_s[0] = (int64_t)B * w[i + 1];
+      d.b = wbf + p->w_off[i]; d.ldb = w[i]; d.b_s[0] = ps;                       // B(o,k) = W[o][k]
+      d.c = dz_next; d.ldc = w[i]; d.c_s[0] = (int64_t)B * w[i];
       d.m = B; d.n = w[i]; d.k = w[i + 1];
       d.mask = (const uint16_t*)p->act[i]; d.mask_ld = w[i]; d.mask_bs = (int64_t)B * w[i];
       e = hdet_launch_bgemm(d, true, false, HDET_EPI_MASK_BF16, N, s);

@@ -1,0 +1,538 @@
+// "Forward + backward" of Algorithm 1 for a decoder-only transformer, replica-batched: every
+// launch covers all N replicas (independent weight sets, the replica is the outermost batch
+// index of each GEMM and grid.y of each row/elementwise kernel).
+//
+// Model (what the benchmark configurations leave open is fixed here): pre-LayerNorm blocks,
+// learned positional embeddings, tanh-GELU MLP, causal softmax attention, biases on every
+// Linear, untied output head with bias, final LayerNorm, eps 1e-5, mean next-token
+// cross-entropy over all B*S positions.  Dropout (Remark 1: the dropout rate as an explored
+// hyperparameter) acts on the two residual branches of a block with keep-scaling 1/(1-p), the
+// rate being replica r's value of the dropout channel; the mask is regenerated in the backward
+// pass from Philox-4x32-10 keyed on (seed, step, replica, site, element), never stored.
+//
+// All matrix products go through the replica-batched GEMMs (matrix cores in bf16 precision,
+// LDS-tiled fp32 otherwise); attention is the unfused chain scores -> softmax -> P V with the
+// (replica, sequence, head) triple as the batch index.  Activations that go to memory are of
+// type T: float, or bfloat16 in mixed precision (logits, attention scores and LayerNorm
+// statistics stay fp32).
+
+#include <vector>
+
+#include "hdet_elem.h"
+#include "hdet_internal.h"
+
+namespace {
+
+constexpr float kLnEps = 1e-5f;
+constexpr uint32_t kDropStream = 0x44524F50u;   // "DROP"
+
+// ------------------------------------------------------------------------------------------
+// elementwise / row kernels; blockIdx.y = replica
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void embed_fwd_kernel(const float* theta, int64_t ps, int64_t tok_off, int64_t pos_off,
+                                                        const int32_t* ids, int M, int S, int d, T* x) {
+  const int r = blockIdx.y;
+  const float* tok = theta + (int64_t)r * ps + tok_off;
+  const float* pos = theta + (int64_t)r * ps + pos_off;
+  const int64_t n = (int64_t)M * d;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int m = (int)(i / d), c = (int)(i % d);
+    const int id = ids[(int64_t)r * M + m];
+    hdet_st(x + (int64_t)r * n + i, tok[(int64_t)id * d + c] + pos[(int64_t)(m % S) * d + c]);
+  }
+}
+
+// dtok[ids[m]] += dx[m], dpos[m % S] += dx[m]  (fp32 atomics; the two regions are zeroed first)
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_kernel(float* grads, int64_t ps, int64_t tok_off, int64_t pos_off,
+                                                        const int32_t* ids, int M, int S, int d, const T* dx) {
+  const int r = blockIdx.y;
+  float* tok = grads + (int64_t)r * ps + tok_off;
+  float* pos = grads + (int64_t)r * ps + pos_off;
+  const int64_t n = (int64_t)M * d;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int m = (int)(i / d), c = (int)(i % d);
+    const float g = hdet_ld(dx + (int64_t)r * n + i);
+    atomicAdd(tok + (int64_t)ids[(int64_t)r * M + m] * d + c, g);
+    atomicAdd(pos + (int64_t)(m % S) * d + c, g);
+  }
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(float* p, int64_t ps, int64_t off, int64_t n) {
+  float* q = p + (int64_t)blockIdx.y * ps + off;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) q[i] = 0.f;
+}
+
+// LayerNorm forward, one wavefront per row: two passes (mean, then variance about it).
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* x, const float* theta, int64_t ps, int64_t g_off,
+                                                     int64_t b_off, int M, int d, T* y, float* mean, float* rstd) {
+  const int r = blockIdx.y, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int64_t base = ((int64_t)r * M + row) * d;
+  const float* g = theta + (int64_t)r * ps + g_off;
+  const float* b = theta + (int64_t)r * ps + b_off;
+  float s = 0.f;
+  for (int c = lane; c < d; c += 64) s += hdet_ld(x + base + c);
+  const float mu = hdet_wave_sum(s) / (float)d;
+  float v = 0.f;
+  for (int c = lane; c < d; c += 64) { const float t = hdet_ld(x + base + c) - mu; v += t * t; }
+  const float rs = 1.f / sqrtf(hdet_wave_sum(v) / (float)d + kLnEps);
+  for (int c = lane; c < d; c += 64) hdet_st(y + base + c, (hdet_ld(x + base + c) - mu) * rs * g[c] + b[c]);
+  if (lane == 0) { mean[(int64_t)r * M + row] = mu; rstd[(int64_t)r * M + row] = rs; }
+}
+
+// dx = rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)) [+ resid], dxhat = dy * g
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
+                                                        const float* theta, int64_t ps, int64_t g_off, int M, int d,
+                                                        const T* resid, T* dx) {
+  const int r = blockIdx.y, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int64_t base = ((int64_t)r * M + row) * d;
+  const float* g = theta + (int64_t)r * ps + g_off;
+  const float mu = mean[(int64_t)r * M + row], rs = rstd[(int64_t)r * M + row];
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = lane; c < d; c += 64) {
+    const float dxh = hdet_ld(dy + base + c) * g[c];
+    s1 += dxh;
+    s2 += dxh * ((hdet_ld(x + base + c) - mu) * rs);
+  }
+  const float m1 = hdet_wave_sum(s1) / (float)d, m2 = hdet_wave_sum(s2) / (float)d;
+  for (int c = lane; c < d; c += 64) {
+    const float xh = (hdet_ld(x + base + c) - mu) * rs;
+    float v = rs * (hdet_ld(dy + base + c) * g[c] - m1 - xh * m2);
+    if (resid) v += hdet_ld(resid + base + c);
+    hdet_st(dx + base + c, v);
+  }
+}
+
+// Column reductions over the M rows: block = 64 columns x 16 row phases; thread (c, q) adds
+// rows q, q+16, ... in ascending order, the 16 partial sums are then added in the order q = 0..15.
+//   MODE 0: out[c]  = sum_m src[m][c]                                   (bias gradients)
+//   MODE 1: out[c]  = sum_m src[m][c] * xhat[m][c],  out2[c] = sum_m src[m][c]   (LayerNorm g, b)
+template <typename T, int MODE>
+__global__ __launch_bounds__(1024) void colsum_kernel(const T* src, int64_t src_rs, int64_t src_bs, int M, int cols,
+                                                      const T* x, const float* mean, const float* rstd,
+                                                      float* out, float* out2, int64_t out_bs) {
+  __shared__ float p1[16][64], p2[16][64];
+  const int r = blockIdx.y, c = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + c;
+  float s1 = 0.f, s2 = 0.f;
+  if (col < cols) {
+    for (int m = q; m < M; m += 16) {
+      const float v = hdet_ld(src + (int64_t)r * src_bs + (int64_t)m * src_rs + col);
+      if (MODE == 1) {
+        const float xh = (hdet_ld(x + ((int64_t)r * M + m) * cols + col) - mean[(int64_t)r * M + m]) * rstd[(int64_t)r * M + m];
+        s1 += v * xh;
+        s2 += v;
+      } else {
+        s1 += v;
+      }
+    }
+  }
+  p1[q][c] = s1; p2[q][c] = s2;
+  __syncthreads();
+  if (q == 0 && col < cols) {
+    float a = 0.f, b = 0.f;
+    for (int i = 0; i < 16; ++i) { a += p1[i][c]; b += p2[i][c]; }
+    out[(int64_t)r * out_bs + col] = a;
+    if (MODE == 1) out2[(int64_t)r * out_bs + col] = b;
+  }
+}
+
+// Causal softmax over scaled scores, one wavefront per query row i: keys j <= i.
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* scores, int64_t rows_total, int S, float scale, T* p) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows_total) return;
+  const int i = (int)(row % S);
+  const float* s = scores + row * S;
+  float mx = -INFINITY;
+  for (int j = lane; j <= i; j += 64) mx = fmaxf(mx, s[j] * scale);
+  mx = hdet_wave_max(mx);
+  float se = 0.f;
+  for (int j = lane; j <= i; j += 64) se += expf(s[j] * scale - mx);
+  const float inv = 1.f / hdet_wave_sum(se);
+  for (int j = lane; j < S; j += 64) hdet_st(p + row * S + j, j <= i ? expf(s[j] * scale - mx) * inv : 0.f);
+}
+
+// ds = p * (dp - sum_j dp_j p_j) * scale  (zero above the diagonal, where p = 0)
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* dp, const T* p, int64_t rows_total, int S,
+                                                          float scale, T* ds) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows_total) return;
+  const int i = (int)(row % S);
+  float dot = 0.f;
+  for (int j = lane; j <= i; j += 64) dot += dp[row * S + j] * hdet_ld(p + row * S + j);
+  dot = hdet_wave_sum(dot);
+  for (int j = lane; j < S; j += 64)
+    hdet_st(ds + row * S + j, j <= i ? hdet_ld(p + row * S + j) * (dp[row * S + j] - dot) * scale : 0.f);
+}
+
+__device__ __forceinline__ float gelu_tanh(float z) {
+  const float c = 0.7978845608028654f;
+  return 0.5f * z * (1.f + tanhf(c * (z + 0.044715f * z * z * z)));
+}
+__device__ __forceinline__ float gelu_tanh_grad(float z) {
+  const float c = 0.7978845608028654f;
+  const float t = tanhf(c * (z + 0.044715f * z * z * z));
+  return 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * z * z);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_fwd_kernel(const T* z, T* f, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    hdet_st(f + i, gelu_tanh(hdet_ld(z + i)));
+}
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* df, const T* z, T* dz, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    hdet_st(dz + i, hdet_ld(df + i) * gelu_tanh_grad(hdet_ld(z + i)));
+}
+
+// Dropout of a residual branch.  Element e of the replica's [M][d] tensor is kept iff word
+// (e mod 4) of philox(counter = (e div 4, step, replica * 65536 + site, kDropStream), key = seed)
+// is >= floor(p * 2^32).  A thread handles the four elements of one Philox block.
+struct drop_args {
+  const hdet_ctrl* ctrl;
+  int channel;          // dropout channel index or -1 (no dropout)
+  uint32_t step, seed_lo, seed_hi;
+  int site;
+};
+
+__device__ __forceinline__ void drop_setup(const drop_args& da, int r, uint32_t* thresh, float* keep_scale) {
+  float p = 0.f;
+  if (da.channel >= 0) p = (float)hdet_channel_value(da.ctrl, da.channel, r, 0.0);
+  *thresh = (uint32_t)floor((double)p * 4294967296.0);
+  *keep_scale = 1.f / (1.f - p);
+}
+
+// out = x + drop(branch)            (ADD)        forward residual add
+// out = drop'(branch) = branch * keep / (1-p)    backward through the dropout
+template <typename T, bool ADD>
+__global__ __launch_bounds__(256) void dropout_kernel(const T* x, const T* branch, T* out, int64_t n, const drop_args da) {
+  const int r = blockIdx.y;
+  uint32_t thresh; float ks;
+  drop_setup(da, r, &thresh, &ks);
+  const int64_t nblk = n >> 2;
+  for (int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x; b < nblk; b += (int64_t)gridDim.x * 256) {
+    hdet_philox4 w = {{0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu}};
+    if (thresh != 0u)
+      w = hdet_philox4x32_10((uint32_t)b, da.step, (uint32_t)r * 65536u + (uint32_t)da.site, kDropStream, da.seed_lo, da.seed_hi);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t i = (int64_t)r * n + (b << 2) + j;
+      float v = hdet_ld(branch + i);
+      if (thresh != 0u) v = w.x[j] >= thresh ? v * ks : 0.f;
+      if (ADD) v += hdet_ld(x + i);
+      hdet_st(out + i, v);
+    }
+  }
+}
+
+int grid_for(int64_t n) { int64_t b = (n + 255) / 256; return (int)(b > 8192 ? 8192 : (b < 1 ? 1 : b)); }
+
+}  // namespace
+
+// xent and loss reduction live with the MLP path
+hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* labels, int rows, int classes, void* dlogits,
+                            float* row_loss, int n_replicas, hipStream_t s);
+hipError_t hdet_launch_loss_reduce(const float* row_loss, int rows, hdet_ctrl* ctrl, int n_replicas, hipStream_t s);
+
+struct tf_block_off { int64_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_1, b_1, w_2, b_2; };
+
+struct hdet_tf_plan {
+  hdet_config cfg;
+  hdet_buffers buf;
+  bool bf16;
+  int N, B, S, M, d, nh, dh, ff, V, L;
+  int drop_channel;
+  int64_t tok, pos, lnf_g, lnf_b, w_head, b_head;
+  std::vector<tf_block_off> blk;
+  // activations (type T), per replica sizes in elements
+  std::vector<char*> x_in, x_mid, h1, h2, qkv, p, a, z, f;   // [L] (+1 for x_in)
+  std::vector<float*> st1_mean, st1_rstd, st2_mean, st2_rstd;
+  char *hf, *tmp_d, *dxa, *dxb, *dtmp, *dtmp2, *dff, *dqkv, *ds, *dlogits;
+  float *stf_mean, *stf_rstd, *scores, *logits, *row_loss;
+};
+
+static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Walks the workspace layout; with base == nullptr only the size is computed.
+static size_t tf_carve(hdet_tf_plan* p, char* base) {
+  const size_t e = p->bf16 ? 2 : 4;
+  const size_t N = p->N, M = p->M, d = p->d, ff = p->ff, V = p->V, S = p->S;
+  const size_t heads = (size_t)p->B * p->nh;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* q = base ? base + off : nullptr; off += al(bytes); return q; };
+  const int L = p->L;
+  p->x_in.assign(L + 1, nullptr); p->x_mid.assign(L, nullptr); p->h1.assign(L, nullptr); p->h2.assign(L, nullptr);
+  p->qkv.assign(L, nullptr); p->p.assign(L, nullptr); p->a.assign(L, nullptr); p->z.assign(L, nullptr); p->f.assign(L, nullptr);
+  p->st1_mean.assign(L, nullptr); p->st1_rstd.assign(L, nullptr); p->st2_mean.assign(L, nullptr); p->st2_rstd.assign(L, nullptr);
+  for (int l = 0; l <= L; ++l) p->x_in[l] = take(N * M * d * e);
+  for (int l = 0; l < L; ++l) {
+    p->x_mid[l] = take(N * M * d * e); p->h1[l] = take(N * M * d * e); p->h2[l] = take(N * M * d * e);
+    p->qkv[l] = take(N * M * 3 * d * e); p->p[l] = take(N * heads * S * S * e); p->a[l] = take(N * M * d * e);
+    p->z[l] = take(N * M * ff * e); p->f[l] = take(N * M * ff * e);
+    p->st1_mean[l] = (float*)take(N * M * 4); p->st1_rstd[l] = (float*)take(N * M * 4);
+    p->st2_mean[l] = (float*)take(N * M * 4); p->st2_rstd[l] = (float*)take(N * M * 4);
+  }
+  p->hf = take(N * M * d * e); p->tmp_d = take(N * M * d * e);
+  p->dxa = take(N * M * d * e); p->dxb = take(N * M * d * e); p->dtmp = take(N * M * d * e); p->dtmp2 = take(N * M * d * e);
+  p->dff = take(N * M * ff * e); p->dqkv = take(N * M * 3 * d * e); p->ds = take(N * heads * S * S * e);
+  p->dlogits = take(N * M * V * e);
+  p->stf_mean = (float*)take(N * M * 4); p->stf_rstd = (float*)take(N * M * 4);
+  p->scores = (float*)take(N * heads * S * S * 4); p->logits = (float*)take(N * M * V * 4);
+  p->row_loss = (float*)take(N * M * 4);
+  return off;
+}
+
+static void tf_dims(hdet_tf_plan* p, const hdet_config& cfg) {
+  p->cfg = cfg;
+  p->bf16 = cfg.precision == HDET_BF16_GEMM_FP32_MASTER;
+  p->N = cfg.n_replicas; p->B = cfg.dims.batch; p->S = cfg.dims.seq_len; p->M = p->B * p->S;
+  p->d = cfg.dims.d_model; p->nh = cfg.dims.n_heads; p->dh = p->d / p->nh; p->ff = cfg.dims.d_ff;
+  p->V = cfg.dims.vocab; p->L = cfg.dims.n_blocks;
+}
+
+int64_t hdet_tf_param_count(const hdet_config& cfg) {
+  const int64_t d = cfg.dims.d_model, ff = cfg.dims.d_ff, V = cfg.dims.vocab, S = cfg.dims.seq_len, L = cfg.dims.n_blocks;
+  return V * d + S * d + L * (2 * d + 3 * d * d + 3 * d + d * d + d + 2 * d + ff * d + ff + d * ff + d) + 2 * d + V * d + V;
+}
+
+int hdet_tf_validate(const hdet_config& cfg, std::string* err) {
+  const hdet_model_dims& m = cfg.dims;
+  if (m.n_blocks < 1 || m.n_blocks > 64 || m.d_model < 4 || m.n_heads < 1 || m.d_ff < 1 || m.seq_len < 1 || m.vocab < 2 || m.batch < 1) {
+    *err = "transformer dimensions out of range"; return HDET_EINVAL;
+  }
+  if (m.d_model % m.n_heads != 0) { *err = "d_model must be a multiple of n_heads"; return HDET_EINVAL; }
+  if (m.d_model % 4 != 0) { *err = "d_model must be a multiple of 4"; return HDET_EINVAL; }
+  return HDET_OK;
+}
+
+int hdet_tf_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err) {
+  int rc = hdet_tf_validate(cfg, err);
+  if (rc != HDET_OK) return rc;
+  hdet_tf_plan p;
+  tf_dims(&p, cfg);
+  *bytes = tf_carve(&p, nullptr);
+  return HDET_OK;
+}
+
+hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, int drop_channel, std::string* err) {
+  if (hdet_tf_validate(cfg, err) != HDET_OK) return nullptr;
+  hdet_tf_plan* p = new hdet_tf_plan();
+  tf_dims(p, cfg);
+  p->buf = buf;
+  p->drop_channel = drop_channel;
+  const size_t need = tf_carve(p, nullptr);
+  if (!buf.workspace_dev || buf.workspace_bytes < need) { *err = "workspace_dev is too small"; delete p; return nullptr; }
+  tf_carve(p, (char*)buf.workspace_dev);
+  const int64_t d = p->d, ff = p->ff, V = p->V, S = p->S;
+  int64_t off = 0;
+  p->tok = off; off += V * d;
+  p->pos = off; off += S * d;
+  for (int l = 0; l < p->L; ++l) {
+    tf_block_off b;
+    b.ln1_g = off; off += d; b.ln1_b = off; off += d;
+    b.w_qkv = off; off += 3 * d * d; b.b_qkv = off; off += 3 * d;
+    b.w_o = off; off += d * d; b.b_o = off; off += d;
+    b.ln2_g = off; off += d; b.ln2_b = off; off += d;
+    b.w_1 = off; off += ff * d; b.b_1 = off; off += ff;
+    b.w_2 = off; off += d * ff; b.b_2 = off; off += d;
+    p->blk.push_back(b);
+  }
+  p->lnf_g = off; off += d; p->lnf_b = off; off += d;
+  p->w_head = off; off += V * d; p->b_head = off; off += V;
+  return p;
+}
+
+void hdet_tf_destroy(hdet_tf_plan* p) { delete p; }
+
+namespace {
+
+enum { NT = 0, NN = 1, TN = 2 };      // forward / dgrad / wgrad operand orders (see the GEMM files)
+
+struct mat { const void* p; int64_t ld; int64_t s[3]; };
+
+// C = A B in the given operand order; the output is of the activation type (act_out) or
+// fp32; bias (fp32, per replica) is optional.  Element offsets inside `p` are in elements of
+// the operand's own type.
+template <typename T>
+hipError_t gemm(const hdet_tf_plan* pl, int form, mat A, mat B, void* c, int64_t ldc, const int64_t* c_s, bool act_out,
+                int m, int n, int k, int n1, int n2, const float* bias, int64_t bias_bs, hipStream_t s) {
+  const int batch = pl->N * (n1 < 1 ? 1 : n1) * (n2 < 1 ? 1 : n2);
+  if (sizeof(T) == 2) {
+    hdet_bgemm_args g = {};
+    g.a = (const uint16_t*)A.p; g.b = (const uint16_t*)B.p; g.c = c;
+    g.m = m; g.n = n; g.k = k; g.n1 = n1; g.n2 = n2;
+    g.lda = A.ld; g.ldb = B.ld; g.ldc = ldc;
+    for (int i = 0; i < 3; ++i) { g.a_s[i] = A.s[i]; g.b_s[i] = B.s[i]; g.c_s[i] = c_s[i]; }
+    g.bias = bias; g.bias_bs = bias_bs;
+    const int epi = act_out ? (bias ? HDET_EPI_BIAS_BF16 : HDET_EPI_BF16) : (bias ? HDET_EPI_BIAS_F32 : HDET_EPI_F32);
+    return hdet_launch_bgemm(g, form != TN, form == NT, epi, batch, s);
+  }
+  hdet_sgemm_args g = {};
+  g.a = (const float*)A.p; g.b = (const float*)B.p; g.c = (float*)c;
+  g.m = m; g.n = n; g.k = k; g.n1 = n1; g.n2 = n2;
+  if (form == TN) { g.a_rs = 1; g.a_cs = A.ld; } else { g.a_rs = A.ld; g.a_cs = 1; }
+  if (form == NT) { g.b_rs = 1; g.b_cs = B.ld; } else { g.b_rs = B.ld; g.b_cs = 1; }
+  g.c_rs = ldc;
+  for (int i = 0; i < 3; ++i) { g.a_s[i] = A.s[i]; g.b_s[i] = B.s[i]; g.c_s[i] = c_s[i]; }
+  g.bias = bias; g.bias_bs = bias_bs;
+  return hdet_launch_sgemm(g, bias ? HDET_SEPI_BIAS : HDET_SEPI_NONE, batch, s);
+}
+
+#define TF_CHECK(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
+
+template <typename T>
+hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl, uint32_t step, hipStream_t s) {
+  const int N = p->N, M = p->M, S = p->S, d = p->d, ff = p->ff, V = p->V, L = p->L, nh = p->nh, dh = p->dh, B = p->B;
+  const int64_t ps = p->buf.plane_stride;
+  const float* theta = p->buf.params_dev;
+  const T* wts = sizeof(T) == 2 ? (const T*)p->buf.params_bf16_dev : (const T*)p->buf.params_dev;
+  float* grads = p->buf.grads_dev;
+  const float scale = 1.f / sqrtf((float)dh);
+  const int64_t heads_rows = (int64_t)N * B * nh * S;
+  const dim3 rows4((M + 3) / 4, N);
+  const int64_t nd = (int64_t)M * d, nff = (int64_t)M * ff;
+  drop_args da = {ctrl, p->drop_channel, step, (uint32_t)(p->cfg.seed & 0xffffffffu), (uint32_t)(p->cfg.seed >> 32), 0};
+  const bool drop = p->drop_channel >= 0;
+
+  // batch strides: activations [N][M][w]; weights per replica plane; attention operands per (replica, sequence, head)
+  auto act = [&](const void* q, int w) { mat t = {q, w, {(int64_t)M * w, 0, 0}}; return t; };
+  auto wt = [&](int64_t off, int ld) { mat t = {wts + off, ld, {ps, 0, 0}}; return t; };
+  auto qkv_part = [&](const void* base, int part) {      // q, k or v of head z2 in sequence z1: [S][dh], ld 3d
+    mat t = {(const T*)base + (int64_t)part * d, 3 * (int64_t)d, {(int64_t)M * 3 * d, (int64_t)S * 3 * d, dh}};
+    return t;
+  };
+  auto head_sq = [&](const void* base) {                  // [S][S] matrix of (replica, sequence, head)
+    mat t = {base, S, {(int64_t)B * nh * S * S, (int64_t)nh * S * S, (int64_t)S * S}};
+    return t;
+  };
+  auto head_cols = [&](const void* base) {                // columns of head z2 inside [M][d]
+    mat t = {base, d, {(int64_t)M * d, (int64_t)S * d, dh}};
+    return t;
+  };
+  const int64_t act_d[3] = {(int64_t)M * d, 0, 0}, act_3d[3] = {(int64_t)M * 3 * d, 0, 0}, act_ff[3] = {(int64_t)M * ff, 0, 0},
+                act_v[3] = {(int64_t)M * V, 0, 0}, plane[3] = {ps, 0, 0};
+
+  // ---- forward ------------------------------------------------------------------------
+  hipLaunchKernelGGL(embed_fwd_kernel<T>, dim3(grid_for(nd), N), dim3(256), 0, s, theta, ps, p->tok, p->pos, ids, M, S, d, (T*)p->x_in[0]);
+  for (int l = 0; l < L; ++l) {
+    const tf_block_off& o = p->blk[l];
+    hipLaunchKernelGGL(ln_fwd_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->x_in[l], theta, ps, o.ln1_g, o.ln1_b, M, d,
+                       (T*)p->h1[l], p->st1_mean[l], p->st1_rstd[l]);
+    TF_CHECK(gemm<T>(p, NT, act(p->h1[l], d), wt(o.w_qkv, d), p->qkv[l], 3 * d, act_3d, true, M, 3 * d, d, 1, 1, theta + o.b_qkv, ps, s));
+    {   // scores = q k^T per (replica, sequence, head)
+      const mat sc = head_sq(p->scores);
+      TF_CHECK(gemm<T>(p, NT, qkv_part(p->qkv[l], 0), qkv_part(p->qkv[l], 1), p->scores, S, sc.s, false, S, S, dh, B, nh, nullptr, 0, s));
+    }
+    hipLaunchKernelGGL(softmax_fwd_kernel<T>, dim3((unsigned)((heads_rows + 3) / 4)), dim3(256), 0, s, p->scores, heads_rows, S, scale, (T*)p->p[l]);
+    {   // a = p v
+      const mat ac = head_cols(p->a[l]);
+      TF_CHECK(gemm<T>(p, NN, head_sq(p->p[l]), qkv_part(p->qkv[l], 2), p->a[l], d, ac.s, true, S, dh, S, B, nh, nullptr, 0, s));
+    }
+    TF_CHECK(gemm<T>(p, NT, act(p->a[l], d), wt(o.w_o, d), p->tmp_d, d, act_d, true, M, d, d, 1, 1, theta + o.b_o, ps, s));
+    da.site = 2 * l;
+    hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_in[l], (const T*)p->tmp_d, (T*)p->x_mid[l], nd, da);
+    hipLaunchKernelGGL(ln_fwd_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->x_mid[l], theta, ps, o.ln2_g, o.ln2_b, M, d,
+                       (T*)p->h2[l], p->st2_mean[l], p->st2_rstd[l]);
+    TF_CHECK(gemm<T>(p, NT, act(p->h2[l], d), wt(o.w_1, d), p->z[l], ff, act_ff, true, M, ff, d, 1, 1, theta + o.b_1, ps, s));
+    hipLaunchKernelGGL(gelu_fwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->z[l], (T*)p->f[l], (int64_t)N * nff);
+    TF_CHECK(gemm<T>(p, NT, act(p->f[l], ff), wt(o.w_2, ff), p->tmp_d, d, act_d, true, M, d, ff, 1, 1, theta + o.b_2, ps, s));
+    da.site = 2 * l + 1;
+    hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_mid[l], (const T*)p->tmp_d, (T*)p->x_in[l + 1], nd, da);
+  }
+  hipLaunchKernelGGL(ln_fwd_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->x_in[L], theta, ps, p->lnf_g, p->lnf_b, M, d,
+                     (T*)p->hf, p->stf_mean, p->stf_rstd);
+  TF_CHECK(gemm<T>(p, NT, act(p->hf, d), wt(p->w_head, d), p->logits, V, act_v, false, M, V, d, 1, 1, theta + p->b_head, ps, s));
+  TF_CHECK(hdet_launch_xent(sizeof(T) == 2, p->logits, targets, M, V, p->dlogits, p->row_loss, N, s));
+  TF_CHECK(hdet_launch_loss_reduce(p->row_loss, M, ctrl, N, s));
+
+  // ---- backward -----------------------------------------------------------------------
+  auto colsum = [&](const void* src, int cols, int64_t out_off) {
+    hipLaunchKernelGGL((colsum_kernel<T, 0>), dim3((cols + 63) / 64, N), dim3(1024), 0, s, (const T*)src, (int64_t)cols, (int64_t)M * cols, M, cols,
+                       (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, grads + out_off, (float*)nullptr, ps);
+  };
+  auto ln_params = [&](const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off, int64_t b_off) {
+    hipLaunchKernelGGL((colsum_kernel<T, 1>), dim3((d + 63) / 64, N), dim3(1024), 0, s, (const T*)dy, (int64_t)d, (int64_t)M * d, M, d,
+                       (const T*)x, mean, rstd, grads + g_off, grads + b_off, ps);
+  };
+  auto wgrad = [&](const void* dy, int wy, const void* x, int wx, int64_t w_off) {      // dW[wy][wx] = dy^T x
+    return gemm<T>(p, TN, act(dy, wy), act(x, wx), grads + w_off, wx, plane, false, wy, wx, M, 1, 1, nullptr, 0, s);
+  };
+
+  TF_CHECK(wgrad(p->dlogits, V, p->hf, d, p->w_head));
+  colsum(p->dlogits, V, p->b_head);
+  TF_CHECK(gemm<T>(p, NN, act(p->dlogits, V), wt(p->w_head, d), p->dtmp, d, act_d, true, M, d, V, 1, 1, nullptr, 0, s));
+  ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b);
+  hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->dtmp, (const T*)p->x_in[L], p->stf_mean, p->stf_rstd,
+                     theta, ps, p->lnf_g, M, d, (const T*)nullptr, (T*)p->dxa);
+  for (int l = L - 1; l >= 0; --l) {
+    const tf_block_off& o = p->blk[l];
+    // MLP branch: x_out = x_mid + drop(y)
+    const void* dy = p->dxa;
+    if (drop) {
+      da.site = 2 * l + 1;
+      hipLaunchKernelGGL((dropout_kernel<T, false>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)nullptr, (const T*)p->dxa, (T*)p->dtmp2, nd, da);
+      dy = p->dtmp2;
+    }
+    TF_CHECK(wgrad(dy, d, p->f[l], ff, o.w_2));
+    colsum(dy, d, o.b_2);
+    TF_CHECK(gemm<T>(p, NN, act(dy, d), wt(o.w_2, ff), p->dff, ff, act_ff, true, M, ff, d, 1, 1, nullptr, 0, s));
+    hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->dff, (const T*)p->z[l], (T*)p->dff, (int64_t)N * nff);
+    TF_CHECK(wgrad(p->dff, ff, p->h2[l], d, o.w_1));
+    colsum(p->dff, ff, o.b_1);
+    TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
+    ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b);
+    hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->dtmp, (const T*)p->x_mid[l], p->st2_mean[l], p->st2_rstd[l],
+                       theta, ps, o.ln2_g, M, d, (const T*)p->dxa, (T*)p->dxb);
+    // attention branch: x_mid = x_in + drop(o)
+    const void* dob = p->dxb;
+    if (drop) {
+      da.site = 2 * l;
+      hipLaunchKernelGGL((dropout_kernel<T, false>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)nullptr, (const T*)p->dxb, (T*)p->dtmp2, nd, da);
+      dob = p->dtmp2;
+    }
+    TF_CHECK(wgrad(dob, d, p->a[l], d, o.w_o));
+    colsum(dob, d, o.b_o);
+    TF_CHECK(gemm<T>(p, NN, act(dob, d), wt(o.w_o, d), p->dtmp, d, act_d, true, M, d, d, 1, 1, nullptr, 0, s));   // da
+    {
+      const mat sc = head_sq(p->scores);
+      const mat dq = qkv_part(p->dqkv, 0), dk = qkv_part(p->dqkv, 1), dv = qkv_part(p->dqkv, 2);
+      // dp = da v^T
+      TF_CHECK(gemm<T>(p, NT, head_cols(p->dtmp), qkv_part(p->qkv[l], 2), p->scores, S, sc.s, false, S, S, dh, B, nh, nullptr, 0, s));
+      // dv = p^T da
+      TF_CHECK(gemm<T>(p, TN, head_sq(p->p[l]), head_cols(p->dtmp), (void*)dv.p, 3 * d, dv.s, true, S, dh, S, B, nh, nullptr, 0, s));
+      hipLaunchKernelGGL(softmax_bwd_kernel<T>, dim3((unsigned)((heads_rows + 3) / 4)), dim3(256), 0, s, p->scores, (const T*)p->p[l], heads_rows, S, scale, (T*)p->ds);
+      // dq = ds k,  dk = ds^T q
+      TF_CHECK(gemm<T>(p, NN, head_sq(p->ds), qkv_part(p->qkv[l], 1), (void*)dq.p, 3 * d, dq.s, true, S, dh, S, B, nh, nullptr, 0, s));
+      TF_CHECK(gemm<T>(p, TN, head_sq(p->ds), qkv_part(p->qkv[l], 0), (void*)dk.p, 3 * d, dk.s, true, S, dh, S, B, nh, nullptr, 0, s));
+    }
+    TF_CHECK(wgrad(p->dqkv, 3 * d, p->h1[l], d, o.w_qkv));
+    colsum(p->dqkv, 3 * d, o.b_qkv);
+    TF_CHECK(gemm<T>(p, NN, act(p->dqkv, 3 * d), wt(o.w_qkv, d), p->dtmp, d, act_d, true, M, d, 3 * d, 1, 1, nullptr, 0, s));
+    ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b);
+    hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->dtmp, (const T*)p->x_in[l], p->st1_mean[l], p->st1_rstd[l],
+                       theta, ps, o.ln1_g, M, d, (const T*)p->dxb, (T*)p->dxa);
+  }
+  const int64_t emb = (int64_t)(V + S) * d;      // tok_emb and pos_emb are adjacent at the head of the plane
+  hipLaunchKernelGGL(zero_kernel, dim3(grid_for(emb), N), dim3(256), 0, s, grads, ps, p->tok, emb);
+  hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3(grid_for(nd), N), dim3(256), 0, s, grads, ps, p->tok, p->pos, ids, M, S, d, (const T*)p->dxa);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t hdet_tf_forward_backward(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl,
+                                    uint32_t step, hipStream_t s) {
+  return p->bf16 ? run<uint16_t>(p, ids, targets, ctrl, step, s) : run<float>(p, ids, targets, ctrl, step, s);
+}

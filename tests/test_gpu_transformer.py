@@ -1,0 +1,181 @@
+"""Parity of the transformer forward/backward (and of the whole HDET loop on it) between the
+HIP path and the CPU oracle: full precision element-wise, mixed precision by loss curve."""
+import numpy as np
+import pytest
+import torch
+
+import hdet_inputs as I
+import paper_2604_24708_amd as H
+from harness import check_state, library_config, oracle_config, rel_err
+from oracle import hdet_oracle as O
+from oracle import transformer_oracle as T
+
+pytestmark = pytest.mark.gpu
+
+TINY = dict(n_blocks=2, d_model=16, n_heads=4, d_ff=40, seq_len=6, vocab=29)
+SMALL = dict(n_blocks=2, d_model=64, n_heads=4, d_ff=256, seq_len=32, vocab=512)      # several tiles
+ODD = dict(n_blocks=1, d_model=24, n_heads=3, d_ff=50, seq_len=70, vocab=131)        # ragged everywhere
+
+
+def norm_err(a, b):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def base(**kw):
+    d = dict(n_replicas=3, total_steps=12, sync_interval=4, warm_steps=4, lr_max=0.02, alpha=0.2,
+             autolr_enabled=True, optimizer=O.SGDM, momentum=0.9, weight_decay=0.0,
+             grad_mode=O.GRAD_PER_REPLICA, seed=I.SEED_PERM)
+    d.update(kw)
+    return d
+
+
+class TfRun:
+    def __init__(self, d, cfg, batch, bf16=False):
+        self.d, self.cfg, self.batch, self.bf16 = d, cfg, batch, bf16
+        self.n = n = d["n_replicas"]
+        self.P = P = I.transformer_param_count(cfg)
+        self.stride = (P + 3) // 4 * 4
+        th0 = I.transformer_init(n, cfg, I.SEED_INIT, std=0.1, bias_std=0.05)
+        self.orc = O.HDETOracle(oracle_config(d), th0)
+        dev = "cuda:0"
+        host = np.zeros((n, self.stride), np.float32)
+        host[:, :P] = th0
+        self.theta = torch.from_numpy(host).to(dev)
+        self.m, self.v = torch.zeros_like(self.theta), torch.zeros_like(self.theta)
+        self.g = torch.full_like(self.theta, 7.0)        # stale values must all be overwritten
+        self.shadow = torch.zeros((n, self.stride), dtype=torch.bfloat16, device=dev) if bf16 else None
+        lc = library_config(d, model_kind=H.HDET_TRANSFORMER, batch=batch,
+                            precision=H.HDET_BF16_GEMM_FP32_MASTER if bf16 else H.HDET_FP32, **cfg)
+        _, _, ws = H.hdet_workspace_bytes(lc, self.stride)
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
+        self.h = H.hdet_create(lc, self.theta, self.m, self.v if d["optimizer"] == O.ADAMW else None,
+                               grads=self.g, params_bf16=self.shadow, workspace=self.ws, plane_stride=self.stride)
+
+    def oracle_grads(self, theta, ids, tgt, step):
+        n = self.n
+        losses, grads = np.zeros(n), np.zeros((n, self.P), np.float32)
+        p = self.orc.dropout_table()
+        for r in range(n):
+            dp = dict(p=float(p[r]), seed=self.d["seed"], step=step, replica=r) if p[r] > 0 else None
+            losses[r], grads[r] = T.loss_and_grad(theta[r], ids[r], tgt[r], self.cfg, bf16=self.bf16, dropout=dp)
+        return losses, grads
+
+    def forward_backward(self, t):
+        ids, tgt = I.zipf_tokens(self.n, self.batch, self.cfg["seq_len"], self.cfg["vocab"], I.SEED_DATA, t)
+        out = H.hdet_forward_backward(self.h, torch.from_numpy(ids).to("cuda:0"), torch.from_numpy(tgt).to("cuda:0"),
+                                      want_losses=True)
+        return ids, tgt, np.array([out[r] for r in range(self.n)])
+
+    def finish_step(self, t, grads, losses, fuse=False):
+        H.hdet_fanout_step(self.h, None, H.HDET_FUSE_CONVERGE if fuse else 0)
+        self.orc.fanout_step(grads, losses)
+        if t % self.d["sync_interval"] == 0:
+            H.hdet_converge(self.h)
+            self.orc.converge()
+            H.hdet_autolr_update(self.h, None)
+            self.orc.autolr_update()
+
+    def close(self):
+        H.hdet_destroy(self.h)
+
+
+def per_tensor_errors(cfg, g_dev, g_ref):
+    out, off = {}, 0
+    for name, shape in I.transformer_shapes(cfg):
+        k = int(np.prod(shape))
+        out[name] = norm_err(g_dev[off:off + k], g_ref[off:off + k])
+        off += k
+    return out
+
+
+@pytest.mark.parametrize("cfg,batch,n", [(TINY, 3, 3), (SMALL, 4, 2), (ODD, 2, 2)])
+def test_fp32_loss_and_every_gradient_tensor(cfg, batch, n):
+    run = TfRun(base(n_replicas=n), cfg, batch)
+    ids, tgt, gl = run.forward_backward(1)
+    losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, 1)
+    assert np.max(np.abs(gl - losses)) <= 1e-5
+    g_dev = run.g.cpu().numpy()[:, :run.P]
+    for r in range(n):
+        errs = per_tensor_errors(cfg, g_dev[r], grads[r])
+        bad = {k: v for k, v in errs.items() if v > 2e-5}
+        assert not bad, (r, bad)
+    assert rel_err(g_dev, grads) <= 2e-4
+    run.close()
+
+
+@pytest.mark.parametrize("cfg,batch,n", [(TINY, 3, 3), (SMALL, 4, 2)])
+def test_fp32_full_loop_trajectory(cfg, batch, n):
+    d = base(n_replicas=n)
+    run = TfRun(d, cfg, batch)
+    first = last = None
+    for t in range(1, 13):
+        ids, tgt, gl = run.forward_backward(t)
+        losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, t)
+        assert np.max(np.abs(gl - losses)) <= 1e-4
+        run.finish_step(t, grads, losses, fuse=(t == 8))
+        assert rel_err(run.theta.cpu().numpy()[:, :run.P], run.orc.theta) <= min(t * 1e-5, 1e-4)
+        check_state(H.hdet_get_state(run.h), run.orc, scalar_rtol=5e-6, lr_ulps=None)
+        first = losses.mean() if first is None else first
+        last = losses.mean()
+    assert last < first
+    run.close()
+
+
+def test_fp32_dropout_and_weight_decay_channels():
+    """Three explored scalars (rate, dropout, weight decay) with independent permutations
+    (Remark 1); dropout masks regenerated on both sides from (seed, step, replica, site)."""
+    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
+    d = base(n_replicas=4, optimizer=O.ADAMW, lr_max=2e-3, alpha=0.15, extra=extra, total_steps=10, sync_interval=2,
+             warm_steps=2)
+    run = TfRun(d, TINY, 3)
+    for t in range(1, 9):
+        # compare each step from the device's own state (Adam's early steps are ill-conditioned in g)
+        run.orc.theta = run.theta.cpu().numpy()[:, :run.P].copy()
+        run.orc.m = run.m.cpu().numpy()[:, :run.P].copy()
+        run.orc.v = run.v.cpu().numpy()[:, :run.P].copy()
+        ids, tgt, gl = run.forward_backward(t)
+        p = run.orc.dropout_table()
+        assert p.max() > 0.15 and p.min() < 0.05
+        losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, t)
+        assert np.max(np.abs(gl - losses)) <= 2e-5
+        g_dev = run.g.cpu().numpy()[:, :run.P]
+        for r in range(4):
+            assert norm_err(g_dev[r], grads[r]) <= 2e-5, (t, r)
+        run.finish_step(t, grads, losses)
+        st = H.hdet_get_state(run.h)
+        assert st.k == run.orc.k
+        for j in range(3):
+            assert [st.perm[j][r] for r in range(4)] == run.orc.perm[j].tolist()
+    assert st.k == 4 and len({tuple(st.perm[j][r] for r in range(4)) for j in range(3)}) >= 2
+    run.close()
+
+
+@pytest.mark.parametrize("cfg,batch,n,steps", [(TINY, 3, 3, 12), (SMALL, 4, 2, 12), (ODD, 2, 2, 6)])
+def test_bf16_loss_curve_within_1e2(cfg, batch, n, steps):
+    d = base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, weight_decay=0.01, total_steps=steps)
+    run = TfRun(d, cfg, batch, bf16=True)
+    for t in range(1, steps + 1):
+        ids, tgt, gl = run.forward_backward(t)
+        losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, t)
+        assert np.max(np.abs(gl - losses)) <= 1e-2
+        if t == 1:
+            g_dev = run.g.cpu().numpy()[:, :run.P]
+            for r in range(n):
+                errs = per_tensor_errors(cfg, g_dev[r], grads[r])
+                bad = {k: v for k, v in errs.items() if v > 4e-2}
+                assert not bad, (r, bad)
+        run.finish_step(t, grads, losses, fuse=(t == 8))
+    run.close()
+
+
+def test_bf16_dropout_loss_matches():
+    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9)]
+    d = base(n_replicas=4, optimizer=O.ADAMW, lr_max=2e-3, extra=extra)
+    run = TfRun(d, SMALL, 2, bf16=True)
+    for t in range(1, 4):
+        ids, tgt, gl = run.forward_backward(t)
+        losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, t)
+        assert np.max(np.abs(gl - losses)) <= 1e-2
+        run.finish_step(t, grads, losses)
+    run.close()
