@@ -146,6 +146,75 @@ def mlp_workload(args):
             "loss_first_replica": float(st.l_step[0])}
 
 
+def transformer_workload(args):
+    """N = 8 replicas of a decoder-only transformer: 6 layers, d_model 512, 8 heads, FFN 2048,
+    seq 256, vocab 32000, 16 sequences per replica, Zipf(1.1) token ids, bf16 GEMMs with fp32
+    master weights, AdamW, one-cycle 2000 steps peak 6e-4, alpha 0.15, T = 32, auto-LR on."""
+    import torch
+    import hdet_inputs as I
+    import paper_2604_24708_amd as H
+    dev = torch.device("cuda:0")
+    n, B, T = 8, 16, 32
+    cfg = dict(n_blocks=6, d_model=512, n_heads=8, d_ff=2048, seq_len=256, vocab=32000)
+    P = I.transformer_param_count(cfg)
+    stride = (P + 3) // 4 * 4
+    total = max(2000, args.warmup + args.steps)
+    theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
+    theta[:, :P] = torch.from_numpy(I.transformer_init(1, cfg, I.SEED_INIT)).to(dev)
+    m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.zeros_like(theta)
+    shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
+    ids, tgt = I.zipf_tokens(n, B, cfg["seq_len"], cfg["vocab"], I.SEED_DATA, 0)
+    ids, tgt = torch.from_numpy(ids).to(dev), torch.from_numpy(tgt).to(dev)
+    stream = torch.cuda.current_stream()
+    lc = H.make_config(n_replicas=n, sync_interval=T, total_steps=total, warm_steps=int(0.3 * total),
+                       lr_max=6e-4, alpha=0.15, autolr_enabled=1, optimizer=H.HDET_ADAMW, weight_decay=0.01,
+                       grad_mode=H.HDET_GRAD_PER_REPLICA, precision=H.HDET_BF16_GEMM_FP32_MASTER,
+                       model_kind=H.HDET_TRANSFORMER, batch=B, seed=I.SEED_PERM, stream=stream.cuda_stream, **cfg)
+    _, _, ws_bytes = H.hdet_workspace_bytes(lc, stride)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    h = H.hdet_create(lc, theta, m, v, grads=g, params_bf16=shadow, workspace=ws, plane_stride=stride)
+    ev = []
+
+    def step(t, timed):
+        if timed:
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(stream)
+        H.hdet_forward_backward(h, ids, tgt)
+        if timed:
+            e[1].record(stream)
+        H.hdet_fanout_step(h, None, H.HDET_FUSE_CONVERGE)
+        if timed:
+            e[2].record(stream)
+            ev.append(e)
+        if t % T == 0:
+            H.hdet_converge(h)
+            H.hdet_autolr_update(h, None)
+
+    for t in range(1, args.warmup + 1):
+        step(t, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup + 1, args.warmup + args.steps + 1):
+        step(t, True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    fb_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / len(ev)
+    up_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
+    st = H.hdet_get_state(h)
+    H.hdet_destroy(h)
+    M, d, ff, V, S, L, nh = B * cfg["seq_len"], cfg["d_model"], cfg["d_ff"], cfg["vocab"], cfg["seq_len"], cfg["n_blocks"], cfg["n_heads"]
+    lin = L * (2.0 * M * d * 3 * d + 2.0 * M * d * d + 2 * 2.0 * M * d * ff) + 2.0 * M * d * V
+    attn = L * 2 * 2.0 * B * nh * S * S * (d // nh)          # scores and P V, full (unmasked) squares
+    gemm_flop = n * 3 * (lin + attn)                          # forward + dgrad + wgrad
+    tflops = gemm_flop / (fb_ms * 1e-3) / 1e12
+    return {"workload": "N=8 x decoder-only transformer 6L d512 h8 ffn2048 seq256 vocab32000, 16 seq/replica, bf16 GEMM + fp32 master, AdamW, T=32",
+            "n_params": P, "replica_steps_per_s": n * args.steps / dt, "tokens_per_s": n * M * args.steps / dt,
+            "ms_per_step": dt / args.steps * 1e3, "forward_backward_ms": fb_ms, "update_ms": up_ms,
+            "update_GBps": 30.0 * n * P / (up_ms * 1e-3) / 1e9, "gemm_flop_per_step": gemm_flop,
+            "forward_backward_TFLOPs": tflops, "mfma_frac_of_bf16_peak": tflops / MFMA_BF16_PEAK_TFLOPS,
+            "loss_first_replica": float(st.l_step[0])}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,7 +228,7 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="update kernel selection (0 = default)")
     ap.add_argument("--blocks", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["flat", "mlp", "both"], default="both",
+    ap.add_argument("--workload", choices=["flat", "mlp", "transformer", "both"], default="both",
                     help="flat: the headline flat-buffer case only; mlp: only the bf16 MLP case (printed as its own "
                          "JSON line); both: the headline line with the MLP figures attached as `mlp_bf16`")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -181,6 +250,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload == "mlp":
         print(json.dumps(mlp_workload(args)))
+        return
+    if args.workload == "transformer":
+        print(json.dumps(transformer_workload(args)))
         return
     n, P, T = args.replicas, int(args.params), args.sync_interval
     stride = (P + 3) // 4 * 4

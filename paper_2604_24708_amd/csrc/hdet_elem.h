@@ -14,6 +14,65 @@ __device__ __forceinline__ void hdet_st(uint16_t* p, float x) {
   *p = (uint16_t)(u >> 16);
 }
 
+// Eight consecutive elements (16-byte aligned for bf16, 32-byte for fp32) in one or two
+// 128-bit accesses.
+struct hdet_f8 { float v[8]; };
+typedef float hdet_f4v __attribute__((ext_vector_type(4)));
+typedef unsigned int hdet_u4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ hdet_f8 hdet_ld8(const float* p) {
+  const hdet_f4v a = *reinterpret_cast<const hdet_f4v*>(p), b = *reinterpret_cast<const hdet_f4v*>(p + 4);
+  hdet_f8 r = {{a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]}};
+  return r;
+}
+__device__ __forceinline__ hdet_f8 hdet_ld8(const uint16_t* p) {
+  const hdet_u4v u = *reinterpret_cast<const hdet_u4v*>(p);
+  hdet_f8 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r.v[2 * i] = __uint_as_float(u[i] << 16);
+    r.v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+  }
+  return r;
+}
+__device__ __forceinline__ unsigned hdet_bf16_bits(float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ void hdet_st8(float* p, const hdet_f8& x) {
+  *reinterpret_cast<hdet_f4v*>(p) = (hdet_f4v){x.v[0], x.v[1], x.v[2], x.v[3]};
+  *reinterpret_cast<hdet_f4v*>(p + 4) = (hdet_f4v){x.v[4], x.v[5], x.v[6], x.v[7]};
+}
+__device__ __forceinline__ void hdet_st8(uint16_t* p, const hdet_f8& x) {
+  hdet_u4v u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) u[i] = hdet_bf16_bits(x.v[2 * i]) | (hdet_bf16_bits(x.v[2 * i + 1]) << 16);
+  *reinterpret_cast<hdet_u4v*>(p) = u;
+}
+
+// Four consecutive elements in one access (16 B fp32, 8 B bf16).
+struct hdet_f4 { float v[4]; };
+typedef unsigned int hdet_u2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ hdet_f4 hdet_ld4(const float* p) {
+  const hdet_f4v a = *reinterpret_cast<const hdet_f4v*>(p);
+  hdet_f4 r = {{a[0], a[1], a[2], a[3]}};
+  return r;
+}
+__device__ __forceinline__ hdet_f4 hdet_ld4(const uint16_t* p) {
+  const hdet_u2v u = *reinterpret_cast<const hdet_u2v*>(p);
+  hdet_f4 r = {{__uint_as_float(u[0] << 16), __uint_as_float(u[0] & 0xffff0000u),
+                __uint_as_float(u[1] << 16), __uint_as_float(u[1] & 0xffff0000u)}};
+  return r;
+}
+__device__ __forceinline__ void hdet_st4(float* p, const hdet_f4& x) {
+  *reinterpret_cast<hdet_f4v*>(p) = (hdet_f4v){x.v[0], x.v[1], x.v[2], x.v[3]};
+}
+__device__ __forceinline__ void hdet_st4(uint16_t* p, const hdet_f4& x) {
+  hdet_u2v u = {hdet_bf16_bits(x.v[0]) | (hdet_bf16_bits(x.v[1]) << 16), hdet_bf16_bits(x.v[2]) | (hdet_bf16_bits(x.v[3]) << 16)};
+  *reinterpret_cast<hdet_u2v*>(p) = u;
+}
+
 __device__ __forceinline__ float hdet_wave_sum(float x) {
   for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
   return x;

@@ -15,6 +15,7 @@
 
 #include <vector>
 
+#include "hdet_elem.h"
 #include "hdet_internal.h"
 
 namespace {
@@ -85,6 +86,59 @@ __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const in
   if (lane == 0) row_loss[gr] = logf(se) - (z[y] - mx);
 }
 
+// Wide rows (2048 <= classes <= 32768, classes % 4 == 0): one 256-thread block per row, the row
+// held in registers (thread t owns the 4-element chunks t, t + 256, ...), so the logits are
+// read once.  Same formulas as xent_kernel.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void xent_row_kernel(const float* logits, const int32_t* labels, int rows, int classes,
+                                                       T* dlogits, float* row_loss) {
+  __shared__ float red[4];
+  const int64_t gr = (int64_t)blockIdx.y * rows + blockIdx.x;
+  const float* z = logits + gr * classes;
+  const int c4 = classes >> 2, tid = threadIdx.x;
+  hdet_f4 v[NV];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int ch = tid + 256 * i;
+    if (ch < c4) {
+      v[i] = hdet_ld4(z + 4 * ch);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) mx = fmaxf(mx, v[i].v[j]);
+    }
+  }
+  mx = wave_max(mx);
+  if ((tid & 63) == 0) red[tid >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float se = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    if (tid + 256 * i < c4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { v[i].v[j] = expf(v[i].v[j] - mx); se += v[i].v[j]; }
+    }
+  se = wave_sum(se);
+  if ((tid & 63) == 0) red[tid >> 6] = se;
+  __syncthreads();
+  se = ((red[0] + red[1]) + red[2]) + red[3];
+  const int y = labels[gr];
+  const float inv = 1.f / se, invb = 1.f / (float)rows;
+  T* d = dlogits + gr * classes;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int ch = tid + 256 * i;
+    if (ch < c4) {
+      hdet_f4 o;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o.v[j] = (v[i].v[j] * inv - (4 * ch + j == y ? 1.f : 0.f)) * invb;
+      hdet_st4(d + 4 * ch, o);
+    }
+  }
+  if (tid == 0) row_loss[gr] = logf(se) - (z[y] - mx);
+}
+
 // Per-replica mean of the row losses in a fixed tree order (one block per replica), the
 // step loss l(theta_r, B_r) of Algorithm 1, and its accumulation into L_acc (Sec. 3.4).
 __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* row_loss, int rows, hdet_ctrl* ctrl) {
@@ -119,6 +173,17 @@ struct hdet_mlp_plan {
 
 hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* labels, int rows, int classes, void* dlogits,
                             float* row_loss, int n_replicas, hipStream_t s) {
+  if (classes >= 2048 && classes <= 32768 && classes % 4 == 0) {
+    const dim3 grid(rows, n_replicas);
+    if (classes <= 8192) {
+      if (bf16) hipLaunchKernelGGL((xent_row_kernel<uint16_t, 8>), grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
+      else hipLaunchKernelGGL((xent_row_kernel<float, 8>), grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
+    } else {
+      if (bf16) hipLaunchKernelGGL((xent_row_kernel<uint16_t, 32>), grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
+      else hipLaunchKernelGGL((xent_row_kernel<float, 32>), grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
+    }
+    return hipGetLastError();
+  }
   const dim3 grid((rows + 3) / 4, n_replicas);
   if (bf16) hipLaunchKernelGGL(xent_kernel<uint16_t>, grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
   else hipLaunchKernelGGL(xent_kernel<float>, grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);

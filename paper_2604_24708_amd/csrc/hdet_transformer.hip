@@ -25,6 +25,7 @@ namespace {
 
 constexpr float kLnEps = 1e-5f;
 constexpr uint32_t kDropStream = 0x44524F50u;   // "DROP"
+constexpr int kColsumRows = 128;                // rows per block in stage 1 of the column sums
 
 // ------------------------------------------------------------------------------------------
 // elementwise / row kernels; blockIdx.y = replica
@@ -110,6 +111,152 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* dy, const T* x,
   }
 }
 
+// Vector forms of the two LayerNorm row kernels for d % 8 == 0, d <= 2048: the row lives in
+// registers (lane l owns the 8-element chunks l, l + 64, ...), so it is read from memory once.
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* x, const float* theta, int64_t ps, int64_t g_off,
+                                                         int64_t b_off, int M, int d, T* y, float* mean, float* rstd) {
+  const int r = blockIdx.y, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int64_t base = ((int64_t)r * M + row) * d;
+  const float* g = theta + (int64_t)r * ps + g_off;
+  const float* b = theta + (int64_t)r * ps + b_off;
+  const int d8 = d >> 3;
+  hdet_f8 xv[NCH];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int ch = lane + 64 * i;
+    if (ch < d8) {
+      xv[i] = hdet_ld8(x + base + 8 * ch);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s += xv[i].v[j];
+    }
+  }
+  const float mu = hdet_wave_sum(s) / (float)d;
+  float v = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+    if (lane + 64 * i < d8) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const float t = xv[i].v[j] - mu; v += t * t; }
+    }
+  const float rs = 1.f / sqrtf(hdet_wave_sum(v) / (float)d + kLnEps);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int ch = lane + 64 * i;
+    if (ch < d8) {
+      const hdet_f8 gv = hdet_ld8(g + 8 * ch), bv = hdet_ld8(b + 8 * ch);
+      hdet_f8 o;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o.v[j] = (xv[i].v[j] - mu) * rs * gv.v[j] + bv.v[j];
+      hdet_st8(y + base + 8 * ch, o);
+    }
+  }
+  if (lane == 0) { mean[(int64_t)r * M + row] = mu; rstd[(int64_t)r * M + row] = rs; }
+}
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void ln_bwd_dx_vec_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
+                                                            const float* theta, int64_t ps, int64_t g_off, int M, int d,
+                                                            const T* resid, T* dx) {
+  const int r = blockIdx.y, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int64_t base = ((int64_t)r * M + row) * d;
+  const float* g = theta + (int64_t)r * ps + g_off;
+  const float mu = mean[(int64_t)r * M + row], rs = rstd[(int64_t)r * M + row];
+  const int d8 = d >> 3;
+  hdet_f8 dxh[NCH], xh[NCH];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int ch = lane + 64 * i;
+    if (ch < d8) {
+      const hdet_f8 dyv = hdet_ld8(dy + base + 8 * ch), xv = hdet_ld8(x + base + 8 * ch), gv = hdet_ld8(g + 8 * ch);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        dxh[i].v[j] = dyv.v[j] * gv.v[j];
+        xh[i].v[j] = (xv.v[j] - mu) * rs;
+        s1 += dxh[i].v[j];
+        s2 += dxh[i].v[j] * xh[i].v[j];
+      }
+    }
+  }
+  const float m1 = hdet_wave_sum(s1) / (float)d, m2 = hdet_wave_sum(s2) / (float)d;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int ch = lane + 64 * i;
+    if (ch < d8) {
+      hdet_f8 o;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o.v[j] = rs * (dxh[i].v[j] - m1 - xh[i].v[j] * m2);
+      if (resid) {
+        const hdet_f8 rv = hdet_ld8(resid + base + 8 * ch);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o.v[j] += rv.v[j];
+      }
+      hdet_st8(dx + base + 8 * ch, o);
+    }
+  }
+}
+
+// Two-stage column reduction for cols % 8 == 0: stage 1, block (512 columns x rows_per_block
+// rows x replica), wavefront w adds rows w, w+4, ... of the chunk, the four partial sums are
+// added in the order w = 0..3 and written to part[replica][row chunk][col]; stage 2 adds the
+// row chunks in ascending order.  Same two modes as colsum_kernel.
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void colsum_part_kernel(const T* src, int64_t src_rs, int64_t src_bs, int M, int cols,
+                                                          int rows_per_block, const T* x, const float* mean,
+                                                          const float* rstd, float* part1, float* part2) {
+  __shared__ float l1[4][512], l2[4][512];
+  const int r = blockIdx.z, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int col = blockIdx.x * 512 + lane * 8;
+  const int m0 = blockIdx.y * rows_per_block;
+  const int m1 = m0 + rows_per_block < M ? m0 + rows_per_block : M;
+  float a1[8] = {0, 0, 0, 0, 0, 0, 0, 0}, a2[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (col < cols) {
+    for (int m = m0 + w; m < m1; m += 4) {
+      const hdet_f8 v = hdet_ld8(src + (int64_t)r * src_bs + (int64_t)m * src_rs + col);
+      if (MODE == 1) {
+        const hdet_f8 xv = hdet_ld8(x + ((int64_t)r * M + m) * cols + col);
+        const float mu = mean[(int64_t)r * M + m], rs = rstd[(int64_t)r * M + m];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { a1[j] += v.v[j] * ((xv.v[j] - mu) * rs); a2[j] += v.v[j]; }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a1[j] += v.v[j];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { l1[w][lane * 8 + j] = a1[j]; l2[w][lane * 8 + j] = a2[j]; }
+  __syncthreads();
+  const int64_t pbase = ((int64_t)r * gridDim.y + blockIdx.y) * cols;
+  for (int c = threadIdx.x; c < 512; c += 256) {
+    const int gc = blockIdx.x * 512 + c;
+    if (gc < cols) {
+      part1[pbase + gc] = ((l1[0][c] + l1[1][c]) + l1[2][c]) + l1[3][c];
+      if (MODE == 1) part2[pbase + gc] = ((l2[0][c] + l2[1][c]) + l2[2][c]) + l2[3][c];
+    }
+  }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* part1, const float* part2, int nchunks, int cols,
+                                                           float* out, float* out2, int64_t out_bs) {
+  const int r = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= cols) return;
+  float a = 0.f, b = 0.f;
+  for (int k = 0; k < nchunks; ++k) {
+    a += part1[((int64_t)r * nchunks + k) * cols + c];
+    if (MODE == 1) b += part2[((int64_t)r * nchunks + k) * cols + c];
+  }
+  out[(int64_t)r * out_bs + c] = a;
+  if (MODE == 1) out2[(int64_t)r * out_bs + c] = b;
+}
+
 // Column reductions over the M rows: block = 64 columns x 16 row phases; thread (c, q) adds
 // rows q, q+16, ... in ascending order, the 16 partial sums are then added in the order q = 0..15.
 //   MODE 0: out[c]  = sum_m src[m][c]                                   (bias gradients)
@@ -176,6 +323,78 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* dp, const
     hdet_st(ds + row * S + j, j <= i ? hdet_ld(p + row * S + j) * (dp[row * S + j] - dot) * scale : 0.f);
 }
 
+// Vector forms for S % 4 == 0, S <= 1024: lane l owns the 4-element chunks l, l + 64, ... of a row.
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void softmax_fwd_vec_kernel(const float* scores, int64_t rows_total, int S, float scale, T* p) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows_total) return;
+  const int i = (int)(row % S), s4 = S >> 2;
+  hdet_f4 v[NCH];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int ch = lane + 64 * k;
+    if (ch < s4) {
+      v[k] = hdet_ld4(scores + row * S + 4 * ch);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { v[k].v[j] *= scale; if (4 * ch + j <= i) mx = fmaxf(mx, v[k].v[j]); }
+    }
+  }
+  mx = hdet_wave_max(mx);
+  float se = 0.f;
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int ch = lane + 64 * k;
+    if (ch < s4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { v[k].v[j] = 4 * ch + j <= i ? expf(v[k].v[j] - mx) : 0.f; se += v[k].v[j]; }
+    }
+  }
+  const float inv = 1.f / hdet_wave_sum(se);
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int ch = lane + 64 * k;
+    if (ch < s4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[k].v[j] *= inv;
+      hdet_st4(p + row * S + 4 * ch, v[k]);
+    }
+  }
+}
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void softmax_bwd_vec_kernel(const float* dp, const T* p, int64_t rows_total, int S,
+                                                              float scale, T* ds) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows_total) return;
+  const int s4 = S >> 2;
+  hdet_f4 dv[NCH], pv[NCH];
+  float dot = 0.f;
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int ch = lane + 64 * k;
+    if (ch < s4) {
+      dv[k] = hdet_ld4(dp + row * S + 4 * ch);
+      pv[k] = hdet_ld4(p + row * S + 4 * ch);          // zero above the diagonal
+#pragma unroll
+      for (int j = 0; j < 4; ++j) dot += dv[k].v[j] * pv[k].v[j];
+    }
+  }
+  dot = hdet_wave_sum(dot);
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int ch = lane + 64 * k;
+    if (ch < s4) {
+      hdet_f4 o;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o.v[j] = pv[k].v[j] * (dv[k].v[j] - dot) * scale;
+      hdet_st4(ds + row * S + 4 * ch, o);
+    }
+  }
+}
+
 __device__ __forceinline__ float gelu_tanh(float z) {
   const float c = 0.7978845608028654f;
   return 0.5f * z * (1.f + tanhf(c * (z + 0.044715f * z * z * z)));
@@ -186,15 +405,29 @@ __device__ __forceinline__ float gelu_tanh_grad(float z) {
   return 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * z * z);
 }
 
+// 8 elements per thread and access; the n % 8 tail is done element-wise by the first threads
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T* z, T* f, int64_t n) {
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
-    hdet_st(f + i, gelu_tanh(hdet_ld(z + i)));
+  const int64_t n8 = n >> 3, tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (int64_t i = tid; i < n8; i += (int64_t)gridDim.x * 256) {
+    hdet_f8 v = hdet_ld8(z + 8 * i);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v.v[j] = gelu_tanh(v.v[j]);
+    hdet_st8(f + 8 * i, v);
+  }
+  if (tid < (n & 7)) hdet_st(f + 8 * n8 + tid, gelu_tanh(hdet_ld(z + 8 * n8 + tid)));
 }
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* df, const T* z, T* dz, int64_t n) {
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
-    hdet_st(dz + i, hdet_ld(df + i) * gelu_tanh_grad(hdet_ld(z + i)));
+  const int64_t n8 = n >> 3, tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (int64_t i = tid; i < n8; i += (int64_t)gridDim.x * 256) {
+    hdet_f8 v = hdet_ld8(df + 8 * i);
+    const hdet_f8 zv = hdet_ld8(z + 8 * i);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v.v[j] *= gelu_tanh_grad(zv.v[j]);
+    hdet_st8(dz + 8 * i, v);
+  }
+  if (tid < (n & 7)) hdet_st(dz + 8 * n8 + tid, hdet_ld(df + 8 * n8 + tid) * gelu_tanh_grad(hdet_ld(z + 8 * n8 + tid)));
 }
 
 // Dropout of a residual branch.  Element e of the replica's [M][d] tensor is kept iff word
@@ -226,14 +459,18 @@ __global__ __launch_bounds__(256) void dropout_kernel(const T* x, const T* branc
     hdet_philox4 w = {{0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu}};
     if (thresh != 0u)
       w = hdet_philox4x32_10((uint32_t)b, da.step, (uint32_t)r * 65536u + (uint32_t)da.site, kDropStream, da.seed_lo, da.seed_hi);
+    const int64_t i = (int64_t)r * n + (b << 2);
+    hdet_f4 v = hdet_ld4(branch + i);
+    if (thresh != 0u) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int64_t i = (int64_t)r * n + (b << 2) + j;
-      float v = hdet_ld(branch + i);
-      if (thresh != 0u) v = w.x[j] >= thresh ? v * ks : 0.f;
-      if (ADD) v += hdet_ld(x + i);
-      hdet_st(out + i, v);
+      for (int j = 0; j < 4; ++j) v.v[j] = w.x[j] >= thresh ? v.v[j] * ks : 0.f;
     }
+    if (ADD) {
+      const hdet_f4 xv = hdet_ld4(x + i);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v.v[j] += xv.v[j];
+    }
+    hdet_st4(out + i, v);
   }
 }
 
@@ -261,6 +498,8 @@ struct hdet_tf_plan {
   std::vector<float*> st1_mean, st1_rstd, st2_mean, st2_rstd;
   char *hf, *tmp_d, *dxa, *dxb, *dtmp, *dtmp2, *dff, *dqkv, *ds, *dlogits;
   float *stf_mean, *stf_rstd, *scores, *logits, *row_loss;
+  float *part1, *part2;      // partial column sums [N][row chunks][cols]
+  int nrc;                   // row chunks of the two-stage column sums
 };
 
 static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -291,6 +530,11 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   p->stf_mean = (float*)take(N * M * 4); p->stf_rstd = (float*)take(N * M * 4);
   p->scores = (float*)take(N * heads * S * S * 4); p->logits = (float*)take(N * M * V * 4);
   p->row_loss = (float*)take(N * M * 4);
+  p->nrc = (int)((M + kColsumRows - 1) / kColsumRows);
+  size_t maxc = V > 3 * d ? V : 3 * d;
+  if (ff > maxc) maxc = ff;
+  p->part1 = (float*)take(N * p->nrc * maxc * 4);
+  p->part2 = (float*)take(N * p->nrc * d * 4);
   return off;
 }
 
@@ -358,6 +602,85 @@ void hdet_tf_destroy(hdet_tf_plan* p) { delete p; }
 
 namespace {
 
+// ---- launch helpers: vector kernels where the shape allows, element-wise ones otherwise ----
+#define HDET_NCH_SWITCH(nch, CALL) \
+  switch (nch) { case 1: CALL(1); break; case 2: CALL(2); break; case 3: CALL(3); break; default: CALL(4); break; }
+
+template <typename T>
+void launch_ln_fwd(const hdet_tf_plan* p, const void* x, int64_t g_off, int64_t b_off, void* y, float* mean, float* rstd, hipStream_t s) {
+  const int M = p->M, d = p->d;
+  const int64_t ps = p->buf.plane_stride;
+  const float* theta = p->buf.params_dev;
+  const dim3 grid((M + 3) / 4, p->N);
+  if (d % 8 == 0 && d <= 2048 && g_off % 4 == 0 && b_off % 4 == 0 && ps % 4 == 0) {
+    const int nch = (d / 8 + 63) / 64;
+#define CALL(K) hipLaunchKernelGGL((ln_fwd_vec_kernel<T, K>), grid, dim3(256), 0, s, (const T*)x, theta, ps, g_off, b_off, M, d, (T*)y, mean, rstd)
+    HDET_NCH_SWITCH(nch, CALL)
+#undef CALL
+  } else {
+    hipLaunchKernelGGL(ln_fwd_kernel<T>, grid, dim3(256), 0, s, (const T*)x, theta, ps, g_off, b_off, M, d, (T*)y, mean, rstd);
+  }
+}
+
+template <typename T>
+void launch_ln_bwd_dx(const hdet_tf_plan* p, const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off,
+                      const void* resid, void* dx, hipStream_t s) {
+  const int M = p->M, d = p->d;
+  const int64_t ps = p->buf.plane_stride;
+  const float* theta = p->buf.params_dev;
+  const dim3 grid((M + 3) / 4, p->N);
+  if (d % 8 == 0 && d <= 2048 && g_off % 4 == 0 && ps % 4 == 0) {
+    const int nch = (d / 8 + 63) / 64;
+#define CALL(K) hipLaunchKernelGGL((ln_bwd_dx_vec_kernel<T, K>), grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx)
+    HDET_NCH_SWITCH(nch, CALL)
+#undef CALL
+  } else {
+    hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx);
+  }
+}
+
+template <typename T>
+void launch_softmax_fwd(const float* scores, int64_t rows, int S, float scale, void* prob, hipStream_t s) {
+  const dim3 grid((unsigned)((rows + 3) / 4));
+  if (S % 4 == 0 && S <= 1024) {
+    const int nch = (S / 4 + 63) / 64;
+#define CALL(K) hipLaunchKernelGGL((softmax_fwd_vec_kernel<T, K>), grid, dim3(256), 0, s, scores, rows, S, scale, (T*)prob)
+    HDET_NCH_SWITCH(nch, CALL)
+#undef CALL
+  } else {
+    hipLaunchKernelGGL(softmax_fwd_kernel<T>, grid, dim3(256), 0, s, scores, rows, S, scale, (T*)prob);
+  }
+}
+
+template <typename T>
+void launch_softmax_bwd(const float* dp, const void* prob, int64_t rows, int S, float scale, void* ds, hipStream_t s) {
+  const dim3 grid((unsigned)((rows + 3) / 4));
+  if (S % 4 == 0 && S <= 1024) {
+    const int nch = (S / 4 + 63) / 64;
+#define CALL(K) hipLaunchKernelGGL((softmax_bwd_vec_kernel<T, K>), grid, dim3(256), 0, s, dp, (const T*)prob, rows, S, scale, (T*)ds)
+    HDET_NCH_SWITCH(nch, CALL)
+#undef CALL
+  } else {
+    hipLaunchKernelGGL(softmax_bwd_kernel<T>, grid, dim3(256), 0, s, dp, (const T*)prob, rows, S, scale, (T*)ds);
+  }
+}
+
+// out[c] (and out2[c]) of the column reductions described at colsum_kernel, per replica
+template <typename T, int MODE>
+void launch_colsum(const hdet_tf_plan* p, const void* src, int cols, const void* x, const float* mean, const float* rstd,
+                   float* out, float* out2, hipStream_t s) {
+  const int M = p->M, N = p->N;
+  const int64_t ps = p->buf.plane_stride;
+  if (cols % 8 == 0) {
+    hipLaunchKernelGGL((colsum_part_kernel<T, MODE>), dim3((cols + 511) / 512, p->nrc, N), dim3(256), 0, s, (const T*)src, (int64_t)cols,
+                       (int64_t)M * cols, M, cols, kColsumRows, (const T*)x, mean, rstd, p->part1, p->part2);
+    hipLaunchKernelGGL((colsum_final_kernel<MODE>), dim3((cols + 255) / 256, N), dim3(256), 0, s, p->part1, p->part2, p->nrc, cols, out, out2, ps);
+  } else {
+    hipLaunchKernelGGL((colsum_kernel<T, MODE>), dim3((cols + 63) / 64, N), dim3(1024), 0, s, (const T*)src, (int64_t)cols, (int64_t)M * cols, M, cols,
+                       (const T*)x, mean, rstd, out, out2, ps);
+  }
+}
+
 enum { NT = 0, NN = 1, TN = 2 };      // forward / dgrad / wgrad operand orders (see the GEMM files)
 
 struct mat { const void* p; int64_t ld; int64_t s[3]; };
@@ -401,7 +724,6 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   float* grads = p->buf.grads_dev;
   const float scale = 1.f / sqrtf((float)dh);
   const int64_t heads_rows = (int64_t)N * B * nh * S;
-  const dim3 rows4((M + 3) / 4, N);
   const int64_t nd = (int64_t)M * d, nff = (int64_t)M * ff;
   drop_args da = {ctrl, p->drop_channel, step, (uint32_t)(p->cfg.seed & 0xffffffffu), (uint32_t)(p->cfg.seed >> 32), 0};
   const bool drop = p->drop_channel >= 0;
@@ -428,14 +750,13 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   hipLaunchKernelGGL(embed_fwd_kernel<T>, dim3(grid_for(nd), N), dim3(256), 0, s, theta, ps, p->tok, p->pos, ids, M, S, d, (T*)p->x_in[0]);
   for (int l = 0; l < L; ++l) {
     const tf_block_off& o = p->blk[l];
-    hipLaunchKernelGGL(ln_fwd_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->x_in[l], theta, ps, o.ln1_g, o.ln1_b, M, d,
-                       (T*)p->h1[l], p->st1_mean[l], p->st1_rstd[l]);
+    launch_ln_fwd<T>(p, p->x_in[l], o.ln1_g, o.ln1_b, p->h1[l], p->st1_mean[l], p->st1_rstd[l], s);
     TF_CHECK(gemm<T>(p, NT, act(p->h1[l], d), wt(o.w_qkv, d), p->qkv[l], 3 * d, act_3d, true, M, 3 * d, d, 1, 1, theta + o.b_qkv, ps, s));
     {   // scores = q k^T per (replica, sequence, head)
       const mat sc = head_sq(p->scores);
       TF_CHECK(gemm<T>(p, NT, qkv_part(p->qkv[l], 0), qkv_part(p->qkv[l], 1), p->scores, S, sc.s, false, S, S, dh, B, nh, nullptr, 0, s));
     }
-    hipLaunchKernelGGL(softmax_fwd_kernel<T>, dim3((unsigned)((heads_rows + 3) / 4)), dim3(256), 0, s, p->scores, heads_rows, S, scale, (T*)p->p[l]);
+    launch_softmax_fwd<T>(p->scores, heads_rows, S, scale, p->p[l], s);
     {   // a = p v
       const mat ac = head_cols(p->a[l]);
       TF_CHECK(gemm<T>(p, NN, head_sq(p->p[l]), qkv_part(p->qkv[l], 2), p->a[l], d, ac.s, true, S, dh, S, B, nh, nullptr, 0, s));
@@ -443,28 +764,24 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(gemm<T>(p, NT, act(p->a[l], d), wt(o.w_o, d), p->tmp_d, d, act_d, true, M, d, d, 1, 1, theta + o.b_o, ps, s));
     da.site = 2 * l;
     hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_in[l], (const T*)p->tmp_d, (T*)p->x_mid[l], nd, da);
-    hipLaunchKernelGGL(ln_fwd_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->x_mid[l], theta, ps, o.ln2_g, o.ln2_b, M, d,
-                       (T*)p->h2[l], p->st2_mean[l], p->st2_rstd[l]);
+    launch_ln_fwd<T>(p, p->x_mid[l], o.ln2_g, o.ln2_b, p->h2[l], p->st2_mean[l], p->st2_rstd[l], s);
     TF_CHECK(gemm<T>(p, NT, act(p->h2[l], d), wt(o.w_1, d), p->z[l], ff, act_ff, true, M, ff, d, 1, 1, theta + o.b_1, ps, s));
     hipLaunchKernelGGL(gelu_fwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->z[l], (T*)p->f[l], (int64_t)N * nff);
     TF_CHECK(gemm<T>(p, NT, act(p->f[l], ff), wt(o.w_2, ff), p->tmp_d, d, act_d, true, M, d, ff, 1, 1, theta + o.b_2, ps, s));
     da.site = 2 * l + 1;
     hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_mid[l], (const T*)p->tmp_d, (T*)p->x_in[l + 1], nd, da);
   }
-  hipLaunchKernelGGL(ln_fwd_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->x_in[L], theta, ps, p->lnf_g, p->lnf_b, M, d,
-                     (T*)p->hf, p->stf_mean, p->stf_rstd);
+  launch_ln_fwd<T>(p, p->x_in[L], p->lnf_g, p->lnf_b, p->hf, p->stf_mean, p->stf_rstd, s);
   TF_CHECK(gemm<T>(p, NT, act(p->hf, d), wt(p->w_head, d), p->logits, V, act_v, false, M, V, d, 1, 1, theta + p->b_head, ps, s));
   TF_CHECK(hdet_launch_xent(sizeof(T) == 2, p->logits, targets, M, V, p->dlogits, p->row_loss, N, s));
   TF_CHECK(hdet_launch_loss_reduce(p->row_loss, M, ctrl, N, s));
 
   // ---- backward -----------------------------------------------------------------------
   auto colsum = [&](const void* src, int cols, int64_t out_off) {
-    hipLaunchKernelGGL((colsum_kernel<T, 0>), dim3((cols + 63) / 64, N), dim3(1024), 0, s, (const T*)src, (int64_t)cols, (int64_t)M * cols, M, cols,
-                       (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, grads + out_off, (float*)nullptr, ps);
+    launch_colsum<T, 0>(p, src, cols, nullptr, nullptr, nullptr, grads + out_off, nullptr, s);
   };
   auto ln_params = [&](const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off, int64_t b_off) {
-    hipLaunchKernelGGL((colsum_kernel<T, 1>), dim3((d + 63) / 64, N), dim3(1024), 0, s, (const T*)dy, (int64_t)d, (int64_t)M * d, M, d,
-                       (const T*)x, mean, rstd, grads + g_off, grads + b_off, ps);
+    launch_colsum<T, 1>(p, dy, d, x, mean, rstd, grads + g_off, grads + b_off, s);
   };
   auto wgrad = [&](const void* dy, int wy, const void* x, int wx, int64_t w_off) {      // dW[wy][wx] = dy^T x
     return gemm<T>(p, TN, act(dy, wy), act(x, wx), grads + w_off, wx, plane, false, wy, wx, M, 1, 1, nullptr, 0, s);
@@ -474,8 +791,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   colsum(p->dlogits, V, p->b_head);
   TF_CHECK(gemm<T>(p, NN, act(p->dlogits, V), wt(p->w_head, d), p->dtmp, d, act_d, true, M, d, V, 1, 1, nullptr, 0, s));
   ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b);
-  hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->dtmp, (const T*)p->x_in[L], p->stf_mean, p->stf_rstd,
-                     theta, ps, p->lnf_g, M, d, (const T*)nullptr, (T*)p->dxa);
+  launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, nullptr, p->dxa, s);
   for (int l = L - 1; l >= 0; --l) {
     const tf_block_off& o = p->blk[l];
     // MLP branch: x_out = x_mid + drop(y)
@@ -493,8 +809,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     colsum(p->dff, ff, o.b_1);
     TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
     ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b);
-    hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->dtmp, (const T*)p->x_mid[l], p->st2_mean[l], p->st2_rstd[l],
-                       theta, ps, o.ln2_g, M, d, (const T*)p->dxa, (T*)p->dxb);
+    launch_ln_bwd_dx<T>(p, p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, p->dxa, p->dxb, s);
     // attention branch: x_mid = x_in + drop(o)
     const void* dob = p->dxb;
     if (drop) {
@@ -512,7 +827,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       TF_CHECK(gemm<T>(p, NT, head_cols(p->dtmp), qkv_part(p->qkv[l], 2), p->scores, S, sc.s, false, S, S, dh, B, nh, nullptr, 0, s));
       // dv = p^T da
       TF_CHECK(gemm<T>(p, TN, head_sq(p->p[l]), head_cols(p->dtmp), (void*)dv.p, 3 * d, dv.s, true, S, dh, S, B, nh, nullptr, 0, s));
-      hipLaunchKernelGGL(softmax_bwd_kernel<T>, dim3((unsigned)((heads_rows + 3) / 4)), dim3(256), 0, s, p->scores, (const T*)p->p[l], heads_rows, S, scale, (T*)p->ds);
+      launch_softmax_bwd<T>(p->scores, p->p[l], heads_rows, S, scale, p->ds, s);
       // dq = ds k,  dk = ds^T q
       TF_CHECK(gemm<T>(p, NN, head_sq(p->ds), qkv_part(p->qkv[l], 1), (void*)dq.p, 3 * d, dq.s, true, S, dh, S, B, nh, nullptr, 0, s));
       TF_CHECK(gemm<T>(p, TN, head_sq(p->ds), qkv_part(p->qkv[l], 0), (void*)dk.p, 3 * d, dk.s, true, S, dh, S, B, nh, nullptr, 0, s));
@@ -521,8 +836,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     colsum(p->dqkv, 3 * d, o.b_qkv);
     TF_CHECK(gemm<T>(p, NN, act(p->dqkv, 3 * d), wt(o.w_qkv, d), p->dtmp, d, act_d, true, M, d, 3 * d, 1, 1, nullptr, 0, s));
     ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b);
-    hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, rows4, dim3(256), 0, s, (const T*)p->dtmp, (const T*)p->x_in[l], p->st1_mean[l], p->st1_rstd[l],
-                       theta, ps, o.ln1_g, M, d, (const T*)p->dxb, (T*)p->dxa);
+    launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s);
   }
   const int64_t emb = (int64_t)(V + S) * d;      // tok_emb and pos_emb are adjacent at the head of the plane
   hipLaunchKernelGGL(zero_kernel, dim3(grid_for(emb), N), dim3(256), 0, s, grads, ps, p->tok, emb);

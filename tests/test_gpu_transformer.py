@@ -15,6 +15,8 @@ pytestmark = pytest.mark.gpu
 TINY = dict(n_blocks=2, d_model=16, n_heads=4, d_ff=40, seq_len=6, vocab=29)
 SMALL = dict(n_blocks=2, d_model=64, n_heads=4, d_ff=256, seq_len=32, vocab=512)      # several tiles
 ODD = dict(n_blocks=1, d_model=24, n_heads=3, d_ff=50, seq_len=70, vocab=131)        # ragged everywhere
+# two register chunks per lane in LayerNorm (d > 512) and softmax (S > 256), wide-row cross-entropy
+MID = dict(n_blocks=1, d_model=576, n_heads=9, d_ff=1152, seq_len=264, vocab=2304)
 
 
 def norm_err(a, b):
@@ -89,7 +91,7 @@ def per_tensor_errors(cfg, g_dev, g_ref):
     return out
 
 
-@pytest.mark.parametrize("cfg,batch,n", [(TINY, 3, 3), (SMALL, 4, 2), (ODD, 2, 2)])
+@pytest.mark.parametrize("cfg,batch,n", [(TINY, 3, 3), (SMALL, 4, 2), (ODD, 2, 2), (MID, 2, 2)])
 def test_fp32_loss_and_every_gradient_tensor(cfg, batch, n):
     run = TfRun(base(n_replicas=n), cfg, batch)
     ids, tgt, gl = run.forward_backward(1)
@@ -100,7 +102,9 @@ def test_fp32_loss_and_every_gradient_tensor(cfg, batch, n):
         errs = per_tensor_errors(cfg, g_dev[r], grads[r])
         bad = {k: v for k, v in errs.items() if v > 2e-5}
         assert not bad, (r, bad)
-    assert rel_err(g_dev, grads) <= 2e-4
+    # entry-wise over the whole plane (tensors of very different scale, dot products of up to
+    # M or V fp32 terms): an intermediate, bounded loosely; the per-tensor norms above are the check
+    assert rel_err(g_dev, grads) <= (2e-4 if cfg is not MID else 5e-3)
     run.close()
 
 
@@ -151,7 +155,7 @@ def test_fp32_dropout_and_weight_decay_channels():
     run.close()
 
 
-@pytest.mark.parametrize("cfg,batch,n,steps", [(TINY, 3, 3, 12), (SMALL, 4, 2, 12), (ODD, 2, 2, 6)])
+@pytest.mark.parametrize("cfg,batch,n,steps", [(TINY, 3, 3, 12), (SMALL, 4, 2, 12), (ODD, 2, 2, 6), (MID, 2, 2, 2)])
 def test_bf16_loss_curve_within_1e2(cfg, batch, n, steps):
     d = base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, weight_decay=0.01, total_steps=steps)
     run = TfRun(d, cfg, batch, bf16=True)
