@@ -17,9 +17,11 @@
 //     transposing LDS load of gfx950 (ds_read_b64_tr_b16, two per fragment), so that no
 //     transposed copy of weights or activations ever exists in HBM.
 //
-// Tiling: 128x128 output tile per 256-thread block (4 wavefronts, 2x2, 64x64 each as 2x2
-// v_mfma_f32_32x32x16_bf16), K step 32, LDS double-buffered (one barrier per K step), global
-// loads prefetched two K steps ahead through a ring of registers.
+// Tiling: each wavefront owns a 64x64 output tile (2x2 blocks of v_mfma_f32_32x32x16_bf16); a
+// block is 2x2 wavefronts (128x128 tile) or, for m >= 192, 4x2 wavefronts (256x128 tile, 512
+// threads).  K step 32, LDS double-buffered (one barrier per K step), the next step's global
+// loads in flight during the MFMAs; launch indices are remapped so that each XCD's L2 serves a
+// contiguous range of tiles.
 
 #include "hdet_internal.h"
 
@@ -31,15 +33,15 @@ typedef unsigned short us8 __attribute__((ext_vector_type(8)));
 typedef short s4 __attribute__((ext_vector_type(4)));
 typedef short s8 __attribute__((ext_vector_type(8)));
 
-constexpr int TM = 128, TN = 128, TK = 32;
+constexpr int TK = 32;
 constexpr int LDK = TK;          // pitch of a [row][k] tile: 64 B, no padding; the four 16-byte chunks of a
                                  // row are stored XOR-swizzled by (row / 4) % 4, which makes both the
                                  // staging stores (4 rows x 4 chunks per 16 lanes) and the fragment
                                  // loads (16 rows x 1 chunk per 16 lanes) free of bank conflicts
-constexpr int LDR = TM + 32;     // pitch of a [k][row] tile: 320 B = 80 banks, so the 4 k-rows that a
-                                 // 16-lane group of a transposing read touches fall on disjoint banks
-constexpr int TILE_ELEMS = 5120; // max(128 * LDK, 32 * LDR)
-constexpr int PF = 2;            // K steps of global loads in flight (even)
+// pitch of a [k][row] tile of ROWS rows: ROWS + 32 elements, i.e. 16 banks past a multiple of 64, so
+// the 4 k-rows that a 16-lane group of a transposing read touches fall on disjoint banks
+__host__ __device__ constexpr int ldr(int rows) { return rows + 32; }
+__host__ __device__ constexpr int tile_elems(int rows) { return TK * ldr(rows); }   // >= rows * LDK
 
 __device__ __forceinline__ unsigned short f2bf(float x) {
   unsigned u = __float_as_uint(x);
@@ -52,14 +54,12 @@ __device__ __forceinline__ float bf2f(unsigned short h) { return __uint_as_float
 // 8 consecutive elements starting at src[idx], of which the first `valid` exist (others 0).
 // FAST: the host has checked that every chunk is 16-byte aligned and either whole or absent
 // (leading dimensions, extents along the chunk axis and replica strides multiples of 8), so the
-// load is one branch-free 128-bit access -- an absent chunk reads src[0..7] and is zeroed.
+// load is one branch-free 128-bit access; an absent chunk reads src[0..7] and is replaced by
+// zeros only when it is written to LDS -- touching the loaded value any earlier would make the
+// wavefront wait for the load and undo the prefetch.
 template <bool FAST>
 __device__ __forceinline__ us8 load8(const uint16_t* src, int64_t idx, int valid, bool vec_ok) {
-  if (FAST) {
-    const us8 v = *reinterpret_cast<const us8*>(src + (valid > 0 ? idx : 0));
-    const us8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    return valid > 0 ? v : zero;
-  }
+  if (FAST) return *reinterpret_cast<const us8*>(src + (valid > 0 ? idx : 0));
   if (valid >= 8 && vec_ok) return *reinterpret_cast<const us8*>(src + idx);
   us8 r = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -68,32 +68,42 @@ __device__ __forceinline__ us8 load8(const uint16_t* src, int64_t idx, int valid
   return r;
 }
 
-// One operand tile: 128 rows of the output dimension x 32 of the contraction.
+// One operand tile: ROWS (128 or 256) rows of the output dimension x 32 of the contraction.
 // KMAJOR: element (row, k) at src[row * ld + k], LDS tile[row][k];
 // otherwise at src[k * ld + row], LDS tile[k][row].
-template <bool KMAJOR, bool FAST>
+template <bool KMAJOR, bool FAST, int ROWS, int THREADS>
 struct operand {
-  us8 reg[2];
+  static constexpr int NCH = ROWS * 4 / THREADS;   // 8-element chunks per thread and K step
+  static constexpr int RCH = ROWS / 8;         // chunks per k-row of a [k][row] tile
+  us8 reg[NCH];
+  unsigned absent;                             // FAST: bit i set if chunk i lies outside the operand
   __device__ __forceinline__ void fetch(const uint16_t* src, int64_t ld, int row0, int rows, int k0, int kdim,
                                         bool vec_ok, int tid) {
+    absent = 0u;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + i * 256;
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + i * THREADS;
+      int valid;
       if (KMAJOR) {
         const int row = row0 + (c >> 2), k = k0 + ((c & 3) << 3);
-        reg[i] = load8<FAST>(src, (int64_t)row * ld + k, row < rows ? kdim - k : 0, vec_ok);
+        valid = row < rows ? kdim - k : 0;
+        reg[i] = load8<FAST>(src, (int64_t)row * ld + k, valid, vec_ok);
       } else {
-        const int k = k0 + (c >> 4), row = row0 + ((c & 15) << 3);
-        reg[i] = load8<FAST>(src, (int64_t)k * ld + row, k < kdim ? rows - row : 0, vec_ok);
+        const int k = k0 + c / RCH, row = row0 + ((c % RCH) << 3);
+        valid = k < kdim ? rows - row : 0;
+        reg[i] = load8<FAST>(src, (int64_t)k * ld + row, valid, vec_ok);
       }
+      if (FAST && valid <= 0) absent |= 1u << i;
     }
   }
   __device__ __forceinline__ void commit(uint16_t* tile, int tid) const {
+    const us8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + i * 256;
-      if (KMAJOR) *reinterpret_cast<us8*>(tile + (c >> 2) * LDK + ((((c & 3) ^ (c >> 4)) & 3) << 3)) = reg[i];
-      else *reinterpret_cast<us8*>(tile + (c >> 4) * LDR + ((c & 15) << 3)) = reg[i];
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + i * THREADS;
+      const us8 v = (FAST && ((absent >> i) & 1u)) ? zero : reg[i];
+      if (KMAJOR) *reinterpret_cast<us8*>(tile + (c >> 2) * LDK + ((((c & 3) ^ (c >> 4)) & 3) << 3)) = v;
+      else *reinterpret_cast<us8*>(tile + (c / RCH) * ldr(ROWS) + ((c % RCH) << 3)) = v;
     }
   }
   // MFMA 32x32x16 operand fragment: lane l gets (row = r0 + l % 32, k = ks + 8 * (l / 32) + 0..7).
@@ -108,9 +118,9 @@ struct operand {
     const int p = lane & 15;
     const int rb = r0 + (((lane >> 4) & 1) << 4);
     const int kb = ks + ((lane >> 5) << 3);
-    const uint16_t* q = tile + (kb + (p >> 2)) * LDR + rb + ((p & 3) << 2);
+    const uint16_t* q = tile + (kb + (p >> 2)) * ldr(ROWS) + rb + ((p & 3) << 2);
     const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)(q));
-    const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)(q + 4 * LDR));
+    const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)(q + 4 * ldr(ROWS)));
     const s8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, both);
   }
@@ -118,82 +128,88 @@ struct operand {
 
 }  // namespace
 
-template <bool A_KMAJOR, bool B_KMAJOR, int EPI, bool FAST>
-__global__ __launch_bounds__(256) void hdet_bgemm_kernel(const hdet_bgemm_args g) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[2][TILE_ELEMS];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][TILE_ELEMS];
-  const hdet_batch_index bi = hdet_split_batch(blockIdx.z, g.n1, g.n2);
+// WMT x WNT: 32x32 MFMA blocks per wavefront in m and n; WGM x 2 wavefronts per block
+// (WGM = 2: 256 threads, WGM = 4: 512 threads), block tile (32 WMT WGM) x (64 WNT).
+template <bool A_KMAJOR, bool B_KMAJOR, int EPI, bool FAST, int WMT, int WNT, int WGM>
+__global__ __launch_bounds__(128 * WGM, WGM) void hdet_bgemm_kernel(const hdet_bgemm_args g) {
+  constexpr int TM = 32 * WMT * WGM, TN = 64 * WNT, THREADS = 128 * WGM;
+  __shared__ __attribute__((aligned(16))) uint16_t As[2][tile_elems(TM)];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][tile_elems(TN)];
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2) in launch order.
+  // Remap the launch index so that an XCD works on a contiguous range of tiles: the tiles that
+  // share an A row-panel or a weight panel then meet in one L2 instead of eight.
+  int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  {
+    const unsigned total = gridDim.x * gridDim.y * gridDim.z;
+    if ((total & 7u) == 0u) {
+      const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+      const unsigned t = (lin & 7u) * (total >> 3) + (lin >> 3);
+      bx = t % gridDim.x;
+      by = (t / gridDim.x) % gridDim.y;
+      bz = t / (gridDim.x * gridDim.y);
+    }
+  }
+  const hdet_batch_index bi = hdet_split_batch(bz, g.n1, g.n2);
   const int z = bi.z0;            // replica: bias and mask are per replica
   const uint16_t* A = g.a + hdet_batch_offset(bi, g.a_s);
   const uint16_t* B = g.b + hdet_batch_offset(bi, g.b_s);
   const int64_t c_base = hdet_batch_offset(bi, g.c_s);
-  const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+  const int m0 = by * TM, n0 = bx * TN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave >> 1) * (32 * WMT), wn = (wave & 1) * (32 * WNT);
   const bool a_vec = (g.lda & 7) == 0 && (reinterpret_cast<uintptr_t>(A) & 15) == 0;
   const bool b_vec = (g.ldb & 7) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0;
 
-  f16v acc[2][2];
+  f16v acc[WMT][WNT];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < WMT; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < WNT; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // Ring of PF register stages: the global loads of K step kt + PF are issued while step kt
-  // is computed, so that about PF x 16 KB per block is in flight -- one step's MFMAs (about
-  // 0.1 us) are far shorter than an HBM round trip.
-  operand<A_KMAJOR, FAST> oa[PF];
-  operand<B_KMAJOR, FAST> ob[PF];
-  // The loop body is free of conditions: K steps past the end of the contraction load zeros
-  // (absent chunks) and multiply them, so the count is simply rounded up to a multiple of PF.
-  const int nk = ((g.k + TK - 1) / TK + PF - 1) / PF * PF;
-#pragma unroll
-  for (int d = 0; d < PF; ++d) {
-    oa[d].fetch(A, g.lda, m0, g.m, d * TK, g.k, a_vec, tid);
-    ob[d].fetch(B, g.ldb, n0, g.n, d * TK, g.k, b_vec, tid);
-  }
-  oa[0].commit(As[0], tid);
-  ob[0].commit(Bs[0], tid);
+  // One register stage: the global loads of K step kt + 1 are issued before the MFMAs of step
+  // kt and written to the other LDS buffer after them (one barrier per step); a second block
+  // on the same CU covers the rest of the memory latency.  The loop body is free of conditions:
+  // the step past the end loads nothing (all chunks absent) and its zeros are never used.
+  operand<A_KMAJOR, FAST, TM, THREADS> oa;
+  operand<B_KMAJOR, FAST, TN, THREADS> ob;
+  const int nk = (g.k + TK - 1) / TK;
+  oa.fetch(A, g.lda, m0, g.m, 0, g.k, a_vec, tid);
+  ob.fetch(B, g.ldb, n0, g.n, 0, g.k, b_vec, tid);
+  oa.commit(As[0], tid);
+  ob.commit(Bs[0], tid);
   __syncthreads();
-  oa[0].fetch(A, g.lda, m0, g.m, PF * TK, g.k, a_vec, tid);
-  ob[0].fetch(B, g.ldb, n0, g.n, PF * TK, g.k, b_vec, tid);
-  for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    oa.fetch(A, g.lda, m0, g.m, (kt + 1) * TK, g.k, a_vec, tid);
+    ob.fetch(B, g.ldb, n0, g.n, (kt + 1) * TK, g.k, b_vec, tid);
+    __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the MFMAs ...
 #pragma unroll
-    for (int d = 0; d < PF; ++d) {
-      const int buf = d & 1;                 // PF is even, so (kt0 + d) & 1 == d & 1
+    for (int ks = 0; ks < TK; ks += 16) {
+      bf16x8 af[WMT], bfr[WNT];
 #pragma unroll
-      for (int ks = 0; ks < TK; ks += 16) {
-        bf16x8 af[2], bfr[2];
+      for (int i = 0; i < WMT; ++i) af[i] = operand<A_KMAJOR, FAST, TM, THREADS>::fragment(As[buf], wm + i * 32, ks, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          af[i] = operand<A_KMAJOR, FAST>::fragment(As[buf], wm + i * 32, ks, lane);
-          bfr[i] = operand<B_KMAJOR, FAST>::fragment(Bs[buf], wn + i * 32, ks, lane);
-        }
+      for (int j = 0; j < WNT; ++j) bfr[j] = operand<B_KMAJOR, FAST, TN, THREADS>::fragment(Bs[buf], wn + j * 32, ks, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < WMT; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
-      // stage tile kt0 + d + 1 into the other LDS buffer (last read before the previous
-      // barrier) and refill its ring slot with tile kt0 + d + 1 + PF
-      const int r = (d + 1) % PF;
-      oa[r].commit(As[buf ^ 1], tid);
-      ob[r].commit(Bs[buf ^ 1], tid);
-      oa[r].fetch(A, g.lda, m0, g.m, (kt0 + d + 1 + PF) * TK, g.k, a_vec, tid);
-      ob[r].fetch(B, g.ldb, n0, g.n, (kt0 + d + 1 + PF) * TK, g.k, b_vec, tid);
-      __syncthreads();
+        for (int j = 0; j < WNT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);     // ... and every use of the loaded data behind them
+    oa.commit(As[buf ^ 1], tid);      // last read before the previous barrier
+    ob.commit(Bs[buf ^ 1], tid);
+    __syncthreads();
   }
 
   // epilogue: accumulator element e of lane l is C(row, col) with
   //   row = (e / 4) * 8 + (l / 32) * 4 + e % 4,  col = l % 32   inside its 32x32 block
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < WMT; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < WNT; ++j) {
       const int col = n0 + wn + j * 32 + (lane & 31);
       if (col >= g.n) continue;
       float bias = 0.f;
@@ -234,14 +250,17 @@ hipError_t hdet_launch_bgemm(const hdet_bgemm_args& g_in, bool a_kmajor, bool b_
   hdet_bgemm_args g = g_in;
   if (g.n1 < 1) g.n1 = 1;
   if (g.n2 < 1) g.n2 = 1;
-  dim3 grid((g.n + TN - 1) / TN, (g.m + TM - 1) / TM, batch);
   // a chunk is 8 elements along the operand's contiguous axis: k if k-major, else the row axis
   const bool fast = chunk_regular(g.a, g.lda, g.a_s, a_kmajor ? g.k : g.m) &&
                     chunk_regular(g.b, g.ldb, g.b_s, b_kmajor ? g.k : g.n);
-#define HDET_BGEMM(AK, BK, E)                                                                          \
-  do {                                                                                                 \
-    if (fast) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, true>), grid, dim3(256), 0, s, g);      \
-    else hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, false>), grid, dim3(256), 0, s, g);          \
+  const bool big = fast && g.m >= 192 && g.n >= 96;       // 256x128 tiles with 8 wavefronts, else 128x128 with 4
+  const int tm = big ? 256 : 128, tn = 128;
+  dim3 grid((g.n + tn - 1) / tn, (g.m + tm - 1) / tm, batch);
+#define HDET_BGEMM(AK, BK, E)                                                                                 \
+  do {                                                                                                        \
+    if (big) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, true, 2, 2, 4>), grid, dim3(512), 0, s, g);      \
+    else if (fast) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, true, 2, 2, 2>), grid, dim3(256), 0, s, g); \
+    else hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, false, 2, 2, 2>), grid, dim3(256), 0, s, g);         \
   } while (0)
 #define HDET_BGEMM_EPI(AK, BK)                                                                         \
   switch (epi) {                                                                                       \
