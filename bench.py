@@ -230,7 +230,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", choices=["flat", "mlp", "transformer", "both"], default="both",
                     help="flat: the headline flat-buffer case only; mlp: only the bf16 MLP case (printed as its own "
-                         "JSON line); both: the headline line with the MLP figures attached as `mlp_bf16`")
+                         "JSON line); transformer: only the bf16 transformer case; both: the headline line with the "
+                         "MLP and transformer figures attached as `mlp_bf16` and `transformer_bf16`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of known size (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -348,6 +349,11 @@ def main():
     torch.cuda.empty_cache()
     if args.workload == "both":
         out["mlp_bf16"] = mlp_workload(args)
+        torch.cuda.empty_cache()
+        targs = argparse.Namespace(**vars(args))
+        targs.steps, targs.warmup = min(args.steps, 16), min(args.warmup, 4)
+        out["transformer_bf16"] = transformer_workload(targs)
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         p_sample, o_steps = 4_000_000, T + 1
         odt, cores = oracle_baseline(n, T, p_sample, o_steps)
