@@ -355,7 +355,7 @@ def main():
         out["transformer_bf16"] = transformer_workload(targs)
         torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        p_sample, o_steps = 4_000_000, T + 1
+        p_sample, o_steps = 10_000_000, T + 1
         odt, cores = oracle_baseline(n, T, p_sample, o_steps)
         out["cpu_baseline"] = {"value": n * o_steps / odt * (p_sample / P), "unit": "replica-steps/s",
                                "cores": cores, "kind": "oracle",
