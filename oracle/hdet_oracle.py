@@ -154,6 +154,43 @@ def permutation(seed: int, k: int, channel: int, n: int) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------------------
+# Sec. 3.5, Eq. 10: warm noisy initialisation
+# --------------------------------------------------------------------------------------
+WARM_STREAM = 0x5741524D  # ASCII "WARM"
+
+
+def standard_normals(seed: int, replica: int, n: int) -> np.ndarray:
+    """n standard normal draws for one replica, a pure function of (seed, replica, index).
+    Elements 4b..4b+3 come from philox(counter = (b, replica, 0, WARM_STREAM), key = seed):
+    with u = (word + 1) / 2^32 in (0, 1] and v = word / 2^32 in [0, 1), the Box-Muller pairs
+    are (sqrt(-2 ln u0) cos(2 pi v1), sqrt(-2 ln u0) sin(2 pi v1)) from words (0, 1) and
+    likewise from words (2, 3)."""
+    key = (seed & _MASK32, (seed >> 32) & _MASK32)
+    out = np.empty(4 * ((n + 3) // 4), dtype=np.float64)
+    for b in range((n + 3) // 4):
+        w = philox4x32_10((b, replica, 0, WARM_STREAM), key)
+        for h in range(2):
+            u = (w[2 * h] + 1) / 4294967296.0
+            v = w[2 * h + 1] / 4294967296.0
+            rad = math.sqrt(-2.0 * math.log(u))
+            out[4 * b + 2 * h] = rad * math.cos(2.0 * math.pi * v)
+            out[4 * b + 2 * h + 1] = rad * math.sin(2.0 * math.pi * v)
+    return out[:n]
+
+
+def warm_noisy_init(theta0: np.ndarray, n_replicas: int, nu: float, seed: int, store=np.float32) -> np.ndarray:
+    """theta_r = theta0 + eps_r, eps_r ~ N(0, nu^2 ||theta0||^2 / d) independently per replica
+    and element (Eq. 10); d = number of parameters."""
+    t0 = theta0.astype(np.float64)
+    d = t0.size
+    sigma = nu * math.sqrt(float(np.sum(t0 * t0)) / d)
+    out = np.empty((n_replicas, d), dtype=store)
+    for r in range(n_replicas):
+        out[r] = (t0 + sigma * standard_normals(seed, r, d)).astype(store)
+    return out
+
+
+# --------------------------------------------------------------------------------------
 # Gradient exchange (Algorithm 1, "AllReduce gradients"): replica-axis mean.
 # --------------------------------------------------------------------------------------
 def shared_gradient(g: np.ndarray) -> np.ndarray:

@@ -434,3 +434,37 @@ def test_nonfinite_loss_leaves_state_untouched():
     cfg = _cfg()
     orc, _ = _run(cfg, steps=16, loss_fn=lambda t: [2.0, float("nan"), 2.0, 2.0] if t > 12 else [2.0] * 4)
     assert orc.nonfinite == 1 and orc.k == 1
+
+
+# ---------------------------------------------------------------- Eq. 10 warm noisy initialisation
+def test_warm_init_noise_scale_and_independence():
+    from scipy import stats
+    rng = np.random.default_rng(9)
+    theta0 = (rng.standard_normal(20000) * 0.3).astype(np.float32)
+    nu = load_golden("controller_defaults.txt")["nu"][0]            # the paper uses nu = 0.01
+    out = O.warm_noisy_init(theta0, 4, nu, 123, store=np.float64)
+    eps = out - theta0.astype(np.float64)
+    norm2 = float(np.sum(theta0.astype(np.float64) ** 2))
+    d = theta0.size
+    for r in range(4):
+        # E ||eps_r||^2 = nu^2 ||theta0||^2 ; chi-square with d dof has relative sd sqrt(2/d)
+        assert np.sum(eps[r] ** 2) == pytest.approx(nu ** 2 * norm2, rel=5 * math.sqrt(2.0 / d))
+        assert abs(eps[r].mean()) < 5 * nu * math.sqrt(norm2 / d) / math.sqrt(d)
+        z = eps[r] / (nu * math.sqrt(norm2 / d))
+        assert stats.kstest(z, "norm").pvalue > 1e-3                  # Gaussian
+    c = np.corrcoef(eps)
+    assert np.all(np.abs(c[~np.eye(4, dtype=bool)]) < 5 / math.sqrt(d))   # replicas independent
+    # deterministic in (seed, replica, index); nu = 0 returns the checkpoint itself
+    assert np.array_equal(O.warm_noisy_init(theta0, 2, nu, 123), O.warm_noisy_init(theta0, 4, nu, 123)[:2])
+    assert not np.array_equal(O.warm_noisy_init(theta0, 1, nu, 124), O.warm_noisy_init(theta0, 1, nu, 123))
+    assert np.array_equal(O.warm_noisy_init(theta0, 3, 0.0, 5), np.broadcast_to(theta0, (3, d)))
+    assert np.array_equal(O.standard_normals(7, 1, 10), O.standard_normals(7, 1, 37)[:10])
+
+
+def test_box_muller_pairs_by_hand():
+    w = O.philox4x32_10((0, 2, 0, O.WARM_STREAM), (11, 0))
+    z = O.standard_normals(11, 2, 4)
+    for h in range(2):
+        u, v = (w[2 * h] + 1) / 2.0 ** 32, w[2 * h + 1] / 2.0 ** 32
+        assert z[2 * h] ** 2 + z[2 * h + 1] ** 2 == pytest.approx(-2 * math.log(u), rel=1e-12)
+        assert math.atan2(z[2 * h + 1], z[2 * h]) % (2 * math.pi) == pytest.approx(2 * math.pi * v, abs=1e-9)
