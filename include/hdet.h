@@ -161,6 +161,14 @@ int hdet_workspace_bytes(const hdet_config* cfg, int64_t plane_stride, size_t* p
  * params_dev.  Errors: HDET_EINVAL (bad argument, misaligned pointer), HDET_EHIP.           */
 int hdet_create(const hdet_config* cfg, const hdet_buffers* buffers, hdet_handle** out);
 
+/* Warm noisy initialisation (Sec. 3.5, Eq. 10): params_dev[r] <- theta0 + eps_r for every
+ * replica r, eps_r ~ N(0, nu^2 ||theta0||^2 / P) independently per replica and element (the
+ * paper uses nu = 0.01).  theta0_dev: [P] fp32 checkpoint in device memory, 16-byte aligned,
+ * not overlapping params_dev.  The noise is a pure function of (seed, replica, index)
+ * (Philox-4x32-10 + Box-Muller); the bf16 copy is refreshed.  Only before the first update:
+ * HDET_ESTATE once t > 0.                                                                   */
+int hdet_warm_init(hdet_handle* h, const float* theta0_dev, double nu, uint64_t seed);
+
 /* Forward, mean cross-entropy and backward of all N replicas on x_dev [N][B][d_in]
  * (fp32; rounded to bf16 on load in bf16 precision) and labels y_dev [N][B] int32 -- for
  * HDET_TRANSFORMER x_dev is token ids [N][B][S] int32 and y_dev the next-token targets

@@ -24,7 +24,7 @@ HDET_CH_LR, HDET_CH_DROPOUT, HDET_CH_WD = 0, 1, 2
 HDET_FUSE_CONVERGE = 1
 
 EXPORTS = [
-    "hdet_workspace_bytes", "hdet_create", "hdet_forward_backward", "hdet_fanout_step",
+    "hdet_workspace_bytes", "hdet_create", "hdet_warm_init", "hdet_forward_backward", "hdet_fanout_step",
     "hdet_converge", "hdet_autolr_update", "hdet_get_state", "hdet_set_state",
     "hdet_set_launch_shape", "hdet_last_error", "hdet_destroy",
 ]
@@ -113,6 +113,7 @@ def load_library(path: Optional[str] = None):
     lib.hdet_workspace_bytes.argtypes = [C.POINTER(hdet_config), C.c_int64, C.POINTER(C.c_size_t),
                                          C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     lib.hdet_create.argtypes = [C.POINTER(hdet_config), C.POINTER(hdet_buffers), C.POINTER(vp)]
+    lib.hdet_warm_init.argtypes = [vp, vp, C.c_double, C.c_uint64]
     lib.hdet_forward_backward.argtypes = [vp, vp, vp, C.POINTER(C.c_float)]
     lib.hdet_fanout_step.argtypes = [vp, vp, C.c_uint32]
     lib.hdet_converge.argtypes = [vp]
@@ -200,6 +201,10 @@ def hdet_create(cfg: hdet_config, params, opt_m, opt_v=None, grads=None, params_
     h = C.c_void_p()
     _check(load_library().hdet_create(C.byref(cfg), C.byref(buf), C.byref(h)))
     return h
+
+
+def hdet_warm_init(h, theta0, nu: float, seed: int):
+    _check(load_library().hdet_warm_init(h, _ptr(theta0), nu, seed), h)
 
 
 def hdet_forward_backward(h, x, y, want_losses: bool = False):

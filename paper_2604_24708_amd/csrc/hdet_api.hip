@@ -262,6 +262,21 @@ int hdet_forward_backward(hdet_handle* h, const void* x_dev, const int32_t* y_de
   return HDET_OK;
 }
 
+int hdet_warm_init(hdet_handle* h, const float* theta0_dev, double nu, uint64_t seed) {
+  if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
+  if (h->t != 0) return fail(h, HDET_ESTATE, "hdet_warm_init is only allowed before the first update");
+  if (!theta0_dev || !aligned16(theta0_dev)) return fail(h, HDET_EINVAL, "theta0_dev must be a 16-byte aligned device pointer");
+  if (!(nu >= 0.0)) return fail(h, HDET_EINVAL, "nu must be >= 0");
+  const int64_t p = param_count(h->cfg);
+  const float* lo = h->buf.params_dev;
+  const float* hi = lo + (int64_t)h->cfg.n_replicas * h->buf.plane_stride;
+  if (theta0_dev + p > lo && theta0_dev < hi) return fail(h, HDET_EINVAL, "theta0_dev must not overlap params_dev");
+  hipError_t e = hdet_launch_warm_init(theta0_dev, h->buf.params_dev, p, h->buf.plane_stride, h->cfg.n_replicas,
+                                       h->ctrl_dev, nu, seed, h->stream);
+  if (e != hipSuccess) return hip_fail(h, e, "warm initialisation kernels");
+  return write_shadow(h);
+}
+
 int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
   if (flags & ~HDET_FUSE_CONVERGE) return fail(h, HDET_EINVAL, "unknown flag");

@@ -26,7 +26,10 @@ struct hdet_ctrl {
   long long k;                                    // controller updates done
   int32_t controller_active;
   int32_t nonfinite;
+  double warm_sumsq;                              // ||theta0||^2 of the warm initialisation
+  double warm_partial[1024];                      // its per-block partial sums
 };
+#define HDET_WARM_PARTIALS 1024
 
 // h_{j,r} = h_bar_j * rho_{j, pi_j(r)} in fp64.  Channel 0 (learning rate) follows the host's
 // one-cycle value `eta_sched` until the controller has taken over.
@@ -88,6 +91,8 @@ hipError_t hdet_launch_converge(const hdet_converge_args& a, int variant, int bl
 hipError_t hdet_launch_shadow(const float* theta, uint16_t* shadow, int64_t n_params, int64_t stride,
                               int n_replicas, int blocks, hipStream_t stream);
 hipError_t hdet_launch_controller(const hdet_controller_args& a, hipStream_t stream);
+hipError_t hdet_launch_warm_init(const float* theta0, float* theta, int64_t n_params, int64_t stride, int n_replicas,
+                                 hdet_ctrl* ctrl, double nu, uint64_t seed, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
 // Replica-batched GEMMs.  The batch index z of a launch is split into up to three levels,

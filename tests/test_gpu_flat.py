@@ -252,3 +252,28 @@ def test_state_round_trip_resumes_bit_exactly():
     assert sa.k == sb.k and sa.base[0] == sb.base[0] and sa.vel[0] == sb.vel[0]
     assert [sa.perm[0][r] for r in range(4)] == [sb.perm[0][r] for r in range(4)]
     a.close(); b.close()
+
+
+@pytest.mark.parametrize("n,P", [(4, 100003), (8, 5), (3, 4096)])
+def test_warm_noisy_init_matches_oracle(n, P):
+    """Eq. 10: every replica starts from the checkpoint plus its own Gaussian perturbation."""
+    d = base_cfg(n_replicas=n)
+    run = FlatRun(d, P)
+    theta0 = (np.random.default_rng(3).standard_normal(P) * 0.05).astype(np.float32)
+    t0 = torch.from_numpy(theta0).to("cuda:0")
+    H.hdet_warm_init(run.h, t0, 0.01, 4242)
+    ref = O.warm_noisy_init(theta0, n, 0.01, 4242)
+    th = run.theta.cpu().numpy()
+    assert rel_err(th[:, :P], ref) <= 1e-6
+    assert np.all(th[:, P:] == run.pad)
+    eps = th[:, :P].astype(np.float64) - theta0
+    if P > 1000:
+        assert np.sum(eps[0] ** 2) == pytest.approx(1e-4 * np.sum(theta0.astype(np.float64) ** 2), rel=0.05)
+        assert abs(np.corrcoef(eps[0], eps[1])[0, 1]) < 0.02
+    with pytest.raises(H.HdetError):
+        H.hdet_warm_init(run.h, run.theta, 0.01, 1)              # overlaps the parameter planes
+    H.hdet_fanout_step(run.h, run.g, 0)
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_warm_init(run.h, t0, 0.01, 4242)                  # only before the first update
+    assert e.value.code == H.HDET_ESTATE
+    run.close()
