@@ -35,7 +35,8 @@ extern "C" {
 #endif
 
 #define HDET_MAX_REPLICAS 64   /* one wavefront holds one replica per lane in the controller */
-#define HDET_MAX_CH       4    /* explored hyperparameter channels (Remark 1)                */
+#define HDET_MAX_CH       8    /* explored hyperparameter channels (Remark 1)                */
+#define HDET_MAX_GROUPS   4    /* parameter groups with a learning-rate channel each        */
 #define HDET_MAX_LAYERS   16
 
 enum { HDET_OK = 0, HDET_EINVAL = -1, HDET_ESTATE = -2, HDET_EHIP = -3 };
@@ -100,8 +101,13 @@ typedef struct {
   int32_t  precision;       /* HDET_FP32 or HDET_BF16_GEMM_FP32_MASTER                       */
   int32_t  model_kind;      /* HDET_FLAT, HDET_MLP or HDET_TRANSFORMER                       */
   hdet_model_dims dims;
-  int32_t  n_extra_channels;           /* 0..HDET_MAX_CH-1                                   */
-  int32_t  reserved;
+  int32_t  n_extra_channels;           /* 0..HDET_MAX_CH - max(n_groups, 1)                  */
+  int32_t  n_groups;        /* 0 or 1: one learning-rate channel for all parameters; G > 1:
+                               parameter groups with a rate channel each (Sec. 3.4, "random
+                               reassignment across hyperparameters": own base rate, velocity
+                               and permutation per group, the same one-cycle until hand-over) */
+  int64_t  group_end[HDET_MAX_GROUPS]; /* group g is the slice [group_end[g-1], group_end[g]) of a
+                               parameter plane; ascending, multiples of 4, the last equals P  */
   hdet_channel extra[HDET_MAX_CH - 1];
   uint64_t seed;            /* keys the permutations of Eq. 9                                */
   void*    stream;          /* hipStream_t, borrowed; NULL = the default stream              */
@@ -137,7 +143,8 @@ typedef struct {
   int32_t nonfinite;          /* controller calls skipped because a loss was not finite      */
   int32_t n_replicas, n_channels;
   double  gamma;              /* decay in use for the learning-rate channel                  */
-  double  base[HDET_MAX_CH];  /* centre value per channel; [0] is meaningful once active     */
+  double  base[HDET_MAX_CH];  /* centre value per channel (rate channels of the groups first,
+                                 then the extra channels); rates are meaningful once active  */
   double  vel[HDET_MAX_CH];   /* velocity v of Eq. 7                                         */
   double  delta[HDET_MAX_CH]; /* last hypergradient (Eq. 6)                                  */
   double  w[HDET_MAX_REPLICAS];        /* last softmax weights (Eq. 4)                       */

@@ -295,8 +295,9 @@ def velocity_update(vel: float, base: float, delta: float, beta: float, gamma: f
 # --------------------------------------------------------------------------------------
 @dataclass
 class Channel:
-    """One explored scalar hyperparameter (Remark 1).  Channel 0 is always the learning
-    rate and its base follows the one-cycle schedule until the controller takes over."""
+    """One explored scalar hyperparameter (Remark 1).  The first channels are learning rates
+    (one per parameter group); their base follows the one-cycle schedule until the controller
+    takes over."""
     kind: int
     base: float
     alpha: float
@@ -330,7 +331,9 @@ class Config:
     seed: int = 7
     gamma_override: float = -1.0          # >= 0 replaces Eq. 8
     constant_lr: bool = False             # base schedule eta(t) = lr_max for all t
-    extra: List[Channel] = field(default_factory=list)   # channels 1.. (dropout, wd)
+    extra: List[Channel] = field(default_factory=list)   # channels after the rates (dropout, wd)
+    group_ends: List[int] = field(default_factory=list)  # parameter groups with a rate channel each:
+                                                         # group g = plane slice [ends[g-1], ends[g])
 
 
 class HDETOracle:
@@ -346,7 +349,10 @@ class HDETOracle:
     * The rates entering Eq. 5 are those in effect at the sync step.
     * Permutations are redrawn only when the controller runs (Algorithm 1).
     * Optimizer state is not averaged by converge (Eq. 3 names the parameters only).
-    * Channels other than the learning rate use gamma = 0 and are clamped to [lo, hi].
+    * Channels other than the learning rates use gamma = 0 and are clamped to [lo, hi].
+    * Parameter groups (Sec. 3.4: per-group rates, each with an independent permutation)
+      share one one-cycle schedule until hand-over; afterwards every group has its own base
+      rate and velocity, driven by the same weights w through its own permutation.
     """
 
     def __init__(self, cfg: Config, theta0: np.ndarray):
@@ -359,7 +365,9 @@ class HDETOracle:
         self.t = 0
         self.k = 0
         self.controller_active = False
-        self.channels = [Channel(CH_LR, cfg.lr_max, cfg.alpha, cfg.lam)] + list(cfg.extra)
+        self.n_lr = max(len(cfg.group_ends), 1)
+        self.group_ends = list(cfg.group_ends) if len(cfg.group_ends) > 1 else [theta0.shape[1]]
+        self.channels = [Channel(CH_LR, cfg.lr_max, cfg.alpha, cfg.lam) for _ in range(self.n_lr)] + list(cfg.extra)
         self.n_ch = len(self.channels)
         self.rho = [spread_multipliers(n, ch.alpha) for ch in self.channels]
         self.perm = [np.arange(n, dtype=np.int32) for _ in self.channels]
@@ -375,10 +383,10 @@ class HDETOracle:
         self.nonfinite = 0
 
     # ---- schedule ---------------------------------------------------------------
-    def base_lr(self, t: int) -> float:
-        """eta_bar used by update t (1-based)."""
+    def base_lr(self, t: int, group: int = 0) -> float:
+        """eta_bar used by update t (1-based) for a parameter group."""
         if self.controller_active:
-            return self.base[0]
+            return self.base[group]
         if self.cfg.constant_lr:
             return self.cfg.lr_max
         c = self.cfg
@@ -396,9 +404,9 @@ class HDETOracle:
                 return j
         return -1
 
-    def lr_table(self, t: int) -> np.ndarray:
-        """Per-replica learning rates handed to the update, rounded to fp32."""
-        return self.values(0, self.base_lr(t)).astype(np.float32)
+    def lr_table(self, t: int, group: int = 0) -> np.ndarray:
+        """Per-replica learning rates of a parameter group handed to the update, rounded to fp32."""
+        return self.values(group, self.base_lr(t, group)).astype(np.float32)
 
     def wd_table(self) -> np.ndarray:
         j = self.channel_index(CH_WD)
@@ -428,20 +436,24 @@ class HDETOracle:
             raise RuntimeError("step beyond total_steps")
         self.t += 1
         t = self.t
-        lr = self.lr_table(t)
         wd = self.wd_table()
-        self.lr_used = lr
+        self.lr_used = self.lr_table(t, 0)
         if c.grad_mode == GRAD_SHARED:
             gbar = shared_gradient(grads)
-        for r in range(n):
-            g = gbar if c.grad_mode == GRAD_SHARED else grads[r]
-            if c.optimizer == SGDM:
-                self.theta[r], self.m[r] = sgdm_update(self.theta[r], g, self.m[r], float(lr[r]),
-                                                       float(wd[r]), c.momentum, t == 1)
-            else:
-                self.theta[r], self.m[r], self.v[r] = adamw_update(
-                    self.theta[r], g, self.m[r], self.v[r], float(lr[r]), float(wd[r]),
-                    c.beta1, c.beta2, c.eps, t)
+        begin = 0
+        for grp, end in enumerate(self.group_ends):
+            lr = self.lr_table(t, grp)
+            sl = slice(begin, end)
+            for r in range(n):
+                g = gbar[sl] if c.grad_mode == GRAD_SHARED else grads[r][sl]
+                if c.optimizer == SGDM:
+                    self.theta[r, sl], self.m[r, sl] = sgdm_update(self.theta[r, sl], g, self.m[r, sl], float(lr[r]),
+                                                                   float(wd[r]), c.momentum, t == 1)
+                else:
+                    self.theta[r, sl], self.m[r, sl], self.v[r, sl] = adamw_update(
+                        self.theta[r, sl], g, self.m[r, sl], self.v[r, sl], float(lr[r]), float(wd[r]),
+                        c.beta1, c.beta2, c.eps, t)
+            begin = end
         if losses is not None:
             self.accumulate_loss(losses)
 
@@ -473,7 +485,9 @@ class HDETOracle:
             return
         if not self.controller_active:
             # hand-over: base = mean of the rates in effect = schedule value of this step
-            self.base[0] = self.base_lr(self.t)
+            eta = self.base_lr(self.t)
+            for g in range(self.n_lr):
+                self.base[g] = eta
             self.controller_active = True
         w = controller_weights(l_r, c.sigma)
         self.w = w

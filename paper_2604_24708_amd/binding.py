@@ -12,7 +12,8 @@ import os
 from typing import Optional, Sequence
 
 HDET_MAX_REPLICAS = 64
-HDET_MAX_CH = 4
+HDET_MAX_CH = 8
+HDET_MAX_GROUPS = 4
 HDET_MAX_LAYERS = 16
 
 HDET_OK, HDET_EINVAL, HDET_ESTATE, HDET_EHIP = 0, -1, -2, -3
@@ -57,7 +58,8 @@ class hdet_config(C.Structure):
         ("eps", C.c_double), ("weight_decay", C.c_double),
         ("precision", C.c_int32), ("model_kind", C.c_int32),
         ("dims", hdet_model_dims),
-        ("n_extra_channels", C.c_int32), ("reserved", C.c_int32),
+        ("n_extra_channels", C.c_int32), ("n_groups", C.c_int32),
+        ("group_end", C.c_int64 * HDET_MAX_GROUPS),
         ("extra", hdet_channel * (HDET_MAX_CH - 1)),
         ("seed", C.c_uint64), ("stream", C.c_void_p),
     ]
@@ -160,6 +162,7 @@ def make_config(**kw) -> hdet_config:
     cfg.seed = 7
     widths = kw.pop("widths", None)
     extra = kw.pop("extra", None)
+    group_end = kw.pop("group_end", None)
     for key in ("n_params", "batch", "n_blocks", "d_model", "n_heads", "d_ff", "seq_len", "vocab"):
         if key in kw:
             setattr(cfg.dims, key, kw.pop(key))
@@ -167,6 +170,10 @@ def make_config(**kw) -> hdet_config:
         cfg.dims.n_layers = len(widths) - 1
         for i, wd in enumerate(widths):
             cfg.dims.widths[i] = wd
+    if group_end is not None:
+        cfg.n_groups = len(group_end)
+        for g, end in enumerate(group_end):
+            cfg.group_end[g] = end
     if extra is not None:
         cfg.n_extra_channels = len(extra)
         for j, ch in enumerate(extra):

@@ -99,7 +99,19 @@ int validate(const hdet_config* c, std::string* why) {
   } else {
     return bad("unknown model_kind");
   }
-  if (c->n_extra_channels < 0 || c->n_extra_channels > HDET_MAX_CH - 1) return bad("n_extra_channels out of range");
+  if (c->n_groups < 0 || c->n_groups > HDET_MAX_GROUPS) return bad("n_groups out of range");
+  const int n_lr = c->n_groups > 1 ? c->n_groups : 1;
+  if (c->n_extra_channels < 0 || c->n_extra_channels > HDET_MAX_CH - n_lr) return bad("n_extra_channels out of range");
+  if (c->n_groups > 1) {
+    const int64_t p = param_count(*c);
+    int64_t prev = 0;
+    for (int g = 0; g < c->n_groups; ++g) {
+      const int64_t e = c->group_end[g];
+      if (e <= prev || e > p || (g + 1 < c->n_groups && (e & 3))) return bad("group_end must ascend in multiples of 4 up to P");
+      prev = e;
+    }
+    if (prev != p) return bad("the last group_end must equal P");
+  }
   int seen_wd = 0, seen_do = 0;
   for (int j = 0; j < c->n_extra_channels; ++j) {
     const hdet_channel& ch = c->extra[j];
@@ -125,6 +137,7 @@ void fill_ctrl_initial(const hdet_handle* h, hdet_ctrl* c) {
     for (int r = 0; r < n; ++r) c->perm[j][r] = r;
   }
   for (int r = 0; r < n; ++r) c->w[r] = 1.0 / n;
+  c->n_lr = h->n_lr;
 }
 
 int upload_ctrl(hdet_handle* h, const hdet_ctrl& c) {
@@ -206,19 +219,22 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
   h->tf = nullptr;
   h->drop_channel = -1;
   h->ctrl_dev = nullptr;
-  h->n_channels = 1 + cfg->n_extra_channels;
+  h->n_lr = cfg->n_groups > 1 ? cfg->n_groups : 1;
+  h->n_channels = h->n_lr + cfg->n_extra_channels;
   h->wd_channel = -1;
   memset(h->channels, 0, sizeof(h->channels));
-  h->channels[0].kind = HDET_CH_LR;
-  h->channels[0].base = cfg->lr_max;
-  h->channels[0].alpha = cfg->alpha;
-  h->channels[0].lambda = cfg->lambda;
-  h->channels[0].lo = 0.0;
-  h->channels[0].hi = INFINITY;
+  for (int g = 0; g < h->n_lr; ++g) {
+    h->channels[g].kind = HDET_CH_LR;
+    h->channels[g].base = cfg->lr_max;
+    h->channels[g].alpha = cfg->alpha;
+    h->channels[g].lambda = cfg->lambda;
+    h->channels[g].lo = 0.0;
+    h->channels[g].hi = INFINITY;
+  }
   for (int j = 0; j < cfg->n_extra_channels; ++j) {
-    h->channels[j + 1] = cfg->extra[j];
-    if (cfg->extra[j].kind == HDET_CH_WD) h->wd_channel = j + 1;
-    if (cfg->extra[j].kind == HDET_CH_DROPOUT) h->drop_channel = j + 1;
+    h->channels[h->n_lr + j] = cfg->extra[j];
+    if (cfg->extra[j].kind == HDET_CH_WD) h->wd_channel = h->n_lr + j;
+    if (cfg->extra[j].kind == HDET_CH_DROPOUT) h->drop_channel = h->n_lr + j;
   }
 
   e = hipMalloc((void**)&h->ctrl_dev, sizeof(hdet_ctrl));
@@ -315,8 +331,20 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   a.momentum = (float)c.momentum;
 
   const bool fuse = (flags & HDET_FUSE_CONVERGE) && (t % c.sync_interval == 0);
-  hipError_t e = hdet_launch_update(a, c.optimizer, c.grad_mode == HDET_GRAD_SHARED, fuse, h->tune_variant, default_blocks(h), h->stream);
-  if (e != hipSuccess) return hip_fail(h, e, "update kernel");
+  // one launch per parameter group: the group's slice of every plane with the group's rate channel
+  int64_t begin = 0;
+  for (int grp = 0; grp < h->n_lr; ++grp) {
+    const int64_t end = h->n_lr > 1 ? c.group_end[grp] : a.n_params;
+    hdet_update_args ga = a;
+    ga.theta += begin; ga.grad += begin; ga.m += begin;
+    if (ga.v) ga.v += begin;
+    if (ga.shadow) ga.shadow += begin;
+    ga.n_params = end - begin;
+    ga.lr_channel = grp;
+    hipError_t e = hdet_launch_update(ga, c.optimizer, c.grad_mode == HDET_GRAD_SHARED, fuse, h->tune_variant, default_blocks(h), h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "update kernel");
+    begin = end;
+  }
   h->t = t;
   if (fuse) h->converged_at_t = t;
   return HDET_OK;
@@ -352,6 +380,7 @@ int hdet_autolr_update(hdet_handle* h, const double* interval_losses_host) {
   a.run_controller = c.autolr_enabled && h->t >= c.warm_steps;
   a.n_replicas = c.n_replicas;
   a.n_channels = h->n_channels;
+  a.n_lr = h->n_lr;
   a.sync_interval = c.sync_interval;
   a.eta_sched = onecycle(c, h->t - 1);
   a.sigma = c.sigma;

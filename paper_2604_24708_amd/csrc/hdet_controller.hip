@@ -104,12 +104,12 @@ __global__ __launch_bounds__(64) void hdet_controller_kernel(const hdet_controll
 
   for (int j = 0; j < a.n_channels; ++j) {
     // at hand-over the base is the mean of the rates in effect: the schedule value
-    const double b = (j == 0 && !was_active) ? a.eta_sched : c->base[j];
+    const double b = (j < a.n_lr && !was_active) ? a.eta_sched : c->base[j];
     const double h = mine ? b * c->rho[j][c->perm[j][lane]] : 0.0;
     // Eq. 5-6: Delta = sum_r w_r h_r - (1/N) sum_r h_r = sum_r (w_r - 1/N) h_r
     const double d = ordered_sum(mine ? (w - inv_n) * h : 0.0, n);
-    // Eq. 7 (gamma of Eq. 8 for the learning rate only)
-    const double gamma = j == 0 ? a.gamma : 0.0;
+    // Eq. 7 (gamma of Eq. 8 for the learning rates only)
+    const double gamma = j < a.n_lr ? a.gamma : 0.0;
     const double nv = a.beta * c->vel[j] + (1.0 - a.beta) * d;
     double nb = b * (1.0 - gamma) + nv * a.lambda[j];
     nb = nb < a.lo[j] ? a.lo[j] : nb;

@@ -26,16 +26,18 @@ struct hdet_ctrl {
   long long k;                                    // controller updates done
   int32_t controller_active;
   int32_t nonfinite;
+  int32_t n_lr;                                   // channels 0..n_lr-1 are learning rates (one per group)
+  int32_t pad_;
   double warm_sumsq;                              // ||theta0||^2 of the warm initialisation
   double warm_partial[1024];                      // its per-block partial sums
 };
 #define HDET_WARM_PARTIALS 1024
 
-// h_{j,r} = h_bar_j * rho_{j, pi_j(r)} in fp64.  Channel 0 (learning rate) follows the host's
+// h_{j,r} = h_bar_j * rho_{j, pi_j(r)} in fp64.  The learning-rate channels follow the host's
 // one-cycle value `eta_sched` until the controller has taken over.
 __device__ __forceinline__ double hdet_channel_value(const hdet_ctrl* c, int j, int r,
                                                      double eta_sched) {
-  const double b = (j == 0 && !c->controller_active) ? eta_sched : c->base[j];
+  const double b = (j < c->n_lr && !c->controller_active) ? eta_sched : c->base[j];
   return b * c->rho[j][c->perm[j][r]];
 }
 
@@ -53,6 +55,7 @@ struct hdet_update_args {
   int64_t n_params;        // P
   int64_t stride;          // plane stride in elements
   int32_t n_replicas;
+  int32_t lr_channel;      // learning-rate channel of the parameter group being updated
   int32_t wd_channel;      // channel index of a weight-decay channel or -1
   int32_t first_step;      // SGDM: buf <- g'
   double eta_sched;        // one-cycle value of this step
@@ -77,6 +80,7 @@ struct hdet_controller_args {
   int32_t use_injected;
   int32_t run_controller;              // enabled and t >= S_warm
   int32_t n_replicas, n_channels;
+  int32_t n_lr;                        // learning-rate channels come first
   int32_t sync_interval;
   double eta_sched;                    // one-cycle value of the sync step (hand-over)
   double sigma, beta, gamma;
@@ -184,7 +188,8 @@ struct hdet_handle {
   int64_t converged_at_t;    // t whose parameters are already averaged
   double gamma;
   int n_channels;
-  hdet_channel channels[HDET_MAX_CH];   // [0] = learning rate
+  int n_lr;                             // learning-rate channels (parameter groups) come first
+  hdet_channel channels[HDET_MAX_CH];
   int wd_channel;
   int32_t tune_variant, tune_blocks;
   int n_cu;

@@ -74,7 +74,7 @@ struct rep_scalars {
 
 __device__ __forceinline__ rep_scalars replica_scalars(const hdet_update_args& a, int r) {
   rep_scalars s;
-  s.lr = (float)hdet_channel_value(a.ctrl, 0, r, a.eta_sched);
+  s.lr = (float)hdet_channel_value(a.ctrl, a.lr_channel, r, a.eta_sched);
   s.wd = a.wd_channel >= 0 ? (float)hdet_channel_value(a.ctrl, a.wd_channel, r, 0.0) : (float)a.wd_const;
   s.decay = (float)(1.0 - (double)s.lr * (double)s.wd);
   s.step = (float)((double)s.lr * a.inv_bc1);
@@ -115,7 +115,7 @@ template <int OPT>
 __global__ __launch_bounds__(kThreads) void hdet_update_plane_kernel(const hdet_update_args a) {
   const int r = blockIdx.y;
   const rep_scalars s = replica_scalars(a, r);
-  if (blockIdx.x == 0 && threadIdx.x == 0) a.ctrl_out->lr_used[r] = s.lr;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && a.lr_channel == 0) a.ctrl_out->lr_used[r] = s.lr;
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= (a.n_params >> 2)) return;
   const int64_t off = (int64_t)r * a.stride + (i << 2);
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void hdet_update_wave_kernel(const 
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int grp = w / n, r = w - grp * n;
   const rep_scalars s = replica_scalars(a, r);
-  if (blockIdx.x == 0 && grp == 0 && lane == 0) a.ctrl_out->lr_used[r] = s.lr;
+  if (blockIdx.x == 0 && grp == 0 && lane == 0 && a.lr_channel == 0) a.ctrl_out->lr_used[r] = s.lr;
   const int64_t i = ((int64_t)blockIdx.x * groups + grp) * 64 + lane;
   const bool ok = i < (a.n_params >> 2);
   const int64_t off = (int64_t)r * a.stride + (i << 2);
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(kThreads) void hdet_update_loop_kernel(const hdet_u
   __shared__ rep_scalars s[HDET_MAX_REPLICAS];
   if ((int)threadIdx.x < a.n_replicas) {
     s[threadIdx.x] = replica_scalars(a, threadIdx.x);
-    if (blockIdx.x == 0) a.ctrl_out->lr_used[threadIdx.x] = s[threadIdx.x].lr;
+    if (blockIdx.x == 0 && a.lr_channel == 0) a.ctrl_out->lr_used[threadIdx.x] = s[threadIdx.x].lr;
   }
   __syncthreads();
   const int64_t nvec = a.n_params >> 2;

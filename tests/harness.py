@@ -41,17 +41,19 @@ def oracle_config(d: dict) -> O.Config:
         kw["lam"] = d["lambda_"]
     kw["autolr_enabled"] = bool(d.get("autolr_enabled", False))
     kw["constant_lr"] = bool(d.get("constant_lr", False))
-    return O.Config(extra=extra, **kw)
+    return O.Config(extra=extra, group_ends=list(d.get("group_end", [])), **kw)
 
 
 def library_config(d: dict, **model):
     import paper_2604_24708_amd as H
-    kw = {k: v for k, v in d.items() if k != "extra"}
+    kw = {k: v for k, v in d.items() if k not in ("extra", "group_end")}
     kw["autolr_enabled"] = int(bool(d.get("autolr_enabled", False)))
     kw["constant_lr"] = int(bool(d.get("constant_lr", False)))
     kw.update(model)
     if d.get("extra"):
         kw["extra"] = d["extra"]
+    if d.get("group_end"):
+        kw["group_end"] = d["group_end"]
     return H.make_config(**kw)
 
 
@@ -66,7 +68,7 @@ def check_state(st, orc: O.HDETOracle, scalar_rtol=1e-12, lr_ulps=1):
     for j in range(orc.n_ch):
         assert [st.perm[j][r] for r in range(n)] == orc.perm[j].tolist(), f"perm[{j}]"
         assert np.allclose([st.rho[j][r] for r in range(n)], orc.rho[j], rtol=1e-15, atol=0)
-        if j > 0 or orc.controller_active:
+        if j >= orc.n_lr or orc.controller_active:
             assert np.isclose(st.base[j], orc.base[j], rtol=scalar_rtol, atol=1e-300), f"base[{j}]"
         # Delta and v are differences of nearly equal terms of the size of the base value:
         # their error is measured against that size

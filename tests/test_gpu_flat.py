@@ -277,3 +277,25 @@ def test_warm_noisy_init_matches_oracle(n, P):
         H.hdet_warm_init(run.h, t0, 0.01, 4242)                  # only before the first update
     assert e.value.code == H.HDET_ESTATE
     run.close()
+
+
+@pytest.mark.parametrize("opt,mode", [(O.ADAMW, O.GRAD_PER_REPLICA), (O.SGDM, O.GRAD_SHARED)])
+def test_parameter_groups_with_own_rate_channels(opt, mode):
+    """Four parameter groups, each with its own base rate, velocity and permutation, plus a
+    weight-decay channel: 5 channels driven by the same weights."""
+    P = 70001
+    extra = [(O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
+    d = base_cfg(n_replicas=8, optimizer=opt, grad_mode=mode, group_end=[4096, 20000, 50004, P], extra=extra,
+                 total_steps=400)
+    run = FlatRun(d, P)
+    for t in range(1, 21):
+        run.step(t, fuse=(t % 8 == 0))
+        run.compare(tol_at(t))
+    st = H.hdet_get_state(run.h)
+    assert st.n_channels == 5 and st.k == 4
+    assert len({tuple(st.perm[j][r] for r in range(8)) for j in range(5)}) >= 4
+    assert len({st.base[j] for j in range(4)}) == 4 and min(st.base[j] for j in range(4)) > 0.0
+    run.close()
+    bad = base_cfg(n_replicas=8, group_end=[4098, P])             # not a multiple of 4
+    with pytest.raises(H.HdetError):
+        FlatRun(bad, P)

@@ -468,3 +468,28 @@ def test_box_muller_pairs_by_hand():
         u, v = (w[2 * h] + 1) / 2.0 ** 32, w[2 * h + 1] / 2.0 ** 32
         assert z[2 * h] ** 2 + z[2 * h + 1] ** 2 == pytest.approx(-2 * math.log(u), rel=1e-12)
         assert math.atan2(z[2 * h + 1], z[2 * h]) % (2 * math.pi) == pytest.approx(2 * math.pi * v, abs=1e-9)
+
+
+def test_parameter_groups_have_independent_rate_channels():
+    """Four parameter groups as in the paper's experiment: same one-cycle before hand-over,
+    then own base, velocity and permutation each; with one group the old behaviour."""
+    ends = [8, 16, 28, 33]
+    cfg = _cfg(n_replicas=8, group_ends=ends)
+    orc, hist = _run(cfg)
+    assert orc.n_lr == 4 and orc.n_ch == 4 and orc.k == 8
+    assert len({tuple(p.tolist()) for p in orc.perm}) == 4                   # independent permutations
+    assert len({round(b, 15) for b in orc.base}) == 4                         # bases drift apart
+    for g in range(4):
+        lr = orc.lr_table(40, g)
+        assert np.allclose(np.sort(lr) / orc.base[g], O.spread_multipliers(8, 0.2), rtol=1e-6)
+    # before hand-over every group used the same rates: identical to the single-group run
+    one, hist1 = _run(_cfg(n_replicas=8))
+    assert np.array_equal(hist[10][0], hist1[10][0])
+    # a group's slice only ever sees its own rate: zero gradient outside group 2 leaves the rest untouched
+    orc2 = O.HDETOracle(_cfg(n_replicas=2, group_ends=ends, optimizer=O.SGDM, momentum=0.0, autolr_enabled=False),
+                        I.flat_theta0(2, 33, 5))
+    g = np.zeros((2, 33), np.float32); g[:, 16:28] = 1.0
+    before = orc2.theta.copy()
+    orc2.fanout_step(g, [0.0, 0.0])
+    assert np.array_equal(before[:, :16], orc2.theta[:, :16]) and np.array_equal(before[:, 28:], orc2.theta[:, 28:])
+    assert not np.array_equal(before[:, 16:28], orc2.theta[:, 16:28])
