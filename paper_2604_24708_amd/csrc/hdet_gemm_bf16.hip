@@ -1,6 +1,9 @@
 // Replica-batched bf16 GEMM on the gfx950 matrix cores for the "Forward + backward" of
 // Algorithm 1 in mixed precision: bf16 operands, fp32 accumulation, N independent weight
-// sets with the replica on blockIdx.z.
+// sets with the replica on blockIdx.z.  This file holds the entry point and the general
+// kernel, which takes any shape, leading dimension and alignment; products whose operands are
+// made of whole, aligned 16-byte chunks are routed to the LDS-direct kernel
+// (hdet_gemm_bf16_dma.hip).
 //
 //   C(m,n) = sum_k A(m,k) * B(k,n)          A, B bfloat16; C fp32 or bfloat16
 //
@@ -18,10 +21,9 @@
 //     transposed copy of weights or activations ever exists in HBM.
 //
 // Tiling: each wavefront owns a 64x64 output tile (2x2 blocks of v_mfma_f32_32x32x16_bf16); a
-// block is 2x2 wavefronts (128x128 tile) or, for m >= 192, 4x2 wavefronts (256x128 tile, 512
-// threads).  K step 32, LDS double-buffered (one barrier per K step), the next step's global
-// loads in flight during the MFMAs; launch indices are remapped so that each XCD's L2 serves a
-// contiguous range of tiles.
+// block is 2x2 wavefronts (128x128 tile).  K step 32, LDS double-buffered (one barrier per K
+// step), the next step's global loads in flight during the MFMAs; launch indices are remapped so
+// that each XCD's L2 serves a contiguous range of tiles.
 
 #include "hdet_internal.h"
 
@@ -51,15 +53,9 @@ __device__ __forceinline__ unsigned short f2bf(float x) {
 }
 __device__ __forceinline__ float bf2f(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
 
-// 8 consecutive elements starting at src[idx], of which the first `valid` exist (others 0).
-// FAST: the host has checked that every chunk is 16-byte aligned and either whole or absent
-// (leading dimensions, extents along the chunk axis and replica strides multiples of 8), so the
-// load is one branch-free 128-bit access; an absent chunk reads src[0..7] and is replaced by
-// zeros only when it is written to LDS -- touching the loaded value any earlier would make the
-// wavefront wait for the load and undo the prefetch.
-template <bool FAST>
+// 8 consecutive elements starting at src[idx], of which the first `valid` exist (others 0);
+// one 128-bit access when the chunk is whole and 16-byte aligned
 __device__ __forceinline__ us8 load8(const uint16_t* src, int64_t idx, int valid, bool vec_ok) {
-  if (FAST) return *reinterpret_cast<const us8*>(src + (valid > 0 ? idx : 0));
   if (valid >= 8 && vec_ok) return *reinterpret_cast<const us8*>(src + idx);
   us8 r = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -71,15 +67,13 @@ __device__ __forceinline__ us8 load8(const uint16_t* src, int64_t idx, int valid
 // One operand tile: ROWS (128 or 256) rows of the output dimension x 32 of the contraction.
 // KMAJOR: element (row, k) at src[row * ld + k], LDS tile[row][k];
 // otherwise at src[k * ld + row], LDS tile[k][row].
-template <bool KMAJOR, bool FAST, int ROWS, int THREADS>
+template <bool KMAJOR, int ROWS, int THREADS>
 struct operand {
   static constexpr int NCH = ROWS * 4 / THREADS;   // 8-element chunks per thread and K step
   static constexpr int RCH = ROWS / 8;         // chunks per k-row of a [k][row] tile
   us8 reg[NCH];
-  unsigned absent;                             // FAST: bit i set if chunk i lies outside the operand
   __device__ __forceinline__ void fetch(const uint16_t* src, int64_t ld, int row0, int rows, int k0, int kdim,
                                         bool vec_ok, int tid) {
-    absent = 0u;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * THREADS;
@@ -87,21 +81,19 @@ struct operand {
       if (KMAJOR) {
         const int row = row0 + (c >> 2), k = k0 + ((c & 3) << 3);
         valid = row < rows ? kdim - k : 0;
-        reg[i] = load8<FAST>(src, (int64_t)row * ld + k, valid, vec_ok);
+        reg[i] = load8(src, (int64_t)row * ld + k, valid, vec_ok);
       } else {
         const int k = k0 + c / RCH, row = row0 + ((c % RCH) << 3);
         valid = k < kdim ? rows - row : 0;
-        reg[i] = load8<FAST>(src, (int64_t)k * ld + row, valid, vec_ok);
+        reg[i] = load8(src, (int64_t)k * ld + row, valid, vec_ok);
       }
-      if (FAST && valid <= 0) absent |= 1u << i;
     }
   }
   __device__ __forceinline__ void commit(uint16_t* tile, int tid) const {
-    const us8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * THREADS;
-      const us8 v = (FAST && ((absent >> i) & 1u)) ? zero : reg[i];
+      const us8 v = reg[i];
       if (KMAJOR) *reinterpret_cast<us8*>(tile + (c >> 2) * LDK + ((((c & 3) ^ (c >> 4)) & 3) << 3)) = v;
       else *reinterpret_cast<us8*>(tile + (c / RCH) * ldr(ROWS) + ((c % RCH) << 3)) = v;
     }
@@ -130,7 +122,7 @@ struct operand {
 
 // WMT x WNT: 32x32 MFMA blocks per wavefront in m and n; WGM x 2 wavefronts per block
 // (WGM = 2: 256 threads, WGM = 4: 512 threads), block tile (32 WMT WGM) x (64 WNT).
-template <bool A_KMAJOR, bool B_KMAJOR, int EPI, bool FAST, int WMT, int WNT, int WGM>
+template <bool A_KMAJOR, bool B_KMAJOR, int EPI, int WMT, int WNT, int WGM>
 __global__ __launch_bounds__(128 * WGM, WGM) void hdet_bgemm_kernel(const hdet_bgemm_args g) {
   constexpr int TM = 32 * WMT * WGM, TN = 64 * WNT, THREADS = 128 * WGM;
   __shared__ __attribute__((aligned(16))) uint16_t As[2][tile_elems(TM)];
@@ -169,11 +161,11 @@ __global__ __launch_bounds__(128 * WGM, WGM) void hdet_bgemm_kernel(const hdet_b
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   // One register stage: the global loads of K step kt + 1 are issued before the MFMAs of step
-  // kt and written to the other LDS buffer after them (one barrier per step); a second block
-  // on the same CU covers the rest of the memory latency.  The loop body is free of conditions:
-  // the step past the end loads nothing (all chunks absent) and its zeros are never used.
-  operand<A_KMAJOR, FAST, TM, THREADS> oa;
-  operand<B_KMAJOR, FAST, TN, THREADS> ob;
+  // kt and written to the other LDS buffer after them (one barrier per step); other blocks
+  // on the same CU cover the rest of the memory latency.  The step past the end loads nothing
+  // (all chunks absent) and its zeros are never used.
+  operand<A_KMAJOR, TM, THREADS> oa;
+  operand<B_KMAJOR, TN, THREADS> ob;
   const int nk = (g.k + TK - 1) / TK;
   oa.fetch(A, g.lda, m0, g.m, 0, g.k, a_vec, tid);
   ob.fetch(B, g.ldb, n0, g.n, 0, g.k, b_vec, tid);
@@ -189,9 +181,9 @@ __global__ __launch_bounds__(128 * WGM, WGM) void hdet_bgemm_kernel(const hdet_b
     for (int ks = 0; ks < TK; ks += 16) {
       bf16x8 af[WMT], bfr[WNT];
 #pragma unroll
-      for (int i = 0; i < WMT; ++i) af[i] = operand<A_KMAJOR, FAST, TM, THREADS>::fragment(As[buf], wm + i * 32, ks, lane);
+      for (int i = 0; i < WMT; ++i) af[i] = operand<A_KMAJOR, TM, THREADS>::fragment(As[buf], wm + i * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < WNT; ++j) bfr[j] = operand<B_KMAJOR, FAST, TN, THREADS>::fragment(Bs[buf], wn + j * 32, ks, lane);
+      for (int j = 0; j < WNT; ++j) bfr[j] = operand<B_KMAJOR, TN, THREADS>::fragment(Bs[buf], wn + j * 32, ks, lane);
 #pragma unroll
       for (int i = 0; i < WMT; ++i)
 #pragma unroll
@@ -240,28 +232,14 @@ __global__ __launch_bounds__(128 * WGM, WGM) void hdet_bgemm_kernel(const hdet_b
     }
 }
 
-static bool chunk_regular(const void* base, int64_t ld, const int64_t* bs, int chunk_extent) {
-  return (ld & 7) == 0 && ((bs[0] | bs[1] | bs[2]) & 7) == 0 && (chunk_extent & 7) == 0 &&
-         (reinterpret_cast<uintptr_t>(base) & 15) == 0;
-}
-
 hipError_t hdet_launch_bgemm(const hdet_bgemm_args& g_in, bool a_kmajor, bool b_kmajor, int epi, int batch,
                              hipStream_t s) {
   hdet_bgemm_args g = g_in;
   if (g.n1 < 1) g.n1 = 1;
   if (g.n2 < 1) g.n2 = 1;
-  // a chunk is 8 elements along the operand's contiguous axis: k if k-major, else the row axis
-  const bool fast = chunk_regular(g.a, g.lda, g.a_s, a_kmajor ? g.k : g.m) &&
-                    chunk_regular(g.b, g.ldb, g.b_s, b_kmajor ? g.k : g.n);
-  const bool big = fast && g.m >= 192 && g.n >= 96;       // 256x128 tiles with 8 wavefronts, else 128x128 with 4
-  const int tm = big ? 256 : 128, tn = 128;
-  dim3 grid((g.n + tn - 1) / tn, (g.m + tm - 1) / tm, batch);
-#define HDET_BGEMM(AK, BK, E)                                                                                 \
-  do {                                                                                                        \
-    if (big) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, true, 2, 2, 4>), grid, dim3(512), 0, s, g);      \
-    else if (fast) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, true, 2, 2, 2>), grid, dim3(256), 0, s, g); \
-    else hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, false, 2, 2, 2>), grid, dim3(256), 0, s, g);         \
-  } while (0)
+  if (hdet_bgemm_dma_eligible(g, a_kmajor, b_kmajor, epi)) return hdet_launch_bgemm_dma(g, a_kmajor, b_kmajor, epi, batch, s);
+  dim3 grid((g.n + 127) / 128, (g.m + 127) / 128, batch);
+#define HDET_BGEMM(AK, BK, E) hipLaunchKernelGGL((hdet_bgemm_kernel<AK, BK, E, 2, 2, 2>), grid, dim3(256), 0, s, g)
 #define HDET_BGEMM_EPI(AK, BK)                                                                         \
   switch (epi) {                                                                                       \
     case HDET_EPI_F32: HDET_BGEMM(AK, BK, HDET_EPI_F32); break;                                        \

@@ -150,6 +150,12 @@ struct hdet_bgemm_args {
 // at b[k*ldb + n].  (true,true) forward, (true,false) dgrad, (false,false) wgrad.
 hipError_t hdet_launch_bgemm(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi, int batch,
                              hipStream_t stream);
+// LDS-direct fast path (hdet_gemm_bf16_dma.hip): taken by hdet_launch_bgemm when `eligible` (operands of
+// whole, 16-byte aligned chunks; C, bias and mask addressable 4 columns at a time; batch-item extents
+// below 2 GiB); n1, n2 >= 1 on entry.
+bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi);
+hipError_t hdet_launch_bgemm_dma(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi, int batch,
+                                 hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
 // MLP forward/backward (hdet_mlp.hip)

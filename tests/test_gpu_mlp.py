@@ -260,16 +260,21 @@ def test_bf16_loss_curve_within_1e2(widths, batch, n, steps):
     run.close()
 
 
-@pytest.mark.parametrize("widths,batch,n", [([64, 128, 10], 32, 4), ([70, 200, 33], 50, 3), ([256, 384, 136], 160, 2),
-                                            ([1024, 512, 1000], 256, 2)])
-def test_bf16_gradients_at_device_parameters(widths, batch, n):
+# The last three cases are sized so that every tile shape of the LDS-direct GEMM kernel runs in
+# each operand order (256x256 and 256x128 tiles with K steps of 64 and 32, ragged m and k edges,
+# a K extent of 8); only the first and last replica are checked there to bound the oracle's time.
+@pytest.mark.parametrize("widths,batch,n,check", [([64, 128, 10], 32, 4, None), ([70, 200, 33], 50, 3, None),
+                                                  ([256, 384, 136], 160, 2, None), ([1024, 512, 1000], 256, 2, None),
+                                                  ([1024, 4096, 2048, 1000], 512, 8, (0, 7)),
+                                                  ([1024, 2048, 8], 1024, 8, (0, 7)), ([512, 2048, 8], 1024, 8, (0, 7))])
+def test_bf16_gradients_at_device_parameters(widths, batch, n, check):
     d = cfg0(n_replicas=n, optimizer=O.ADAMW, total_steps=4)
     run = MlpRun(d, widths, batch, bf16=True)
     x, y = I.mlp_batch(n, batch, widths[0], I.SEED_DATA, 1, widths, I.SEED_TEACHER)
     out = H.hdet_forward_backward(run.h, torch.from_numpy(x).to("cuda:0"), torch.from_numpy(y).to("cuda:0"),
                                   want_losses=True)
     g_dev = run.g.cpu().numpy()[:, :run.P]
-    for r in range(n):
+    for r in (check or range(n)):
         loss, g = M.mlp_loss_and_grad(run.orc.theta[r], x[r], y[r], widths, bf16=True)
         assert abs(out[r] - loss) <= 2e-3
         off = 0
