@@ -73,6 +73,20 @@ __device__ __forceinline__ void hdet_st4(uint16_t* p, const hdet_f4& x) {
   *reinterpret_cast<hdet_u2v*>(p) = u;
 }
 
+// the same accesses marked non-temporal: data that is touched once and is larger than the caches
+__device__ __forceinline__ hdet_f4 hdet_ld4_stream(const float* p) {
+  const hdet_f4v a = __builtin_nontemporal_load(reinterpret_cast<const hdet_f4v*>(p));
+  hdet_f4 r = {{a[0], a[1], a[2], a[3]}};
+  return r;
+}
+__device__ __forceinline__ void hdet_st4_stream(float* p, const hdet_f4& x) {
+  __builtin_nontemporal_store((hdet_f4v){x.v[0], x.v[1], x.v[2], x.v[3]}, reinterpret_cast<hdet_f4v*>(p));
+}
+__device__ __forceinline__ void hdet_st4_stream(uint16_t* p, const hdet_f4& x) {
+  const hdet_u2v u = {hdet_bf16_bits(x.v[0]) | (hdet_bf16_bits(x.v[1]) << 16), hdet_bf16_bits(x.v[2]) | (hdet_bf16_bits(x.v[3]) << 16)};
+  __builtin_nontemporal_store(u, reinterpret_cast<hdet_u2v*>(p));
+}
+
 __device__ __forceinline__ float hdet_wave_sum(float x) {
   for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
   return x;

@@ -86,13 +86,15 @@ __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const in
   if (lane == 0) row_loss[gr] = logf(se) - (z[y] - mx);
 }
 
-// Wide rows (2048 <= classes <= 32768, classes % 4 == 0): one 256-thread block per row, the row
-// held in registers (thread t owns the 4-element chunks t, t + 256, ...), so the logits are
-// read once.  Same formulas as xent_kernel.
-template <typename T, int NV>
-__global__ __launch_bounds__(256) void xent_row_kernel(const float* logits, const int32_t* labels, int rows, int classes,
-                                                       T* dlogits, float* row_loss) {
-  __shared__ float red[4];
+// Wide rows (2048 <= classes <= 32768, classes % 4 == 0): one block of BS threads per row, the row
+// held in registers (thread t owns the 4-element chunks t, t + BS, ...), so the logits are
+// read once; logits and their gradient are streamed past the caches.  Same formulas as
+// xent_kernel.
+template <typename T, int BS, int NV>
+__global__ __launch_bounds__(BS) void xent_row_kernel(const float* logits, const int32_t* labels, int rows, int classes,
+                                                      T* dlogits, float* row_loss) {
+  constexpr int NW = BS / 64;
+  __shared__ float red[NW];
   const int64_t gr = (int64_t)blockIdx.y * rows + blockIdx.x;
   const float* z = logits + gr * classes;
   const int c4 = classes >> 2, tid = threadIdx.x;
@@ -100,9 +102,9 @@ __global__ __launch_bounds__(256) void xent_row_kernel(const float* logits, cons
   float mx = -INFINITY;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int ch = tid + 256 * i;
+    const int ch = tid + BS * i;
     if (ch < c4) {
-      v[i] = hdet_ld4(z + 4 * ch);
+      v[i] = hdet_ld4_stream(z + 4 * ch);
 #pragma unroll
       for (int j = 0; j < 4; ++j) mx = fmaxf(mx, v[i].v[j]);
     }
@@ -110,30 +112,34 @@ __global__ __launch_bounds__(256) void xent_row_kernel(const float* logits, cons
   mx = wave_max(mx);
   if ((tid & 63) == 0) red[tid >> 6] = mx;
   __syncthreads();
-  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  mx = red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) mx = fmaxf(mx, red[w]);
   __syncthreads();
   float se = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i)
-    if (tid + 256 * i < c4) {
+    if (tid + BS * i < c4) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) { v[i].v[j] = expf(v[i].v[j] - mx); se += v[i].v[j]; }
     }
   se = wave_sum(se);
   if ((tid & 63) == 0) red[tid >> 6] = se;
   __syncthreads();
-  se = ((red[0] + red[1]) + red[2]) + red[3];
+  se = red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) se += red[w];
   const int y = labels[gr];
   const float inv = 1.f / se, invb = 1.f / (float)rows;
   T* d = dlogits + gr * classes;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int ch = tid + 256 * i;
+    const int ch = tid + BS * i;
     if (ch < c4) {
       hdet_f4 o;
 #pragma unroll
       for (int j = 0; j < 4; ++j) o.v[j] = (v[i].v[j] * inv - (4 * ch + j == y ? 1.f : 0.f)) * invb;
-      hdet_st4(d + 4 * ch, o);
+      hdet_st4_stream(d + 4 * ch, o);
     }
   }
   if (tid == 0) row_loss[gr] = logf(se) - (z[y] - mx);
@@ -176,11 +182,11 @@ hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* label
   if (classes >= 2048 && classes <= 32768 && classes % 4 == 0) {
     const dim3 grid(rows, n_replicas);
     if (classes <= 8192) {
-      if (bf16) hipLaunchKernelGGL((xent_row_kernel<uint16_t, 8>), grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
-      else hipLaunchKernelGGL((xent_row_kernel<float, 8>), grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
+      if (bf16) hipLaunchKernelGGL((xent_row_kernel<uint16_t, 256, 8>), grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
+      else hipLaunchKernelGGL((xent_row_kernel<float, 256, 8>), grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
     } else {
-      if (bf16) hipLaunchKernelGGL((xent_row_kernel<uint16_t, 32>), grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
-      else hipLaunchKernelGGL((xent_row_kernel<float, 32>), grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
+      if (bf16) hipLaunchKernelGGL((xent_row_kernel<uint16_t, 512, 16>), grid, dim3(512), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
+      else hipLaunchKernelGGL((xent_row_kernel<float, 512, 16>), grid, dim3(512), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
     }
     return hipGetLastError();
   }
