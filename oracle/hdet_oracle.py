@@ -34,6 +34,8 @@ GRAD_PER_REPLICA = 1
 CH_LR = 0
 CH_DROPOUT = 1
 CH_WD = 2
+CH_LABEL_SMOOTH = 3     # label smoothing eps of the cross-entropy (Remark 1)
+CH_ATTN_TEMP = 4        # attention temperature tau (Remark 1)
 
 
 # --------------------------------------------------------------------------------------
@@ -334,6 +336,8 @@ class Config:
     extra: List[Channel] = field(default_factory=list)   # channels after the rates (dropout, wd)
     group_ends: List[int] = field(default_factory=list)  # parameter groups with a rate channel each:
                                                          # group g = plane slice [ends[g-1], ends[g])
+    reshuffle_every_sync: bool = False    # Fig. 1's reading: new permutations at every sync step,
+                                          # also while the controller does not run yet
 
 
 class HDETOracle:
@@ -347,7 +351,10 @@ class HDETOracle:
       the base is piecewise constant and changes only through Eq. 7.  At hand-over the
       base is the mean of the rates in effect, i.e. the one-cycle value of that step.
     * The rates entering Eq. 5 are those in effect at the sync step.
-    * Permutations are redrawn only when the controller runs (Algorithm 1).
+    * Permutations are redrawn only when the controller runs (Algorithm 1), numbered by the
+      controller update k.  With reshuffle_every_sync (the caption of Fig. 1: reshuffled before
+      every cycle) they are redrawn at every sync step, numbered by the sync step t / T; a sync
+      step whose losses are not finite still leaves everything untouched.
     * Optimizer state is not averaged by converge (Eq. 3 names the parameters only).
     * Channels other than the learning rates use gamma = 0 and are clamped to [lo, hi].
     * Parameter groups (Sec. 3.4: per-group rates, each with an independent permutation)
@@ -422,6 +429,20 @@ class HDETOracle:
             return np.zeros(n, dtype=np.float32)
         return self.values(j).astype(np.float32)
 
+    def label_smoothing_table(self) -> np.ndarray:
+        """eps_r handed to the loss of replica r, rounded to fp32 (0 without such a channel)."""
+        j = self.channel_index(CH_LABEL_SMOOTH)
+        if j < 0:
+            return np.zeros(self.cfg.n_replicas, dtype=np.float32)
+        return self.values(j).astype(np.float32)
+
+    def attn_temp_table(self) -> np.ndarray:
+        """tau_r handed to the attention of replica r, rounded to fp32 (1 without such a channel)."""
+        j = self.channel_index(CH_ATTN_TEMP)
+        if j < 0:
+            return np.ones(self.cfg.n_replicas, dtype=np.float32)
+        return self.values(j).astype(np.float32)
+
     def is_sync(self) -> bool:
         return self.t > 0 and self.t % self.cfg.sync_interval == 0
 
@@ -478,6 +499,9 @@ class HDETOracle:
         self.l_acc = np.zeros(n, dtype=np.float64)
         self.l_last = l_r
         if not (c.autolr_enabled and self.t >= c.warm_steps):
+            if c.reshuffle_every_sync:
+                for j in range(self.n_ch):
+                    self.perm[j] = permutation(c.seed, self.t // c.sync_interval, j, n)
             return
         if not np.all(np.isfinite(l_r)):
             # a non-finite loss carries no ranking signal: state is left untouched
@@ -499,8 +523,9 @@ class HDETOracle:
             self.delta[j] = d
             self.base[j] = min(max(nb, ch.lo), ch.hi)
         self.k += 1
+        draw = self.t // c.sync_interval if c.reshuffle_every_sync else self.k
         for j in range(self.n_ch):
-            self.perm[j] = permutation(c.seed, self.k, j, n)
+            self.perm[j] = permutation(c.seed, draw, j, n)
 
     def step(self, grads: np.ndarray, losses: Sequence[float]):
         """One full iteration of Algorithm 1's loop body."""

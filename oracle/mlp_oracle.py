@@ -44,22 +44,26 @@ def split_params(flat: np.ndarray, widths: Sequence[int]) -> List[Tuple[np.ndarr
     return out
 
 
-def softmax_xent(logits: np.ndarray, labels: np.ndarray) -> Tuple[float, np.ndarray]:
-    """Mean over rows of -log softmax(logits)[label]; returns (loss, dloss/dlogits)."""
+def softmax_xent(logits: np.ndarray, labels: np.ndarray, smoothing: float = 0.0) -> Tuple[float, np.ndarray]:
+    """Mean over rows of the cross-entropy between the target distribution q and
+    softmax(logits); returns (loss, dloss/dlogits).  q is the one-hot label for smoothing = 0;
+    with label smoothing eps (one of the scalars Remark 1 names as explorable) it is the usual
+    mixture q = (1 - eps) onehot + eps / C with the uniform distribution over the C classes."""
     z = logits - logits.max(axis=1, keepdims=True)
     e = np.exp(z)
     s = e.sum(axis=1, keepdims=True)
     logp = z - np.log(s)
-    rows = np.arange(logits.shape[0])
-    loss = float(-logp[rows, labels].mean())
-    d = e / s
-    d[rows, labels] -= 1.0
-    d /= logits.shape[0]
+    n, c = logits.shape
+    rows = np.arange(n)
+    q = np.full((n, c), smoothing / c)
+    q[rows, labels] += 1.0 - smoothing
+    loss = float(-(q * logp).sum(axis=1).mean())
+    d = (e / s - q) / n
     return loss, d
 
 
 def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Sequence[int],
-                      bf16: bool = False, info: dict = None) -> Tuple[float, np.ndarray]:
+                      bf16: bool = False, info: dict = None, label_smoothing: float = 0.0) -> Tuple[float, np.ndarray]:
     """Loss and flat fp32 gradient for one replica.  x: [B, d_in], y: [B] int.
 
     If `info` is given, info["relu_margin"] receives the smallest |pre-activation| over all
@@ -80,7 +84,7 @@ def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Se
             acts.append(q(np.maximum(zi, 0.0)))
     if info is not None:
         info["relu_margin"] = min([float(np.min(np.abs(p))) for p in pre[:-1]] + [float("inf")])
-    loss, dz = softmax_xent(pre[-1], y.astype(np.int64))
+    loss, dz = softmax_xent(pre[-1], y.astype(np.int64), label_smoothing)
     grads: List[np.ndarray] = [None] * (2 * n_layers)
     for i in range(n_layers - 1, -1, -1):
         w, _ = layers[i]

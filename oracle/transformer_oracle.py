@@ -8,7 +8,8 @@ the benchmark configurations name decoder-only transformers by (layers, d_model,
 sequence, vocabulary).  What they leave open is read as: pre-LayerNorm blocks, learned
 positional embeddings, GELU in its tanh form, causal attention, biases on every Linear, an
 untied output head with bias, a final LayerNorm, LayerNorm epsilon 1e-5.  Dropout, when a
-rate p > 0 is given (Remark 1: the dropout rate as an explored hyperparameter), acts on the
+rate p > 0 is given (Remark 1: the dropout rate as an explored hyperparameter; label
+smoothing and the attention temperature are two more, see loss_and_grad), acts on the
 two residual branches of every block (after the attention projection and after the MLP) with
 keep-scaling 1/(1-p); its mask is a pure function of (seed, step, replica, site, element)
 drawn from Philox-4x32-10, so both implementations regenerate it without exchanging it.
@@ -110,8 +111,12 @@ def layer_norm_backward(dy, xhat, rstd, g):
 
 
 def loss_and_grad(flat: np.ndarray, ids: np.ndarray, targets: np.ndarray, cfg: dict, bf16: bool = False,
-                  dropout: Optional[dict] = None) -> Tuple[float, np.ndarray]:
+                  dropout: Optional[dict] = None, label_smoothing: float = 0.0,
+                  attn_temp: float = 1.0) -> Tuple[float, np.ndarray]:
     """ids, targets: [B, S] ints.  dropout: dict(p, seed, step, replica) or None.
+    label_smoothing eps and attention temperature tau are two more of the scalars Remark 1
+    names as explorable: the targets become (1 - eps) onehot + eps / V, and the attention
+    scores are q.k / (sqrt(d_head) tau) (tau = 1: plain scaled dot-product attention).
     Returns (mean cross-entropy over the B*S positions, flat fp32 gradient)."""
     def q(a):
         return round_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64) if bf16 else np.asarray(a, np.float64)
@@ -130,7 +135,7 @@ def loss_and_grad(flat: np.ndarray, ids: np.ndarray, targets: np.ndarray, cfg: d
         k = dropout_keep(dropout["seed"], dropout["step"], dropout["replica"], site, M * d, p_drop)
         return k.reshape(M, d)
 
-    scale = 1.0 / math.sqrt(dh)
+    scale = 1.0 / (math.sqrt(dh) * attn_temp)
     causal = np.tril(np.ones((S, S), dtype=bool))
     pos = np.tile(np.arange(S), B)
     tok = ids.reshape(-1)
@@ -176,7 +181,7 @@ def loss_and_grad(flat: np.ndarray, ids: np.ndarray, targets: np.ndarray, cfg: d
     yf, xhatf, rstdf = layer_norm(x, W["lnf_g"], W["lnf_b"])
     hf = q(yf)
     logits = hf @ q(W["w_head"]).T + W["b_head"]
-    loss, dlogits = softmax_xent(logits, targets.reshape(-1).astype(np.int64))
+    loss, dlogits = softmax_xent(logits, targets.reshape(-1).astype(np.int64), label_smoothing)
 
     G = {k: np.zeros_like(v, dtype=np.float64) for k, v in P.items()}
     dl = q(dlogits)

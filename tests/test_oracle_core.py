@@ -493,3 +493,39 @@ def test_parameter_groups_have_independent_rate_channels():
     orc2.fanout_step(g, [0.0, 0.0])
     assert np.array_equal(before[:, :16], orc2.theta[:, :16]) and np.array_equal(before[:, 28:], orc2.theta[:, 28:])
     assert not np.array_equal(before[:, 16:28], orc2.theta[:, 16:28])
+
+
+def test_reshuffle_every_sync_redraws_before_the_controller_runs():
+    """Fig. 1's reading: a fresh assignment at every sync step, numbered by the sync step; with
+    the flag off nothing moves before the first controller update (Algorithm 1)."""
+    cfg_on = _cfg(n_replicas=8, reshuffle_every_sync=True)
+    cfg_off = _cfg(n_replicas=8)
+    on = O.HDETOracle(cfg_on, I.flat_theta0(8, 33, 5))
+    off = O.HDETOracle(cfg_off, I.flat_theta0(8, 33, 5))
+    T = cfg_on.sync_interval
+    seen = []
+    for t in range(1, cfg_on.total_steps + 1):
+        g = I.flat_grads(8, 33, 99, t, std=0.1)
+        on.step(g, I.flat_losses(8, t)); off.step(g, I.flat_losses(8, t))
+        if t % T == 0:
+            assert on.perm[0].tolist() == O.permutation(cfg_on.seed, t // T, 0, 8).tolist()
+            assert sorted(on.perm[0].tolist()) == list(range(8))
+            seen.append(tuple(on.perm[0].tolist()))
+            if t < cfg_off.warm_steps:
+                assert off.perm[0].tolist() == list(range(8)) and on.k == 0
+            else:
+                assert off.perm[0].tolist() == O.permutation(cfg_off.seed, off.k, 0, 8).tolist()
+    assert len(set(seen)) == len(seen)               # all different draws
+    assert on.k == off.k                             # the controller itself runs at the same steps
+    # a non-finite interval loss leaves the assignment alone under both readings
+    bad = O.HDETOracle(cfg_on, I.flat_theta0(8, 33, 5))
+    for t in range(1, cfg_on.warm_steps + 1):
+        bad.fanout_step(I.flat_grads(8, 33, 99, t, std=0.1), I.flat_losses(8, t))
+        if t % T == 0:
+            bad.converge()
+            before = bad.perm[0].copy()
+            if t == cfg_on.warm_steps:
+                bad.autolr_update([float("nan")] + [1.0] * 7)
+                assert bad.perm[0].tolist() == before.tolist() and bad.nonfinite == 1
+            else:
+                bad.autolr_update()

@@ -1,5 +1,7 @@
 """Pins for oracle/mlp_oracle.py: finite differences, an independent autograd library in
 fp64, closed-form one-layer cases, bf16 rounding against the library's conversion."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -98,3 +100,29 @@ def test_bf16_mode_close_to_full_precision():
     l1, g1 = M.mlp_loss_and_grad(th, x, y, widths, bf16=True)
     assert abs(l0 - l1) < 2e-2 and l0 != l1
     assert np.linalg.norm(g0 - g1) / np.linalg.norm(g0) < 3e-2
+
+
+def test_label_smoothing_closed_forms():
+    """eps = 1 makes the target uniform: the loss is the mean of (logsumexp - mean logit) and the
+    gradient softmax - 1/C; uniform logits give log C for every eps; and the library's
+    cross-entropy with label_smoothing agrees for intermediate eps."""
+    rng = np.random.default_rng(5)
+    z = rng.normal(size=(7, 11)); y = rng.integers(0, 11, size=7)
+    loss, d = M.softmax_xent(z, y, 1.0)
+    lse = np.log(np.exp(z).sum(axis=1))
+    assert loss == pytest.approx(float((lse - z.mean(axis=1)).mean()), rel=1e-13)
+    sm = np.exp(z) / np.exp(z).sum(axis=1, keepdims=True)
+    assert np.allclose(d, (sm - 1.0 / 11) / 7, rtol=1e-12, atol=1e-15)
+    for eps in (0.0, 0.3, 1.0):
+        assert M.softmax_xent(np.zeros((4, 11)), y[:4], eps)[0] == pytest.approx(math.log(11), rel=1e-13)
+    for eps in (0.05, 0.4):
+        loss, d = M.softmax_xent(z, y, eps)
+        t = torch.tensor(z, dtype=torch.float64, requires_grad=True)
+        ref = torch.nn.functional.cross_entropy(t, torch.tensor(y, dtype=torch.long), label_smoothing=eps)
+        ref.backward()
+        assert loss == pytest.approx(ref.item(), rel=1e-13)
+        assert np.allclose(d, t.grad.numpy(), rtol=1e-11, atol=1e-15)
+        assert np.allclose(d.sum(axis=1), 0.0, atol=1e-16)
+    # the loss is linear in eps between the two closed forms
+    l0, l1, lh = M.softmax_xent(z, y, 0.0)[0], M.softmax_xent(z, y, 1.0)[0], M.softmax_xent(z, y, 0.5)[0]
+    assert lh == pytest.approx(0.5 * (l0 + l1), rel=1e-13)

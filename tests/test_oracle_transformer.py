@@ -18,7 +18,7 @@ def _case(cfg=CFG, B=3, seed=0):
     return th, ids[0], tgt[0]
 
 
-def torch_reference(th, ids, tgt, cfg, keep=None, p_drop=0.0):
+def torch_reference(th, ids, tgt, cfg, keep=None, p_drop=0.0, label_smoothing=0.0, attn_temp=1.0):
     """The same model written with the library's own layers and autograd (fp64)."""
     F = torch.nn.functional
     d, nh, S, L = cfg["d_model"], cfg["n_heads"], cfg["seq_len"], cfg["n_blocks"]
@@ -32,7 +32,7 @@ def torch_reference(th, ids, tgt, cfg, keep=None, p_drop=0.0):
     for l in range(L):
         h = F.layer_norm(x, (d,), P[f"ln1_g.{l}"], P[f"ln1_b.{l}"], eps=1e-5)
         qkv = F.linear(h, P[f"w_qkv.{l}"], P[f"b_qkv.{l}"]).view(B, S, 3, nh, dh).permute(2, 0, 3, 1, 4)
-        a = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2], is_causal=True)
+        a = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2], is_causal=True, scale=1.0 / (math.sqrt(dh) * attn_temp))
         o = F.linear(a.permute(0, 2, 1, 3).reshape(B, S, d), P[f"w_o.{l}"], P[f"b_o.{l}"])
         if keep is not None:
             o = o * torch.tensor(keep[2 * l].reshape(B, S, d), dtype=torch.float64) / (1 - p_drop)
@@ -43,7 +43,8 @@ def torch_reference(th, ids, tgt, cfg, keep=None, p_drop=0.0):
             y = y * torch.tensor(keep[2 * l + 1].reshape(B, S, d), dtype=torch.float64) / (1 - p_drop)
         x = x + y
     logits = F.linear(F.layer_norm(x, (d,), P["lnf_g"], P["lnf_b"], eps=1e-5), P["w_head"], P["b_head"])
-    loss = F.cross_entropy(logits.view(B * S, -1), torch.tensor(tgt.reshape(-1), dtype=torch.long))
+    loss = F.cross_entropy(logits.view(B * S, -1), torch.tensor(tgt.reshape(-1), dtype=torch.long),
+                           label_smoothing=label_smoothing)
     loss.backward()
     return loss.item(), flat.grad.numpy()
 
@@ -135,3 +136,41 @@ def test_zipf_tokens():
     assert counts[0] > counts[1] > counts[3] > counts[15]          # rank-frequency decreasing
     w = 1.0 / np.arange(1, 32001) ** 1.1
     assert abs(counts[0] / big.size - w[0] / w.sum()) < 0.01
+
+
+def test_label_smoothing_and_attention_temperature_match_autograd_library():
+    """Remark 1's further scalars: the library's own label_smoothing and attention scale."""
+    th, ids, tgt = _case(seed=4)
+    for eps, tau in [(0.1, 1.0), (0.0, 1.7), (0.25, 0.6)]:
+        loss, g = T.loss_and_grad(th, ids, tgt, CFG, label_smoothing=eps, attn_temp=tau)
+        ref_loss, ref_g = torch_reference(th, ids, tgt, CFG, label_smoothing=eps, attn_temp=tau)
+        assert loss == pytest.approx(ref_loss, rel=1e-12)
+        assert np.allclose(g, ref_g, rtol=2e-6, atol=1e-9)
+    base, g0 = T.loss_and_grad(th, ids, tgt, CFG)
+    assert T.loss_and_grad(th, ids, tgt, CFG, label_smoothing=0.1)[0] != base
+    assert T.loss_and_grad(th, ids, tgt, CFG, attn_temp=1.7)[0] != base
+
+
+def test_attention_temperature_equals_rescaled_query_weights():
+    """softmax(q.k / (sqrt(d_h) tau)) is what dividing the query projection by tau gives:
+    same loss, and the gradient of the key/value/other tensors is unchanged."""
+    th, ids, tgt = _case(seed=5)
+    tau = 1.6
+    d = CFG["d_model"]
+    scaled = th.astype(np.float64).copy()
+    off = 0
+    q_slices = []
+    for name, shape in T.layout(CFG):
+        k = int(np.prod(shape))
+        if name.startswith("w_qkv"):
+            scaled[off:off + d * d] /= tau; q_slices.append((off, off + d * d))
+        if name.startswith("b_qkv"):
+            scaled[off:off + d] /= tau; q_slices.append((off, off + d))
+        off += k
+    l1, g1 = T.loss_and_grad(th, ids, tgt, CFG, attn_temp=tau)
+    l2, g2 = T.loss_and_grad(scaled, ids, tgt, CFG)
+    assert l1 == pytest.approx(l2, rel=1e-12)
+    for a, b in q_slices:                     # chain rule: d/dW_q at tau = (1/tau) d/dW_q' at W_q' = W_q/tau
+        assert np.allclose(g1[a:b], g2[a:b] / tau, rtol=1e-5, atol=1e-10)
+        g1[a:b] = 0; g2[a:b] = 0
+    assert np.allclose(g1, g2, rtol=1e-5, atol=1e-10)
