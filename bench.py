@@ -215,6 +215,44 @@ def transformer_workload(args):
             "loss_first_replica": float(st.l_step[0])}
 
 
+def shared_state_leg(H, I, theta, g, m, v, n, P, T, stride, stream, args):
+    """2 T steps of shared-gradient AdamW with one plane of each moment, timed like the main leg."""
+    import torch
+    steps, warm = 2 * T, 4
+    m1, v1 = m[:1], v[:1]
+    m1.zero_(); v1.zero_()
+    cfg = H.make_config(n_replicas=n, sync_interval=T, total_steps=steps + warm, warm_steps=int(0.3 * (steps + warm)),
+                        lr_max=1e-3, alpha=0.1, autolr_enabled=1, optimizer=H.HDET_ADAMW, weight_decay=0.01,
+                        grad_mode=H.HDET_GRAD_SHARED, shared_opt_state=1, model_kind=H.HDET_FLAT, n_params=P,
+                        seed=I.SEED_PERM, stream=stream.cuda_stream)
+    h = H.hdet_create(cfg, theta, m1, v1, plane_stride=stride)
+    losses = [1.0 + 0.01 * r for r in range(n)]
+    ev = []
+    t0 = None
+    for t in range(1, steps + warm + 1):
+        if t == warm + 1:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        if t > warm:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+        H.hdet_fanout_step(h, g, H.HDET_FUSE_CONVERGE)
+        if t > warm:
+            e1.record(stream)
+            ev.append((e0, e1))
+        if t % T == 0:
+            H.hdet_converge(h)
+            H.hdet_autolr_update(h, losses)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    H.hdet_destroy(h)
+    ms = sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+    nbytes = (12 * n + 16) * P
+    return {"replica_steps_per_s": n * steps / dt, "ms_per_step": dt / steps * 1e3, "kernel_ms": ms,
+            "algorithmic_bytes_per_launch": nbytes, "achieved": nbytes / (ms * 1e-3) / 1e9, "unit": "GB/s",
+            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,6 +262,8 @@ def main():
     ap.add_argument("--replicas", type=int, default=8)
     ap.add_argument("--sync-interval", type=int, default=16)
     ap.add_argument("--grad-mode", choices=["per_replica", "shared"], default="per_replica")
+    ap.add_argument("--shared-state", action="store_true",
+                    help="with --grad-mode shared: one set of AdamW moments for all replicas (12N+16 B per element)")
     ap.add_argument("--unfused", action="store_true", help="standalone converge kernel on sync steps")
     ap.add_argument("--variant", type=int, default=0, help="update kernel selection (0 = default)")
     ap.add_argument("--blocks", type=int, default=0)
@@ -259,10 +299,13 @@ def main():
     stride = (P + 3) // 4 * 4
     total = args.warmup + args.steps
 
+    if args.shared_state and args.grad_mode != "shared":
+        print("bench.py: --shared-state needs --grad-mode shared", file=sys.stderr)
+        sys.exit(2)
     theta = torch.empty((n, stride), dtype=torch.float32, device=dev)
     g = torch.empty_like(theta)
-    m = torch.zeros_like(theta)
-    v = torch.zeros_like(theta)
+    m = torch.zeros((1 if args.shared_state else n, stride), dtype=torch.float32, device=dev)
+    v = torch.zeros_like(m)
     I.device_normal_(theta[0], I.SEED_INIT, 0.02)          # identical replicas at t = 0
     for r in range(1, n):
         theta[r].copy_(theta[0])
@@ -274,6 +317,7 @@ def main():
                         lr_max=1e-3, alpha=0.1, autolr_enabled=1, optimizer=H.HDET_ADAMW,
                         weight_decay=0.01,
                         grad_mode=H.HDET_GRAD_SHARED if args.grad_mode == "shared" else H.HDET_GRAD_PER_REPLICA,
+                        shared_opt_state=int(args.shared_state),
                         model_kind=H.HDET_FLAT, n_params=P, seed=I.SEED_PERM, stream=stream.cuda_stream)
     h = H.hdet_create(cfg, theta, m, v, plane_stride=stride)
     if args.variant or args.blocks:
@@ -318,7 +362,7 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     upd_ms = sum(a.elapsed_time(b) for a, b in upd_ev) / len(upd_ev)
-    bytes_per_launch = ADAMW_BYTES * n * P
+    bytes_per_launch = (12 * n + 16) * P if args.shared_state else ADAMW_BYTES * n * P
     achieved = bytes_per_launch / (upd_ms * 1e-3) / 1e9
     st = H.hdet_get_state(h)
     H.hdet_destroy(h)
@@ -332,7 +376,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"flat fan-out+converge: N={n} replicas x P={P:.3g} fp32, AdamW(0.9,0.999,wd 0.01), "
-                               f"alpha=0.1, T={T}, grads ~N(0,1e-3^2) per replica, {args.grad_mode} gradients, "
+                               f"alpha=0.1, T={T}, grads ~N(0,1e-3^2) per replica, {args.grad_mode} gradients"
+                               f"{' with one set of moments' if args.shared_state else ''}, "
                                f"converge {'standalone' if args.unfused else 'fused into the sync-step update'}, auto-LR on",
                    "n_replicas": n, "n_params": P, "sync_interval": T, "grad_mode": args.grad_mode,
                    "controller_updates": int(st.k)},
@@ -345,6 +390,10 @@ def main():
         cms = sum(a.elapsed_time(b) for a, b in conv_ev) / len(conv_ev)
         out["converge_standalone"] = {"kernel_ms": cms, "achieved": CONVERGE_BYTES * n * P / (cms * 1e-3) / 1e9,
                                       "unit": "GB/s"}
+    if args.workload == "both" and not args.shared_state:
+        # the paper's own mode on the same buffers: every replica applies the mean gradient, and
+        # AdamW's moments, which then do not depend on the replica, are kept once
+        out["shared_gradient_one_set_of_moments"] = shared_state_leg(H, I, theta, g, m, v, n, P, T, stride, stream, args)
     del theta, g, m, v
     torch.cuda.empty_cache()
     if args.workload == "both":

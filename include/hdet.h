@@ -45,7 +45,8 @@ enum { HDET_SGDM = 0, HDET_ADAMW = 1 };                       /* optimizer      
 enum { HDET_GRAD_SHARED = 0, HDET_GRAD_PER_REPLICA = 1 };     /* gradient exchange           */
 enum { HDET_FP32 = 0, HDET_BF16_GEMM_FP32_MASTER = 1 };       /* precision of the model GEMMs */
 enum { HDET_FLAT = 0, HDET_MLP = 1, HDET_TRANSFORMER = 2 };   /* model kind                  */
-enum { HDET_CH_LR = 0, HDET_CH_DROPOUT = 1, HDET_CH_WD = 2 }; /* channel kinds               */
+enum { HDET_CH_LR = 0, HDET_CH_DROPOUT = 1, HDET_CH_WD = 2,      /* channel kinds (Remark 1)   */
+       HDET_CH_LABEL_SMOOTH = 3, HDET_CH_ATTN_TEMP = 4 };
 
 /* flags of hdet_fanout_step */
 #define HDET_FUSE_CONVERGE 1u  /* on a sync step, average inside the update kernel (Eq. 3)   */
@@ -55,7 +56,7 @@ typedef struct hdet_handle hdet_handle;
 /* One explored scalar hyperparameter beside the learning rate (Remark 1): replica r uses
  * base * rho_{pi(r)} with rho from Eq. 1 at this channel's alpha and its own permutation. */
 typedef struct {
-  int32_t kind;        /* HDET_CH_DROPOUT or HDET_CH_WD                                      */
+  int32_t kind;        /* HDET_CH_DROPOUT, HDET_CH_WD, HDET_CH_LABEL_SMOOTH or HDET_CH_ATTN_TEMP */
   int32_t reserved;
   double  base;        /* initial centre value h_bar                                         */
   double  alpha;       /* spread ratio                                                       */
@@ -95,6 +96,15 @@ typedef struct {
   int32_t  grad_mode;       /* HDET_GRAD_SHARED: every replica applies the replica mean of
                                the gradients (the paper's gradient AllReduce);
                                HDET_GRAD_PER_REPLICA: replica r applies its own gradient    */
+  int32_t  shared_opt_state;       /* 1 (HDET_ADAMW with HDET_GRAD_SHARED only): the moments
+                               depend on the mean gradient alone, so they are the same for every
+                               replica and are kept once: opt_m_dev and opt_v_dev are
+                               [plane_stride] instead of [N][plane_stride], and a step moves
+                               12 N + 16 bytes per element instead of 28 N                   */
+  int32_t  reshuffle_every_sync;   /* 0: new permutations only when the controller runs
+                               (Algorithm 1), numbered by the controller update k; 1: at every
+                               sync step, also before warm_steps or with the controller off
+                               (the caption of Fig. 1), numbered by the sync step t / T      */
   double   momentum;        /* SGDM                                                          */
   double   beta1, beta2, eps;      /* AdamW                                                  */
   double   weight_decay;    /* used by all replicas unless a HDET_CH_WD channel exists       */
@@ -125,8 +135,9 @@ typedef struct {
   float*    grads_dev;        /* [N][plane_stride] fp32; written by hdet_forward_backward;
                                  may be NULL for HDET_FLAT (gradients are passed per step)   */
   float*    opt_m_dev;        /* [N][plane_stride] AdamW first moment / SGD momentum buffer;
-                                 must be zero at t = 0                                       */
-  float*    opt_v_dev;        /* [N][plane_stride] AdamW second moment; NULL for HDET_SGDM   */
+                                 must be zero at t = 0 ([plane_stride] with shared_opt_state) */
+  float*    opt_v_dev;        /* [N][plane_stride] AdamW second moment; NULL for HDET_SGDM
+                                 ([plane_stride] with shared_opt_state)                      */
   uint16_t* params_bf16_dev;  /* [N][plane_stride] bfloat16 copy of the parameters, kept in
                                  step by the update and converge kernels; NULL unless
                                  precision == HDET_BF16_GEMM_FP32_MASTER                     */
@@ -183,7 +194,9 @@ int hdet_warm_init(hdet_handle* h, const float* theta0_dev, double nu, uint64_t 
  * ("Forward + backward" of Algorithm 1; the loss is the one that Sec. 3.4 averages into
  * L_r).  With a HDET_CH_DROPOUT channel (Remark 1) replica r drops the two residual
  * branches of every transformer block at its own rate; the mask is a pure function of
- * (seed, step, replica, site, element) from Philox-4x32-10.  Writes grads_dev, the per-replica losses of this step and adds them to L_acc.
+ * (seed, step, replica, site, element) from Philox-4x32-10.  With a HDET_CH_LABEL_SMOOTH
+ * channel replica r's targets are (1 - eps_r) onehot + eps_r / C (MLP and transformer); with
+ * a HDET_CH_ATTN_TEMP channel its attention scores are q.k / (sqrt(d_head) tau_r).  Writes grads_dev, the per-replica losses of this step and adds them to L_acc.
  * If losses_host is not NULL the call waits for the stream and copies the N losses there.
  * HDET_ESTATE for HDET_FLAT handles.                                                        */
 int hdet_forward_backward(hdet_handle* h, const void* x_dev, const int32_t* y_dev,

@@ -21,7 +21,7 @@ HDET_SGDM, HDET_ADAMW = 0, 1
 HDET_GRAD_SHARED, HDET_GRAD_PER_REPLICA = 0, 1
 HDET_FP32, HDET_BF16_GEMM_FP32_MASTER = 0, 1
 HDET_FLAT, HDET_MLP, HDET_TRANSFORMER = 0, 1, 2
-HDET_CH_LR, HDET_CH_DROPOUT, HDET_CH_WD = 0, 1, 2
+HDET_CH_LR, HDET_CH_DROPOUT, HDET_CH_WD, HDET_CH_LABEL_SMOOTH, HDET_CH_ATTN_TEMP = 0, 1, 2, 3, 4
 HDET_FUSE_CONVERGE = 1
 
 EXPORTS = [
@@ -54,6 +54,7 @@ class hdet_config(C.Structure):
         ("alpha", C.c_double), ("beta", C.c_double), ("sigma", C.c_double),
         ("lambda_", C.c_double), ("gamma_override", C.c_double),
         ("optimizer", C.c_int32), ("grad_mode", C.c_int32),
+        ("shared_opt_state", C.c_int32), ("reshuffle_every_sync", C.c_int32),
         ("momentum", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
         ("eps", C.c_double), ("weight_decay", C.c_double),
         ("precision", C.c_int32), ("model_kind", C.c_int32),

@@ -112,15 +112,22 @@ int validate(const hdet_config* c, std::string* why) {
     }
     if (prev != p) return bad("the last group_end must equal P");
   }
-  int seen_wd = 0, seen_do = 0;
+  int seen[5] = {0, 0, 0, 0, 0};
   for (int j = 0; j < c->n_extra_channels; ++j) {
     const hdet_channel& ch = c->extra[j];
-    if (ch.kind == HDET_CH_WD) ++seen_wd;
-    else if (ch.kind == HDET_CH_DROPOUT) ++seen_do;
-    else return bad("extra channel kind must be HDET_CH_DROPOUT or HDET_CH_WD");
+    if (ch.kind != HDET_CH_WD && ch.kind != HDET_CH_DROPOUT && ch.kind != HDET_CH_LABEL_SMOOTH && ch.kind != HDET_CH_ATTN_TEMP)
+      return bad("extra channel kind must be HDET_CH_DROPOUT, HDET_CH_WD, HDET_CH_LABEL_SMOOTH or HDET_CH_ATTN_TEMP");
+    if (++seen[ch.kind] > 1) return bad("at most one channel per kind");
     if (!(ch.alpha >= 0.0 && ch.alpha <= 1.0) || !(ch.base >= 0.0) || !(ch.lo <= ch.hi)) return bad("bad extra channel parameters");
+    if (ch.kind == HDET_CH_LABEL_SMOOTH && (c->model_kind == HDET_FLAT || !(ch.hi <= 1.0) || !(ch.base * (1.0 + ch.alpha) <= 1.0)))
+      return bad("label smoothing needs a model and values in [0, 1]");
+    if (ch.kind == HDET_CH_ATTN_TEMP && (c->model_kind != HDET_TRANSFORMER || !(ch.lo > 0.0) || !(ch.base * (1.0 - ch.alpha) > 0.0)))
+      return bad("attention temperature needs a transformer and values > 0");
   }
-  if (seen_wd > 1 || seen_do > 1) return bad("at most one channel per kind");
+  if (c->shared_opt_state != 0 && c->shared_opt_state != 1) return bad("shared_opt_state must be 0 or 1");
+  if (c->shared_opt_state && (c->optimizer != HDET_ADAMW || c->grad_mode != HDET_GRAD_SHARED))
+    return bad("shared_opt_state needs HDET_ADAMW with HDET_GRAD_SHARED");
+  if (c->reshuffle_every_sync != 0 && c->reshuffle_every_sync != 1) return bad("reshuffle_every_sync must be 0 or 1");
   return HDET_OK;
 }
 
@@ -218,6 +225,8 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
   h->mlp = nullptr;
   h->tf = nullptr;
   h->drop_channel = -1;
+  h->ls_channel = -1;
+  h->temp_channel = -1;
   h->ctrl_dev = nullptr;
   h->n_lr = cfg->n_groups > 1 ? cfg->n_groups : 1;
   h->n_channels = h->n_lr + cfg->n_extra_channels;
@@ -235,6 +244,8 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
     h->channels[h->n_lr + j] = cfg->extra[j];
     if (cfg->extra[j].kind == HDET_CH_WD) h->wd_channel = h->n_lr + j;
     if (cfg->extra[j].kind == HDET_CH_DROPOUT) h->drop_channel = h->n_lr + j;
+    if (cfg->extra[j].kind == HDET_CH_LABEL_SMOOTH) h->ls_channel = h->n_lr + j;
+    if (cfg->extra[j].kind == HDET_CH_ATTN_TEMP) h->temp_channel = h->n_lr + j;
   }
 
   e = hipMalloc((void**)&h->ctrl_dev, sizeof(hdet_ctrl));
@@ -244,11 +255,11 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
   rc = upload_ctrl(h, c);
   if (rc == HDET_OK) rc = write_shadow(h);
   if (rc == HDET_OK && cfg->model_kind == HDET_MLP) {
-    h->mlp = hdet_mlp_create(h->cfg, h->buf, &why);
+    h->mlp = hdet_mlp_create(h->cfg, h->buf, h->ls_channel, &why);
     if (!h->mlp) { h->err = why; rc = HDET_EINVAL; }
   }
   if (rc == HDET_OK && cfg->model_kind == HDET_TRANSFORMER) {
-    h->tf = hdet_tf_create(h->cfg, h->buf, h->drop_channel, &why);
+    h->tf = hdet_tf_create(h->cfg, h->buf, h->drop_channel, h->ls_channel, h->temp_channel, &why);
     if (!h->tf) { h->err = why; rc = HDET_EINVAL; }
   }
   if (rc != HDET_OK) {
@@ -317,6 +328,7 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   a.n_replicas = c.n_replicas;
   a.wd_channel = h->wd_channel;
   a.first_step = t == 1;
+  a.shared_state = c.shared_opt_state;
   a.eta_sched = onecycle(c, t - 1);        // update t uses schedule index t-1
   a.wd_const = c.weight_decay;
   const double bc1 = 1.0 - pow(c.beta1, (double)t);
@@ -391,6 +403,8 @@ int hdet_autolr_update(hdet_handle* h, const double* interval_losses_host) {
     a.lo[j] = h->channels[j].lo;
     a.hi[j] = h->channels[j].hi;
   }
+  a.reshuffle = c.reshuffle_every_sync;
+  a.sync_index = (uint32_t)(h->t / c.sync_interval);
   a.seed_lo = (uint32_t)(c.seed & 0xffffffffu);
   a.seed_hi = (uint32_t)(c.seed >> 32);
   hipError_t e = hdet_launch_controller(a, h->stream);

@@ -34,7 +34,8 @@ __device__ philox_out philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint3
 
 constexpr uint32_t kPermStream = 0x48444554u;   // "HDET"
 
-// Fresh permutation of Eq. 9 for controller update k and channel j: Fisher-Yates from the
+// Fresh permutation of Eq. 9 for draw number k (the controller update, or the sync step when
+// permutations are redrawn at every sync step) and channel j: Fisher-Yates from the
 // top index down on the identity, each draw uniform on [0, i] by rejection from successive
 // 32-bit words of philox(counter = (block, k, j, kPermStream), key = seed).
 __device__ void draw_permutation(int32_t* pi, int n, uint32_t k, uint32_t j, uint32_t seed_lo,
@@ -81,7 +82,17 @@ __global__ __launch_bounds__(64) void hdet_controller_kernel(const hdet_controll
     c->l_last[lane] = L;
     c->l_acc[lane] = 0.0;
   }
-  if (!a.run_controller) return;
+  if (!a.run_controller) {
+    // Fig. 1's reading: a fresh assignment before every cycle, also while the base still follows
+    // the one-cycle schedule
+    if (a.reshuffle) {
+      if (lane < a.n_channels) draw_permutation(s_perm[lane], n, a.sync_index, (uint32_t)lane, a.seed_lo, a.seed_hi);
+      __syncthreads();
+      if (mine)
+        for (int j = 0; j < a.n_channels; ++j) c->perm[j][lane] = s_perm[j][lane];
+    }
+    return;
+  }
 
   const bool bad = mine && !isfinite(L);
   if (__ballot(bad) != 0ull) {               // no ranking signal: leave the state untouched
@@ -120,8 +131,8 @@ __global__ __launch_bounds__(64) void hdet_controller_kernel(const hdet_controll
   if (mine) c->w[lane] = w;
 
   // Eq. 9: one independent permutation per channel
-  if (lane < a.n_channels) draw_permutation(s_perm[lane], n, (uint32_t)k_new, (uint32_t)lane, a.seed_lo,
-                                            a.seed_hi);
+  if (lane < a.n_channels)
+    draw_permutation(s_perm[lane], n, a.reshuffle ? a.sync_index : (uint32_t)k_new, (uint32_t)lane, a.seed_lo, a.seed_hi);
   __syncthreads();
   if (mine)
     for (int j = 0; j < a.n_channels; ++j) c->perm[j][lane] = s_perm[j][lane];

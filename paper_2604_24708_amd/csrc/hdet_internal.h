@@ -58,6 +58,7 @@ struct hdet_update_args {
   int32_t lr_channel;      // learning-rate channel of the parameter group being updated
   int32_t wd_channel;      // channel index of a weight-decay channel or -1
   int32_t first_step;      // SGDM: buf <- g'
+  int32_t shared_state;    // AdamW on the mean gradient: m, v are one plane, not one per replica
   double eta_sched;        // one-cycle value of this step
   double wd_const;
   double inv_bc1;          // 1 / (1 - beta1^t)
@@ -82,6 +83,8 @@ struct hdet_controller_args {
   int32_t n_replicas, n_channels;
   int32_t n_lr;                        // learning-rate channels come first
   int32_t sync_interval;
+  int32_t reshuffle;                   // new permutations at every sync step, numbered by it
+  uint32_t sync_index;                 // t / T of this sync step
   double eta_sched;                    // one-cycle value of the sync step (hand-over)
   double sigma, beta, gamma;
   double lambda[HDET_MAX_CH], lo[HDET_MAX_CH], hi[HDET_MAX_CH];
@@ -162,7 +165,7 @@ hipError_t hdet_launch_bgemm_dma(const hdet_bgemm_args& g, bool a_kmajor, bool b
 // ---------------------------------------------------------------------------------------
 struct hdet_mlp_plan;
 int hdet_mlp_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err);
-hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, std::string* err);
+hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, int ls_channel, std::string* err);
 void hdet_mlp_destroy(hdet_mlp_plan* p);
 hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
                                      hipStream_t stream);
@@ -174,7 +177,9 @@ struct hdet_tf_plan;
 int64_t hdet_tf_param_count(const hdet_config& cfg);
 int hdet_tf_validate(const hdet_config& cfg, std::string* err);
 int hdet_tf_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err);
-hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, int drop_channel, std::string* err);
+// drop_channel, ls_channel, temp_channel: channel indices of Remark 1's scalars read by the model, or -1
+hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, int drop_channel, int ls_channel,
+                             int temp_channel, std::string* err);
 void hdet_tf_destroy(hdet_tf_plan* p);
 // `step`: the update this gradient is for (keys the dropout masks)
 hipError_t hdet_tf_forward_backward(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl,
@@ -202,5 +207,7 @@ struct hdet_handle {
   hdet_mlp_plan* mlp;
   hdet_tf_plan* tf;
   int drop_channel;
+  int ls_channel;                       // label-smoothing channel or -1
+  int temp_channel;                     // attention-temperature channel or -1
   std::string err;
 };

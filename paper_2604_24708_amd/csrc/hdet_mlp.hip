@@ -63,27 +63,38 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-// One wavefront per row: loss_b = log(sum exp(z - max)) - (z_y - max);
-// dlogits = (softmax - onehot) / B.  4 rows per 256-thread block.
+// Label smoothing eps of replica r (Remark 1): the value of its channel, or 0 without one.
+__device__ __forceinline__ float smoothing_of(const hdet_ctrl* ctrl, int ls_channel, int r) {
+  return ls_channel >= 0 ? (float)hdet_channel_value(ctrl, ls_channel, r, 0.0) : 0.f;
+}
+
+// One wavefront per row.  With the target q = (1 - eps) onehot + eps / C:
+//   loss_b = log(sum exp(z - max)) - (1 - eps) (z_y - max) - eps mean_c (z_c - max),
+//   dlogits = (softmax - q) / B.
+// 4 rows per 256-thread block.
 template <typename T>
 __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const int32_t* labels, int rows,
-                                                   int classes, T* dlogits, float* row_loss) {
+                                                   int classes, T* dlogits, float* row_loss, const hdet_ctrl* ctrl,
+                                                   int ls_channel) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
+  const float eps = smoothing_of(ctrl, ls_channel, blockIdx.y);
   const int64_t gr = (int64_t)blockIdx.y * rows + row;
   const float* z = logits + gr * classes;
   float mx = -INFINITY;
   for (int c = lane; c < classes; c += 64) mx = fmaxf(mx, z[c]);
   mx = wave_max(mx);
-  float se = 0.f;
-  for (int c = lane; c < classes; c += 64) se += expf(z[c] - mx);
+  float se = 0.f, sz = 0.f;
+  for (int c = lane; c < classes; c += 64) { se += expf(z[c] - mx); sz += z[c] - mx; }
   se = wave_sum(se);
+  sz = wave_sum(sz);
   const int y = labels[gr];
   const float inv = 1.f / se, invb = 1.f / (float)rows;
+  const float hit = 1.f - eps, miss = eps / (float)classes;
   T* d = dlogits + gr * classes;
-  for (int c = lane; c < classes; c += 64) put(d + c, (expf(z[c] - mx) * inv - (c == y ? 1.f : 0.f)) * invb);
-  if (lane == 0) row_loss[gr] = logf(se) - (z[y] - mx);
+  for (int c = lane; c < classes; c += 64) put(d + c, (expf(z[c] - mx) * inv - (c == y ? hit : 0.f) - miss) * invb);
+  if (lane == 0) row_loss[gr] = logf(se) - hit * (z[y] - mx) - eps * (sz / (float)classes);
 }
 
 // Wide rows (2048 <= classes <= 32768, classes % 4 == 0): one block of BS threads per row, the row
@@ -92,9 +103,10 @@ __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const in
 // xent_kernel.
 template <typename T, int BS, int NV>
 __global__ __launch_bounds__(BS) void xent_row_kernel(const float* logits, const int32_t* labels, int rows, int classes,
-                                                      T* dlogits, float* row_loss) {
+                                                      T* dlogits, float* row_loss, const hdet_ctrl* ctrl, int ls_channel) {
   constexpr int NW = BS / 64;
-  __shared__ float red[NW];
+  __shared__ float red[NW], red2[NW];
+  const float eps = smoothing_of(ctrl, ls_channel, blockIdx.y);
   const int64_t gr = (int64_t)blockIdx.y * rows + blockIdx.x;
   const float* z = logits + gr * classes;
   const int c4 = classes >> 2, tid = threadIdx.x;
@@ -116,21 +128,24 @@ __global__ __launch_bounds__(BS) void xent_row_kernel(const float* logits, const
 #pragma unroll
   for (int w = 1; w < NW; ++w) mx = fmaxf(mx, red[w]);
   __syncthreads();
-  float se = 0.f;
+  float se = 0.f, sz = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i)
     if (tid + BS * i < c4) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { v[i].v[j] = expf(v[i].v[j] - mx); se += v[i].v[j]; }
+      for (int j = 0; j < 4; ++j) { sz += v[i].v[j] - mx; v[i].v[j] = expf(v[i].v[j] - mx); se += v[i].v[j]; }
     }
   se = wave_sum(se);
-  if ((tid & 63) == 0) red[tid >> 6] = se;
+  sz = wave_sum(sz);
+  if ((tid & 63) == 0) { red[tid >> 6] = se; red2[tid >> 6] = sz; }
   __syncthreads();
   se = red[0];
+  sz = red2[0];
 #pragma unroll
-  for (int w = 1; w < NW; ++w) se += red[w];
+  for (int w = 1; w < NW; ++w) { se += red[w]; sz += red2[w]; }
   const int y = labels[gr];
   const float inv = 1.f / se, invb = 1.f / (float)rows;
+  const float hit = 1.f - eps, miss = eps / (float)classes;
   T* d = dlogits + gr * classes;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -138,11 +153,11 @@ __global__ __launch_bounds__(BS) void xent_row_kernel(const float* logits, const
     if (ch < c4) {
       hdet_f4 o;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) o.v[j] = (v[i].v[j] * inv - (4 * ch + j == y ? 1.f : 0.f)) * invb;
+      for (int j = 0; j < 4; ++j) o.v[j] = (v[i].v[j] * inv - (4 * ch + j == y ? hit : 0.f) - miss) * invb;
       hdet_st4_stream(d + 4 * ch, o);
     }
   }
-  if (tid == 0) row_loss[gr] = logf(se) - (z[y] - mx);
+  if (tid == 0) row_loss[gr] = logf(se) - hit * (z[y] - mx) - eps * (sz / (float)classes);
 }
 
 // Per-replica mean of the row losses in a fixed tree order (one block per replica), the
@@ -175,24 +190,28 @@ struct hdet_mlp_plan {
   void* dz_a; void* dz_b;                // ping-pong activation gradients, fp32 or bf16
   float* row_loss;
   bool bf16;
+  int ls_channel;                        // label-smoothing channel or -1
 };
 
 hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* labels, int rows, int classes, void* dlogits,
-                            float* row_loss, int n_replicas, hipStream_t s) {
+                            float* row_loss, int n_replicas, const hdet_ctrl* ctrl, int ls_channel, hipStream_t s) {
   if (classes >= 2048 && classes <= 32768 && classes % 4 == 0) {
     const dim3 grid(rows, n_replicas);
+#define HDET_XENT_ROW(T, BS, NV) \
+  hipLaunchKernelGGL((xent_row_kernel<T, BS, NV>), grid, dim3(BS), 0, s, logits, labels, rows, classes, (T*)dlogits, row_loss, ctrl, ls_channel)
     if (classes <= 8192) {
-      if (bf16) hipLaunchKernelGGL((xent_row_kernel<uint16_t, 256, 8>), grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
-      else hipLaunchKernelGGL((xent_row_kernel<float, 256, 8>), grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
+      if (bf16) HDET_XENT_ROW(uint16_t, 256, 8);
+      else HDET_XENT_ROW(float, 256, 8);
     } else {
-      if (bf16) hipLaunchKernelGGL((xent_row_kernel<uint16_t, 512, 16>), grid, dim3(512), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
-      else hipLaunchKernelGGL((xent_row_kernel<float, 512, 16>), grid, dim3(512), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
+      if (bf16) HDET_XENT_ROW(uint16_t, 512, 16);
+      else HDET_XENT_ROW(float, 512, 16);
     }
+#undef HDET_XENT_ROW
     return hipGetLastError();
   }
   const dim3 grid((rows + 3) / 4, n_replicas);
-  if (bf16) hipLaunchKernelGGL(xent_kernel<uint16_t>, grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss);
-  else hipLaunchKernelGGL(xent_kernel<float>, grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss);
+  if (bf16) hipLaunchKernelGGL(xent_kernel<uint16_t>, grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss, ctrl, ls_channel);
+  else hipLaunchKernelGGL(xent_kernel<float>, grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss, ctrl, ls_channel);
   return hipGetLastError();
 }
 
@@ -222,12 +241,13 @@ int hdet_mlp_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string*
   return HDET_OK;
 }
 
-hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, std::string* err) {
+hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, int ls_channel, std::string* err) {
   size_t need = 0;
   if (hdet_mlp_workspace_bytes(cfg, &need, err) != HDET_OK) return nullptr;
   if (!buf.workspace_dev || buf.workspace_bytes < need) { *err = "workspace_dev is too small"; return nullptr; }
   hdet_mlp_plan* p = new hdet_mlp_plan();
   p->cfg = cfg; p->buf = buf; p->n_layers = cfg.dims.n_layers;
+  p->ls_channel = ls_channel;
   const size_t n = cfg.n_replicas, b = cfg.dims.batch;
   const int L = p->n_layers;
   int64_t off = 0;
@@ -276,7 +296,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
   }
   // loss and dlogits
   float* dz = (float*)p->dz_a; float* dz_next = (float*)p->dz_b;
-  hipLaunchKernelGGL(xent_kernel<float>, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss);
+  hipLaunchKernelGGL(xent_kernel<float>, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss, ctrl, p->ls_channel);
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   // backward
   for (int i = L - 1; i >= 0; --i) {
@@ -330,7 +350,7 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
     if (e != hipSuccess) return e;
   }
   uint16_t* dz = (uint16_t*)p->dz_a; uint16_t* dz_next = (uint16_t*)p->dz_b;
-  hipLaunchKernelGGL(xent_kernel<uint16_t>, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss);
+  hipLaunchKernelGGL(xent_kernel<uint16_t>, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss, ctrl, p->ls_channel);
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   for (int i = L - 1; i >= 0; --i) {
     hdet_bgemm_args g = {};                          // dW = dZ^T X

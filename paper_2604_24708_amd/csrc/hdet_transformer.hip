@@ -291,12 +291,20 @@ __global__ __launch_bounds__(1024) void colsum_kernel(const T* src, int64_t src_
   }
 }
 
+// Score scale of the replica that owns `row`: 1 / sqrt(d_head), divided by the replica's
+// attention temperature when that is an explored channel (Remark 1).
+struct temp_args { const hdet_ctrl* ctrl; int channel; int64_t rows_per_replica; };
+__device__ __forceinline__ float score_scale(float scale, const temp_args& t, int64_t row) {
+  return t.channel >= 0 ? scale / (float)hdet_channel_value(t.ctrl, t.channel, (int)(row / t.rows_per_replica), 0.0) : scale;
+}
+
 // Causal softmax over scaled scores, one wavefront per query row i: keys j <= i.
 template <typename T>
-__global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* scores, int64_t rows_total, int S, float scale, T* p) {
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* scores, int64_t rows_total, int S, float scale0, temp_args ta, T* p) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows_total) return;
+  const float scale = score_scale(scale0, ta, row);
   const int i = (int)(row % S);
   const float* s = scores + row * S;
   float mx = -INFINITY;
@@ -311,10 +319,11 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* scores, i
 // ds = p * (dp - sum_j dp_j p_j) * scale  (zero above the diagonal, where p = 0)
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* dp, const T* p, int64_t rows_total, int S,
-                                                          float scale, T* ds) {
+                                                          float scale0, temp_args ta, T* ds) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows_total) return;
+  const float scale = score_scale(scale0, ta, row);
   const int i = (int)(row % S);
   float dot = 0.f;
   for (int j = lane; j <= i; j += 64) dot += dp[row * S + j] * hdet_ld(p + row * S + j);
@@ -325,10 +334,11 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* dp, const
 
 // Vector forms for S % 4 == 0, S <= 1024: lane l owns the 4-element chunks l, l + 64, ... of a row.
 template <typename T, int NCH>
-__global__ __launch_bounds__(256) void softmax_fwd_vec_kernel(const float* scores, int64_t rows_total, int S, float scale, T* p) {
+__global__ __launch_bounds__(256) void softmax_fwd_vec_kernel(const float* scores, int64_t rows_total, int S, float scale0, temp_args ta, T* p) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows_total) return;
+  const float scale = score_scale(scale0, ta, row);
   const int i = (int)(row % S), s4 = S >> 2;
   hdet_f4 v[NCH];
   float mx = -INFINITY;
@@ -365,10 +375,11 @@ __global__ __launch_bounds__(256) void softmax_fwd_vec_kernel(const float* score
 
 template <typename T, int NCH>
 __global__ __launch_bounds__(256) void softmax_bwd_vec_kernel(const float* dp, const T* p, int64_t rows_total, int S,
-                                                              float scale, T* ds) {
+                                                              float scale0, temp_args ta, T* ds) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows_total) return;
+  const float scale = score_scale(scale0, ta, row);
   const int s4 = S >> 2;
   hdet_f4 dv[NCH], pv[NCH];
   float dot = 0.f;
@@ -480,7 +491,7 @@ int grid_for(int64_t n) { int64_t b = (n + 255) / 256; return (int)(b > 8192 ? 8
 
 // xent and loss reduction live with the MLP path
 hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* labels, int rows, int classes, void* dlogits,
-                            float* row_loss, int n_replicas, hipStream_t s);
+                            float* row_loss, int n_replicas, const hdet_ctrl* ctrl, int ls_channel, hipStream_t s);
 hipError_t hdet_launch_loss_reduce(const float* row_loss, int rows, hdet_ctrl* ctrl, int n_replicas, hipStream_t s);
 
 struct tf_block_off { int64_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_1, b_1, w_2, b_2; };
@@ -491,6 +502,8 @@ struct hdet_tf_plan {
   bool bf16;
   int N, B, S, M, d, nh, dh, ff, V, L;
   int drop_channel;
+  int ls_channel;       // label-smoothing channel or -1
+  int temp_channel;     // attention-temperature channel or -1
   int64_t tok, pos, lnf_g, lnf_b, w_head, b_head;
   std::vector<tf_block_off> blk;
   // activations (type T), per replica sizes in elements
@@ -570,12 +583,15 @@ int hdet_tf_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* 
   return HDET_OK;
 }
 
-hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, int drop_channel, std::string* err) {
+hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, int drop_channel, int ls_channel,
+                             int temp_channel, std::string* err) {
   if (hdet_tf_validate(cfg, err) != HDET_OK) return nullptr;
   hdet_tf_plan* p = new hdet_tf_plan();
   tf_dims(p, cfg);
   p->buf = buf;
   p->drop_channel = drop_channel;
+  p->ls_channel = ls_channel;
+  p->temp_channel = temp_channel;
   const size_t need = tf_carve(p, nullptr);
   if (!buf.workspace_dev || buf.workspace_bytes < need) { *err = "workspace_dev is too small"; delete p; return nullptr; }
   tf_carve(p, (char*)buf.workspace_dev);
@@ -640,28 +656,28 @@ void launch_ln_bwd_dx(const hdet_tf_plan* p, const void* dy, const void* x, cons
 }
 
 template <typename T>
-void launch_softmax_fwd(const float* scores, int64_t rows, int S, float scale, void* prob, hipStream_t s) {
+void launch_softmax_fwd(const float* scores, int64_t rows, int S, float scale, temp_args ta, void* prob, hipStream_t s) {
   const dim3 grid((unsigned)((rows + 3) / 4));
   if (S % 4 == 0 && S <= 1024) {
     const int nch = (S / 4 + 63) / 64;
-#define CALL(K) hipLaunchKernelGGL((softmax_fwd_vec_kernel<T, K>), grid, dim3(256), 0, s, scores, rows, S, scale, (T*)prob)
+#define CALL(K) hipLaunchKernelGGL((softmax_fwd_vec_kernel<T, K>), grid, dim3(256), 0, s, scores, rows, S, scale, ta, (T*)prob)
     HDET_NCH_SWITCH(nch, CALL)
 #undef CALL
   } else {
-    hipLaunchKernelGGL(softmax_fwd_kernel<T>, grid, dim3(256), 0, s, scores, rows, S, scale, (T*)prob);
+    hipLaunchKernelGGL(softmax_fwd_kernel<T>, grid, dim3(256), 0, s, scores, rows, S, scale, ta, (T*)prob);
   }
 }
 
 template <typename T>
-void launch_softmax_bwd(const float* dp, const void* prob, int64_t rows, int S, float scale, void* ds, hipStream_t s) {
+void launch_softmax_bwd(const float* dp, const void* prob, int64_t rows, int S, float scale, temp_args ta, void* ds, hipStream_t s) {
   const dim3 grid((unsigned)((rows + 3) / 4));
   if (S % 4 == 0 && S <= 1024) {
     const int nch = (S / 4 + 63) / 64;
-#define CALL(K) hipLaunchKernelGGL((softmax_bwd_vec_kernel<T, K>), grid, dim3(256), 0, s, dp, (const T*)prob, rows, S, scale, (T*)ds)
+#define CALL(K) hipLaunchKernelGGL((softmax_bwd_vec_kernel<T, K>), grid, dim3(256), 0, s, dp, (const T*)prob, rows, S, scale, ta, (T*)ds)
     HDET_NCH_SWITCH(nch, CALL)
 #undef CALL
   } else {
-    hipLaunchKernelGGL(softmax_bwd_kernel<T>, grid, dim3(256), 0, s, dp, (const T*)prob, rows, S, scale, (T*)ds);
+    hipLaunchKernelGGL(softmax_bwd_kernel<T>, grid, dim3(256), 0, s, dp, (const T*)prob, rows, S, scale, ta, (T*)ds);
   }
 }
 
@@ -727,6 +743,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   const int64_t nd = (int64_t)M * d, nff = (int64_t)M * ff;
   drop_args da = {ctrl, p->drop_channel, step, (uint32_t)(p->cfg.seed & 0xffffffffu), (uint32_t)(p->cfg.seed >> 32), 0};
   const bool drop = p->drop_channel >= 0;
+  const temp_args ta = {ctrl, p->temp_channel, (int64_t)B * nh * S};
 
   // batch strides: activations [N][M][w]; weights per replica plane; attention operands per (replica, sequence, head)
   auto act = [&](const void* q, int w) { mat t = {q, w, {(int64_t)M * w, 0, 0}}; return t; };
@@ -756,7 +773,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       const mat sc = head_sq(p->scores);
       TF_CHECK(gemm<T>(p, NT, qkv_part(p->qkv[l], 0), qkv_part(p->qkv[l], 1), p->scores, S, sc.s, false, S, S, dh, B, nh, nullptr, 0, s));
     }
-    launch_softmax_fwd<T>(p->scores, heads_rows, S, scale, p->p[l], s);
+    launch_softmax_fwd<T>(p->scores, heads_rows, S, scale, ta, p->p[l], s);
     {   // a = p v
       const mat ac = head_cols(p->a[l]);
       TF_CHECK(gemm<T>(p, NN, head_sq(p->p[l]), qkv_part(p->qkv[l], 2), p->a[l], d, ac.s, true, S, dh, S, B, nh, nullptr, 0, s));
@@ -773,7 +790,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   }
   launch_ln_fwd<T>(p, p->x_in[L], p->lnf_g, p->lnf_b, p->hf, p->stf_mean, p->stf_rstd, s);
   TF_CHECK(gemm<T>(p, NT, act(p->hf, d), wt(p->w_head, d), p->logits, V, act_v, false, M, V, d, 1, 1, theta + p->b_head, ps, s));
-  TF_CHECK(hdet_launch_xent(sizeof(T) == 2, p->logits, targets, M, V, p->dlogits, p->row_loss, N, s));
+  TF_CHECK(hdet_launch_xent(sizeof(T) == 2, p->logits, targets, M, V, p->dlogits, p->row_loss, N, ctrl, p->ls_channel, s));
   TF_CHECK(hdet_launch_loss_reduce(p->row_loss, M, ctrl, N, s));
 
   // ---- backward -----------------------------------------------------------------------
@@ -827,7 +844,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       TF_CHECK(gemm<T>(p, NT, head_cols(p->dtmp), qkv_part(p->qkv[l], 2), p->scores, S, sc.s, false, S, S, dh, B, nh, nullptr, 0, s));
       // dv = p^T da
       TF_CHECK(gemm<T>(p, TN, head_sq(p->p[l]), head_cols(p->dtmp), (void*)dv.p, 3 * d, dv.s, true, S, dh, S, B, nh, nullptr, 0, s));
-      launch_softmax_bwd<T>(p->scores, p->p[l], heads_rows, S, scale, p->ds, s);
+      launch_softmax_bwd<T>(p->scores, p->p[l], heads_rows, S, scale, ta, p->ds, s);
       // dq = ds k,  dk = ds^T q
       TF_CHECK(gemm<T>(p, NN, head_sq(p->ds), qkv_part(p->qkv[l], 1), (void*)dq.p, 3 * d, dq.s, true, S, dh, S, B, nh, nullptr, 0, s));
       TF_CHECK(gemm<T>(p, TN, head_sq(p->ds), qkv_part(p->qkv[l], 0), (void*)dk.p, 3 * d, dk.s, true, S, dh, S, B, nh, nullptr, 0, s));

@@ -41,6 +41,9 @@ def oracle_config(d: dict) -> O.Config:
         kw["lam"] = d["lambda_"]
     kw["autolr_enabled"] = bool(d.get("autolr_enabled", False))
     kw["constant_lr"] = bool(d.get("constant_lr", False))
+    kw["reshuffle_every_sync"] = bool(d.get("reshuffle_every_sync", False))
+    # shared_opt_state is a storage choice of the library: the oracle keeps one set of moments per
+    # replica, which in shared-gradient AdamW are identical by construction
     return O.Config(extra=extra, group_ends=list(d.get("group_end", [])), **kw)
 
 
@@ -49,6 +52,8 @@ def library_config(d: dict, **model):
     kw = {k: v for k, v in d.items() if k not in ("extra", "group_end")}
     kw["autolr_enabled"] = int(bool(d.get("autolr_enabled", False)))
     kw["constant_lr"] = int(bool(d.get("constant_lr", False)))
+    kw["reshuffle_every_sync"] = int(bool(d.get("reshuffle_every_sync", False)))
+    kw["shared_opt_state"] = int(bool(d.get("shared_opt_state", False)))
     kw.update(model)
     if d.get("extra"):
         kw["extra"] = d["extra"]

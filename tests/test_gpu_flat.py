@@ -45,8 +45,10 @@ class FlatRun:
         host = np.full((self.n, self.stride), self.pad, dtype=np.float32)
         host[:, :P] = th0
         self.theta = torch.from_numpy(host).to(dev)
-        self.m = torch.zeros((self.n, self.stride), device=dev)
-        self.v = torch.zeros((self.n, self.stride), device=dev)
+        self.shared_state = bool(d.get("shared_opt_state", False))     # one plane of moments for all replicas
+        planes = 1 if self.shared_state else self.n
+        self.m = torch.zeros((planes, self.stride), device=dev)
+        self.v = torch.zeros((planes, self.stride), device=dev)
         self.g = torch.zeros((self.n, self.stride), device=dev)
         cfg = library_config(d, n_params=P, model_kind=H.HDET_FLAT)
         self.h = H.hdet_create(cfg, self.theta, self.m, self.v if d["optimizer"] == O.ADAMW else None,
@@ -72,9 +74,12 @@ class FlatRun:
         P = self.P
         th = self.theta.cpu().numpy()
         assert rel_err(th[:, :P], self.orc.theta) <= tol
-        assert rel_err(self.m.cpu().numpy()[:, :P], self.orc.m) <= tol
+        om, ov = (self.orc.m[:1], self.orc.v[:1]) if self.shared_state else (self.orc.m, self.orc.v)
+        assert rel_err(self.m.cpu().numpy()[:, :P], om) <= tol
         if self.d["optimizer"] == O.ADAMW:
-            assert rel_err(self.v.cpu().numpy()[:, :P], self.orc.v) <= tol
+            assert rel_err(self.v.cpu().numpy()[:, :P], ov) <= tol
+        if self.shared_state:
+            assert np.all(self.m.cpu().numpy()[:, P:] == 0) and np.all(self.v.cpu().numpy()[:, P:] == 0)
         assert np.all(th[:, P:] == self.pad)
         check_state(H.hdet_get_state(self.h), self.orc)
 
@@ -299,3 +304,55 @@ def test_parameter_groups_with_own_rate_channels(opt, mode):
     bad = base_cfg(n_replicas=8, group_end=[4098, P])             # not a multiple of 4
     with pytest.raises(H.HdetError):
         FlatRun(bad, P)
+
+
+@pytest.mark.parametrize("n,P", [(1, 5), (3, 1023), (8, 70001), (8, 262147), (20, 4099)])
+def test_shared_optimizer_state_matches_per_replica_state(n, P):
+    """AdamW on the mean gradient: the moments do not depend on the replica, so one plane of each
+    gives the oracle's trajectory (whose per-replica moments are identical) and, bit for bit, the
+    trajectory of the library's own per-replica-state run."""
+    d = base_cfg(n_replicas=n, optimizer=O.ADAMW, grad_mode=O.GRAD_SHARED, shared_opt_state=True,
+                 extra=[(O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))])
+    run = FlatRun(d, P)
+    ref = FlatRun(dict(d, shared_opt_state=False), P)
+    for t in range(1, 17):
+        run.step(t, fuse=(t % 8 == 0))
+        ref.step(t, fuse=(t % 8 == 0))
+        run.compare(tol_at(t))
+        assert np.all(run.orc.m == run.orc.m[:1]) and np.all(run.orc.v == run.orc.v[:1])
+    assert torch.equal(run.theta, ref.theta)
+    assert torch.equal(run.m[0], ref.m[0]) and torch.equal(run.v[0], ref.v[n - 1])
+    run.close(); ref.close()
+    for bad in (dict(optimizer=O.SGDM, grad_mode=O.GRAD_SHARED), dict(optimizer=O.ADAMW, grad_mode=O.GRAD_PER_REPLICA)):
+        with pytest.raises(H.HdetError):
+            FlatRun(base_cfg(n_replicas=2, shared_opt_state=True, **bad), 64)
+
+
+def test_shared_optimizer_state_with_parameter_groups_and_loop_kernel():
+    P = 50004
+    d = base_cfg(n_replicas=8, optimizer=O.ADAMW, grad_mode=O.GRAD_SHARED, shared_opt_state=True,
+                 group_end=[4096, 20000, P], total_steps=400)
+    a, b = FlatRun(d, P), FlatRun(d, P, variant=1, blocks=7)
+    for t in range(1, 13):
+        a.step(t, fuse=(t % 8 == 0)); b.step(t, fuse=(t % 8 == 0))
+        a.compare(tol_at(t))
+    assert torch.equal(a.theta, b.theta) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v)
+    a.close(); b.close()
+
+
+def test_reshuffle_every_sync_before_and_after_hand_over():
+    """Fig. 1's reading: permutations change at every sync step from the first one on (the
+    controller starts at t = 8 here), numbered by the sync step; parity includes them."""
+    d = base_cfg(n_replicas=8, reshuffle_every_sync=True, extra=[(O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))])
+    run = FlatRun(d, 4099)
+    perms = []
+    for t in range(1, 21):
+        run.step(t, fuse=False)
+        run.compare(tol_at(t))
+        if t % 4 == 0:
+            st = H.hdet_get_state(run.h)
+            perms.append(tuple(st.perm[0][r] for r in range(8)))
+            assert list(perms[-1]) == O.permutation(7, t // 4, 0, 8).tolist()
+    assert perms[0] != tuple(range(8)) and len(set(perms)) == len(perms)
+    assert H.hdet_get_state(run.h).k == 4
+    run.close()

@@ -58,9 +58,11 @@ class TfRun:
         n = self.n
         losses, grads = np.zeros(n), np.zeros((n, self.P), np.float32)
         p = self.orc.dropout_table()
+        eps, tau = self.orc.label_smoothing_table(), self.orc.attn_temp_table()
         for r in range(n):
             dp = dict(p=float(p[r]), seed=self.d["seed"], step=step, replica=r) if p[r] > 0 else None
-            losses[r], grads[r] = T.loss_and_grad(theta[r], ids[r], tgt[r], self.cfg, bf16=self.bf16, dropout=dp)
+            losses[r], grads[r] = T.loss_and_grad(theta[r], ids[r], tgt[r], self.cfg, bf16=self.bf16, dropout=dp,
+                                                  label_smoothing=float(eps[r]), attn_temp=float(tau[r]))
         return losses, grads
 
     def forward_backward(self, t):
@@ -183,3 +185,43 @@ def test_bf16_dropout_loss_matches():
         assert np.max(np.abs(gl - losses)) <= 1e-2
         run.finish_step(t, grads, losses)
     run.close()
+
+
+@pytest.mark.parametrize("cfg,batch", [(TINY, 3), (SMALL, 2)])
+def test_fp32_label_smoothing_and_attention_temperature_channels(cfg, batch):
+    """Two more of Remark 1's scalars as channels: replica r smooths its targets by eps_r and
+    divides its attention scores by tau_r; five channels with the dropout and weight-decay
+    ones, each with its own permutation."""
+    n = 4
+    extra = [(O.CH_LABEL_SMOOTH, 0.1, 0.5, 0.5, 0.0, 0.5), (O.CH_ATTN_TEMP, 1.2, 0.4, 0.5, 0.25, 4.0),
+             (O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
+    d = base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, extra=extra)
+    run = TfRun(d, cfg, batch)
+    for t in range(1, 13):
+        ids, tgt, gl = run.forward_backward(t)
+        losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, t)
+        assert np.max(np.abs(gl - losses)) <= 1e-4
+        if t in (1, 9):
+            g_dev = run.g.cpu().numpy()[:, :run.P]
+            for r in range(n):
+                at_dev = T.loss_and_grad(run.theta.cpu().numpy()[r, :run.P], ids[r], tgt[r], cfg,
+                                         dropout=dict(p=float(run.orc.dropout_table()[r]), seed=d["seed"], step=t, replica=r),
+                                         label_smoothing=float(run.orc.label_smoothing_table()[r]),
+                                         attn_temp=float(run.orc.attn_temp_table()[r]))[1]
+                bad = {k: v for k, v in per_tensor_errors(cfg, g_dev[r], at_dev).items() if v > 5e-5}
+                assert not bad, (t, r, bad)
+        run.finish_step(t, grads, losses, fuse=(t == 8))
+        st = H.hdet_get_state(run.h)
+        assert st.k == run.orc.k and st.n_channels == 5
+        for j in range(5):
+            assert [st.perm[j][r] for r in range(n)] == run.orc.perm[j].tolist()
+    tau = run.orc.attn_temp_table()
+    assert len(set(tau.tolist())) == n and tau.min() > 0.5
+    # a run without the two channels gives different losses: the scalars do reach the kernels
+    plain = TfRun(base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, extra=extra[2:]), cfg, batch)
+    _, _, gl0 = plain.forward_backward(1)
+    run2 = TfRun(d, cfg, batch)
+    _, _, gl1 = run2.forward_backward(1)
+    assert np.min(np.abs(gl0 - gl1)) > 1e-4
+    for x in (run, plain, run2):
+        x.close()
