@@ -31,7 +31,7 @@ CONVERGE_BYTES = 8        # standalone converge: 4 read + 4 written
 # HBM bytes per launch of the update kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain 4e9-byte copy: x2.000 and x1.000), measured on the
 # default workload; valid only for the kernel source it was taken with.
-TRAFFIC_KERNEL_SHA = "fed40120815a0bbe"
+TRAFFIC_KERNEL_SHA = "27c4de97d1e28446"
 TRAFFIC_BYTES_PER_REPLICA_ELEMENT = 224.000e9 / 8e9
 
 
