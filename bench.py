@@ -156,6 +156,14 @@ def transformer_workload(args):
     dev = torch.device("cuda:0")
     n, B, T = 8, 16, 32
     cfg = dict(n_blocks=6, d_model=512, n_heads=8, d_ff=2048, seq_len=256, vocab=32000)
+    lr_max, alpha, extra = 6e-4, 0.15, []
+    if getattr(args, "tf_config", "6L") == "12L":
+        # the larger configuration: 12 layers, d_model 1024, 16 heads, FFN 4096, seq 512, T = 64, and three
+        # explored scalars (rate; dropout base 0.1 spread 1.0; weight decay base 0.05 spread 0.5)
+        T = 64
+        cfg = dict(n_blocks=12, d_model=1024, n_heads=16, d_ff=4096, seq_len=512, vocab=32000)
+        lr_max = 3e-4
+        extra = [(H.HDET_CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (H.HDET_CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
     P = I.transformer_param_count(cfg)
     stride = (P + 3) // 4 * 4
     total = max(2000, args.warmup + args.steps)
@@ -167,9 +175,10 @@ def transformer_workload(args):
     ids, tgt = torch.from_numpy(ids).to(dev), torch.from_numpy(tgt).to(dev)
     stream = torch.cuda.current_stream()
     lc = H.make_config(n_replicas=n, sync_interval=T, total_steps=total, warm_steps=int(0.3 * total),
-                       lr_max=6e-4, alpha=0.15, autolr_enabled=1, optimizer=H.HDET_ADAMW, weight_decay=0.01,
+                       lr_max=lr_max, alpha=alpha, autolr_enabled=1, optimizer=H.HDET_ADAMW, weight_decay=0.01,
                        grad_mode=H.HDET_GRAD_PER_REPLICA, precision=H.HDET_BF16_GEMM_FP32_MASTER,
-                       model_kind=H.HDET_TRANSFORMER, batch=B, seed=I.SEED_PERM, stream=stream.cuda_stream, **cfg)
+                       model_kind=H.HDET_TRANSFORMER, batch=B, seed=I.SEED_PERM, stream=stream.cuda_stream,
+                       extra=extra, **cfg)
     _, _, ws_bytes = H.hdet_workspace_bytes(lc, stride)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     h = H.hdet_create(lc, theta, m, v, grads=g, params_bf16=shadow, workspace=ws, plane_stride=stride)
@@ -207,7 +216,8 @@ def transformer_workload(args):
     attn = L * 2 * 2.0 * B * nh * S * S * (d // nh)          # scores and P V, full (unmasked) squares
     gemm_flop = n * 3 * (lin + attn)                          # forward + dgrad + wgrad
     tflops = gemm_flop / (fb_ms * 1e-3) / 1e12
-    return {"workload": "N=8 x decoder-only transformer 6L d512 h8 ffn2048 seq256 vocab32000, 16 seq/replica, bf16 GEMM + fp32 master, AdamW, T=32",
+    return {"workload": f"N=8 x decoder-only transformer {L}L d{d} h{nh} ffn{ff} seq{S} vocab{V}, {B} seq/replica, "
+                        f"bf16 GEMM + fp32 master, AdamW, T={T}, {1 + len(extra)} channel(s)",
             "n_params": P, "replica_steps_per_s": n * args.steps / dt, "tokens_per_s": n * M * args.steps / dt,
             "ms_per_step": dt / args.steps * 1e3, "forward_backward_ms": fb_ms, "update_ms": up_ms,
             "update_GBps": 30.0 * n * P / (up_ms * 1e-3) / 1e9, "gemm_flop_per_step": gemm_flop,
@@ -272,6 +282,8 @@ def main():
                     help="flat: the headline flat-buffer case only; mlp: only the bf16 MLP case (printed as its own "
                          "JSON line); transformer: only the bf16 transformer case; both: the headline line with the "
                          "MLP and transformer figures attached as `mlp_bf16` and `transformer_bf16`")
+    ap.add_argument("--tf-config", choices=["6L", "12L"], default="6L",
+                    help="transformer workload: 6 layers d512 seq256 (default) or 12 layers d1024 seq512 with 3 channels")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of known size (reference point for HBM byte counters)")
     args = ap.parse_args()

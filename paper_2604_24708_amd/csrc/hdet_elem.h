@@ -96,6 +96,32 @@ __device__ __forceinline__ float hdet_wave_max(float x) {
   return x;
 }
 
+// GELU in its tanh form and its derivative (the transformer's MLP activation)
+__device__ __forceinline__ float hdet_gelu_tanh(float z) {
+  const float c = 0.7978845608028654f;
+  return 0.5f * z * (1.f + tanhf(c * (z + 0.044715f * z * z * z)));
+}
+__device__ __forceinline__ float hdet_gelu_tanh_grad(float z) {
+  const float c = 0.7978845608028654f;
+  const float t = tanhf(c * (z + 0.044715f * z * z * z));
+  return 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * z * z);
+}
+
+// The same two functions with tanh(u) = 1 - 2 / (exp(2u) + 1) on the hardware exp2 and
+// reciprocal (absolute error of a few 1e-7): for results that are rounded to bfloat16 anyway.
+__device__ __forceinline__ float hdet_tanh_fast(float u) {
+  return 1.f - 2.f * __builtin_amdgcn_rcpf(__expf(2.f * u) + 1.f);
+}
+__device__ __forceinline__ float hdet_gelu_tanh_fast(float z) {
+  const float c = 0.7978845608028654f;
+  return 0.5f * z * (1.f + hdet_tanh_fast(c * (z + 0.044715f * z * z * z)));
+}
+__device__ __forceinline__ float hdet_gelu_tanh_grad_fast(float z) {
+  const float c = 0.7978845608028654f;
+  const float t = hdet_tanh_fast(c * (z + 0.044715f * z * z * z));
+  return 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * z * z);
+}
+
 // Philox-4x32 with 10 rounds (Salmon et al., SC'11); used for dropout masks.
 struct hdet_philox4 { uint32_t x[4]; };
 __device__ __forceinline__ hdet_philox4 hdet_philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,

@@ -34,6 +34,7 @@
 //  * Launch order is remapped so that each XCD (own L2) works on a contiguous range of tiles.
 
 #include "hdet_internal.h"
+#include "hdet_elem.h"
 
 namespace {
 
@@ -265,7 +266,8 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
   static_assert(WGM * WGN * 32 * EP * 4 <= NST * STAGE * 2, "staging area exceeds the stage buffers");
   float* stg = reinterpret_cast<float*>(S) + wave * (32 * EP);
   const int lr = lane / LPR, lc = (lane % LPR) * 4;
-  constexpr bool kBias = EPI == HDET_EPI_BIAS_RELU_BF16 || EPI == HDET_EPI_BIAS_F32 || EPI == HDET_EPI_BIAS_BF16;
+  constexpr bool kBias = EPI == HDET_EPI_BIAS_RELU_BF16 || EPI == HDET_EPI_BIAS_F32 || EPI == HDET_EPI_BIAS_BF16 ||
+                         EPI == HDET_EPI_BIAS_GELU_BF16;
 #pragma unroll
   for (int jg = 0; jg < WNT / JG; ++jg) {
     const int col = n0 + wn + jg * CW + lc;
@@ -298,8 +300,19 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = bf2f(a[q]) > 0.f ? v[q] : 0.f;
           }
+          if (EPI == HDET_EPI_GELUGRAD_BF16) {  // the incoming gradient is rounded as the unfused path stores it
+            const us4 a = *reinterpret_cast<const us4*>(g.mask + (int64_t)z * g.mask_bs + (int64_t)row * g.mask_ld + col);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = bf2f(f2bf(v[q])) * hdet_gelu_tanh_grad_fast(bf2f(a[q]));
+          }
           if (EPI == HDET_EPI_F32 || EPI == HDET_EPI_BIAS_F32) {
             *reinterpret_cast<f4*>(reinterpret_cast<float*>(g.c) + off) = v;
+          } else if (EPI == HDET_EPI_BIAS_GELU_BF16) {
+            const us4 pre = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
+            *reinterpret_cast<us4*>(reinterpret_cast<uint16_t*>(g.c) + off) = pre;
+            const us4 o = {f2bf(hdet_gelu_tanh_fast(bf2f(pre[0]))), f2bf(hdet_gelu_tanh_fast(bf2f(pre[1]))),
+                           f2bf(hdet_gelu_tanh_fast(bf2f(pre[2]))), f2bf(hdet_gelu_tanh_fast(bf2f(pre[3])))};
+            *reinterpret_cast<us4*>(reinterpret_cast<uint16_t*>(g.c2) + off) = o;
           } else {
             const us4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
             *reinterpret_cast<us4*>(reinterpret_cast<uint16_t*>(g.c) + off) = o;
@@ -340,7 +353,8 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
 
 bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi) {
   const bool f32_out = epi == HDET_EPI_F32 || epi == HDET_EPI_BIAS_F32;
-  const bool has_bias = epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_BIAS_RELU_BF16;
+  const bool has_bias = epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_BIAS_RELU_BF16 ||
+                        epi == HDET_EPI_BIAS_GELU_BF16;
   if (g.m < 1 || g.n < 1 || g.k < 1) return false;
   // a chunk is 8 elements along the operand's contiguous axis: k if k-major, else the row axis
   if (!chunk_regular(g.a, g.lda, g.a_s, a_kmajor ? g.k : g.m)) return false;
@@ -355,11 +369,15 @@ bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kma
   if ((g.ldc & 3) || ((g.c_s[0] | g.c_s[1] | g.c_s[2]) & 3) || (g.n & 3)) return false;
   if (reinterpret_cast<uintptr_t>(g.c) & (f32_out ? 15 : 7)) return false;
   if (has_bias && ((g.bias_bs & 3) || (reinterpret_cast<uintptr_t>(g.bias) & 15))) return false;
-  if (epi == HDET_EPI_MASK_BF16 && ((g.mask_ld & 3) || (g.mask_bs & 3) || (reinterpret_cast<uintptr_t>(g.mask) & 7))) return false;
+  if ((epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_GELUGRAD_BF16) &&
+      (!g.mask || (g.mask_ld & 3) || (g.mask_bs & 3) || (reinterpret_cast<uintptr_t>(g.mask) & 7)))
+    return false;
+  if (epi == HDET_EPI_BIAS_GELU_BF16 && (!g.c2 || (reinterpret_cast<uintptr_t>(g.c2) & 7))) return false;
   // instantiated combinations: what the MLP and the transformer use
   if (a_kmajor && b_kmajor)
-    return epi == HDET_EPI_BIAS_RELU_BF16 || epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_F32;
-  if (a_kmajor && !b_kmajor) return epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_BF16;
+    return epi == HDET_EPI_BIAS_RELU_BF16 || epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_F32 ||
+           epi == HDET_EPI_BIAS_GELU_BF16;
+  if (a_kmajor && !b_kmajor) return epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_BF16 || epi == HDET_EPI_GELUGRAD_BF16;
   if (!a_kmajor && !b_kmajor) return epi == HDET_EPI_F32 || epi == HDET_EPI_BF16;
   return false;
 }
@@ -375,11 +393,13 @@ hipError_t hdet_launch_bgemm_dma(const hdet_bgemm_args& g_in, bool a_kmajor, boo
       case HDET_EPI_BIAS_RELU_BF16: return launch_shape<true, true, HDET_EPI_BIAS_RELU_BF16>(g, batch, s);
       case HDET_EPI_BIAS_F32: return launch_shape<true, true, HDET_EPI_BIAS_F32>(g, batch, s);
       case HDET_EPI_BIAS_BF16: return launch_shape<true, true, HDET_EPI_BIAS_BF16>(g, batch, s);
+      case HDET_EPI_BIAS_GELU_BF16: return launch_shape<true, true, HDET_EPI_BIAS_GELU_BF16>(g, batch, s);
       default: return launch_shape<true, true, HDET_EPI_F32>(g, batch, s);
     }
   }
   if (a_kmajor) {                        // dgrad
     if (epi == HDET_EPI_MASK_BF16) return launch_shape<true, false, HDET_EPI_MASK_BF16>(g, batch, s);
+    if (epi == HDET_EPI_GELUGRAD_BF16) return launch_shape<true, false, HDET_EPI_GELUGRAD_BF16>(g, batch, s);
     return launch_shape<true, false, HDET_EPI_BF16>(g, batch, s);
   }
   if (epi == HDET_EPI_F32) return launch_shape<false, false, HDET_EPI_F32>(g, batch, s);   // wgrad

@@ -135,12 +135,16 @@ hipError_t hdet_launch_sgemm(const hdet_sgemm_args& g, int epi, int batch, hipSt
 
 // bf16 GEMM on the matrix cores (hdet_gemm_bf16.hip)
 enum { HDET_EPI_F32 = 0, HDET_EPI_BIAS_F32 = 1, HDET_EPI_BIAS_RELU_BF16 = 2, HDET_EPI_MASK_BF16 = 3,
-       HDET_EPI_BF16 = 4, HDET_EPI_BIAS_BF16 = 5 };
+       HDET_EPI_BF16 = 4, HDET_EPI_BIAS_BF16 = 5,
+       // LDS-direct kernel only (the caller checks hdet_bgemm_dma_eligible first):
+       HDET_EPI_BIAS_GELU_BF16 = 6,   // c = bf16(acc + bias), c2 = bf16(gelu(c)): pre-activation and activation
+       HDET_EPI_GELUGRAD_BF16 = 7 };  // c = bf16(bf16(acc) * gelu'(mask)): gradient through the GELU at pre-activation `mask`
 
 struct hdet_bgemm_args {
   const uint16_t* a;       // bf16
   const uint16_t* b;       // bf16
   void* c;                 // fp32 or bf16, row-major [m][ldc]
+  void* c2;                // second bf16 output in c's layout (HDET_EPI_BIAS_GELU_BF16) or nullptr
   int m, n, k;
   int n1, n2;              // batch split (0 is read as 1)
   int64_t lda, ldb, ldc;   // leading dimensions in elements

@@ -406,15 +406,6 @@ __global__ __launch_bounds__(256) void softmax_bwd_vec_kernel(const float* dp, c
   }
 }
 
-__device__ __forceinline__ float gelu_tanh(float z) {
-  const float c = 0.7978845608028654f;
-  return 0.5f * z * (1.f + tanhf(c * (z + 0.044715f * z * z * z)));
-}
-__device__ __forceinline__ float gelu_tanh_grad(float z) {
-  const float c = 0.7978845608028654f;
-  const float t = tanhf(c * (z + 0.044715f * z * z * z));
-  return 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * z * z);
-}
 
 // 8 elements per thread and access; the n % 8 tail is done element-wise by the first threads
 template <typename T>
@@ -423,10 +414,10 @@ __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T* z, T* f, int64_t
   for (int64_t i = tid; i < n8; i += (int64_t)gridDim.x * 256) {
     hdet_f8 v = hdet_ld8(z + 8 * i);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v.v[j] = gelu_tanh(v.v[j]);
+    for (int j = 0; j < 8; ++j) v.v[j] = hdet_gelu_tanh(v.v[j]);
     hdet_st8(f + 8 * i, v);
   }
-  if (tid < (n & 7)) hdet_st(f + 8 * n8 + tid, gelu_tanh(hdet_ld(z + 8 * n8 + tid)));
+  if (tid < (n & 7)) hdet_st(f + 8 * n8 + tid, hdet_gelu_tanh(hdet_ld(z + 8 * n8 + tid)));
 }
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* df, const T* z, T* dz, int64_t n) {
@@ -435,10 +426,10 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* df, const T* z, 
     hdet_f8 v = hdet_ld8(df + 8 * i);
     const hdet_f8 zv = hdet_ld8(z + 8 * i);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v.v[j] *= gelu_tanh_grad(zv.v[j]);
+    for (int j = 0; j < 8; ++j) v.v[j] *= hdet_gelu_tanh_grad(zv.v[j]);
     hdet_st8(dz + 8 * i, v);
   }
-  if (tid < (n & 7)) hdet_st(dz + 8 * n8 + tid, hdet_ld(df + 8 * n8 + tid) * gelu_tanh_grad(hdet_ld(z + 8 * n8 + tid)));
+  if (tid < (n & 7)) hdet_st(dz + 8 * n8 + tid, hdet_ld(df + 8 * n8 + tid) * hdet_gelu_tanh_grad(hdet_ld(z + 8 * n8 + tid)));
 }
 
 // Dropout of a residual branch.  Element e of the replica's [M][d] tensor is kept iff word
@@ -704,18 +695,36 @@ struct mat { const void* p; int64_t ld; int64_t s[3]; };
 // C = A B in the given operand order; the output is of the activation type (act_out) or
 // fp32; bias (fp32, per replica) is optional.  Element offsets inside `p` are in elements of
 // the operand's own type.
+// GELU fused into the bf16 GEMMs around it.  gelu_out: the product is the pre-activation z
+// (written to c) and f = gelu(z) goes to gelu_out; gelu_pre: the product is the gradient at f and
+// c receives the gradient at z = that * gelu'(gelu_pre).  `*fused` tells whether the GEMM took
+// them (it does on the LDS-direct path); otherwise the caller runs the element-wise kernel.
+struct gelu_fusion { void* gelu_out; const void* gelu_pre; bool* fused; };
+
 template <typename T>
 hipError_t gemm(const hdet_tf_plan* pl, int form, mat A, mat B, void* c, int64_t ldc, const int64_t* c_s, bool act_out,
-                int m, int n, int k, int n1, int n2, const float* bias, int64_t bias_bs, hipStream_t s) {
+                int m, int n, int k, int n1, int n2, const float* bias, int64_t bias_bs, hipStream_t s,
+                const gelu_fusion* gf = nullptr) {
   const int batch = pl->N * (n1 < 1 ? 1 : n1) * (n2 < 1 ? 1 : n2);
+  if (gf) *gf->fused = false;
   if (sizeof(T) == 2) {
     hdet_bgemm_args g = {};
     g.a = (const uint16_t*)A.p; g.b = (const uint16_t*)B.p; g.c = c;
-    g.m = m; g.n = n; g.k = k; g.n1 = n1; g.n2 = n2;
+    g.m = m; g.n = n; g.k = k; g.n1 = n1 < 1 ? 1 : n1; g.n2 = n2 < 1 ? 1 : n2;
     g.lda = A.ld; g.ldb = B.ld; g.ldc = ldc;
     for (int i = 0; i < 3; ++i) { g.a_s[i] = A.s[i]; g.b_s[i] = B.s[i]; g.c_s[i] = c_s[i]; }
     g.bias = bias; g.bias_bs = bias_bs;
-    const int epi = act_out ? (bias ? HDET_EPI_BIAS_BF16 : HDET_EPI_BF16) : (bias ? HDET_EPI_BIAS_F32 : HDET_EPI_F32);
+    int epi = act_out ? (bias ? HDET_EPI_BIAS_BF16 : HDET_EPI_BF16) : (bias ? HDET_EPI_BIAS_F32 : HDET_EPI_F32);
+    if (gf && act_out) {
+      hdet_bgemm_args f = g;
+      int fepi;
+      if (gf->gelu_out) { f.c2 = gf->gelu_out; fepi = HDET_EPI_BIAS_GELU_BF16; }
+      else { f.mask = (const uint16_t*)gf->gelu_pre; f.mask_ld = ldc; f.mask_bs = c_s[0]; fepi = HDET_EPI_GELUGRAD_BF16; }
+      if ((fepi != HDET_EPI_BIAS_GELU_BF16 || bias) && hdet_bgemm_dma_eligible(f, form != TN, form == NT, fepi)) {
+        *gf->fused = true;
+        return hdet_launch_bgemm(f, form != TN, form == NT, fepi, batch, s);
+      }
+    }
     return hdet_launch_bgemm(g, form != TN, form == NT, epi, batch, s);
   }
   hdet_sgemm_args g = {};
@@ -782,8 +791,13 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     da.site = 2 * l;
     hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_in[l], (const T*)p->tmp_d, (T*)p->x_mid[l], nd, da);
     launch_ln_fwd<T>(p, p->x_mid[l], o.ln2_g, o.ln2_b, p->h2[l], p->st2_mean[l], p->st2_rstd[l], s);
-    TF_CHECK(gemm<T>(p, NT, act(p->h2[l], d), wt(o.w_1, d), p->z[l], ff, act_ff, true, M, ff, d, 1, 1, theta + o.b_1, ps, s));
-    hipLaunchKernelGGL(gelu_fwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->z[l], (T*)p->f[l], (int64_t)N * nff);
+    {
+      bool fused = false;
+      const gelu_fusion gf = {p->f[l], nullptr, &fused};
+      TF_CHECK(gemm<T>(p, NT, act(p->h2[l], d), wt(o.w_1, d), p->z[l], ff, act_ff, true, M, ff, d, 1, 1, theta + o.b_1, ps, s, &gf));
+      if (!fused)
+        hipLaunchKernelGGL(gelu_fwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->z[l], (T*)p->f[l], (int64_t)N * nff);
+    }
     TF_CHECK(gemm<T>(p, NT, act(p->f[l], ff), wt(o.w_2, ff), p->tmp_d, d, act_d, true, M, d, ff, 1, 1, theta + o.b_2, ps, s));
     da.site = 2 * l + 1;
     hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_mid[l], (const T*)p->tmp_d, (T*)p->x_in[l + 1], nd, da);
@@ -820,8 +834,13 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     }
     TF_CHECK(wgrad(dy, d, p->f[l], ff, o.w_2));
     colsum(dy, d, o.b_2);
-    TF_CHECK(gemm<T>(p, NN, act(dy, d), wt(o.w_2, ff), p->dff, ff, act_ff, true, M, ff, d, 1, 1, nullptr, 0, s));
-    hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->dff, (const T*)p->z[l], (T*)p->dff, (int64_t)N * nff);
+    {
+      bool fused = false;
+      const gelu_fusion gf = {nullptr, p->z[l], &fused};
+      TF_CHECK(gemm<T>(p, NN, act(dy, d), wt(o.w_2, ff), p->dff, ff, act_ff, true, M, ff, d, 1, 1, nullptr, 0, s, &gf));
+      if (!fused)
+        hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->dff, (const T*)p->z[l], (T*)p->dff, (int64_t)N * nff);
+    }
     TF_CHECK(wgrad(p->dff, ff, p->h2[l], d, o.w_1));
     colsum(p->dff, ff, o.b_1);
     TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
