@@ -233,7 +233,9 @@ int hdet_set_state(hdet_handle* h, const hdet_state* in);
  * kernel for the case (one thread per replica column, or -- when gradients or parameters
  * must cross the replica axis and N <= 16 -- one wavefront per replica with an LDS
  * exchange); variant 1: the general kernel in which one thread walks the replica axis (any
- * N).  `blocks` > 0 sets the grid of the grid-stride kernels (0: library default).          */
+ * N).  `blocks` > 0 sets the grid of the grid-stride kernels (0: library default).
+ * variant | 2: the transformer's attention runs as separate batched GEMMs and softmax
+ * kernels (scores and probabilities in device memory) also where the fused kernels apply.    */
 int hdet_set_launch_shape(hdet_handle* h, int32_t variant, int32_t blocks);
 
 /* Message of the last failure on this handle (or of the last failed hdet_create if h is

@@ -13,7 +13,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhdet.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["hdet_api.hip", "hdet_update.hip", "hdet_controller.hip", "hdet_mlp.hip", "hdet_gemm_bf16.hip", "hdet_gemm_bf16_dma.hip", "hdet_gemm_f32.hip", "hdet_transformer.hip", "hdet_warm.hip"]
+SOURCES = ["hdet_api.hip", "hdet_update.hip", "hdet_controller.hip", "hdet_mlp.hip", "hdet_gemm_bf16.hip", "hdet_gemm_bf16_dma.hip", "hdet_gemm_f32.hip", "hdet_transformer.hip", "hdet_attention.hip", "hdet_warm.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -478,10 +478,11 @@ int hdet_set_state(hdet_handle* h, const hdet_state* in) {
 
 int hdet_set_launch_shape(hdet_handle* h, int32_t variant, int32_t blocks) {
   if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
-  if (variant < 0 || variant > 1) return fail(h, HDET_EINVAL, "variant must be 0 or 1");
+  if (variant < 0 || variant > 3) return fail(h, HDET_EINVAL, "variant must be 0..3");
   if (blocks < 0) return fail(h, HDET_EINVAL, "negative block count");
-  h->tune_variant = variant;
+  h->tune_variant = variant & 1;
   h->tune_blocks = blocks;
+  if (h->tf) hdet_tf_set_fused_attention(h->tf, (variant & 2) == 0);
   return HDET_OK;
 }
 

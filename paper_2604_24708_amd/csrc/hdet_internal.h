@@ -185,9 +185,30 @@ int hdet_tf_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* 
 hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, int drop_channel, int ls_channel,
                              int temp_channel, std::string* err);
 void hdet_tf_destroy(hdet_tf_plan* p);
+void hdet_tf_set_fused_attention(hdet_tf_plan* p, bool on);   // on by default where the fused kernels apply
 // `step`: the update this gradient is for (keys the dropout masks)
 hipError_t hdet_tf_forward_backward(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl,
                                     uint32_t step, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// Fused causal attention, bf16 (hdet_attention.hip)
+// ---------------------------------------------------------------------------------------
+struct hdet_attn_desc {
+  const uint16_t* qkv;      // [N][B][S][3 d_model]: q | k | v, head h in columns h*64..
+  uint16_t* a;              // forward output [N][B][S][d_model]
+  const uint16_t* da;       // backward: gradient at a
+  uint16_t* dqkv;           // backward output, layout of qkv
+  float* row_max;           // [N][B][heads][S] row statistics, written by the forward
+  float* row_inv;
+  float* row_dot;           // scratch of the backward, same shape
+  const hdet_ctrl* ctrl;
+  int temp_channel;         // attention-temperature channel or -1
+  float scale;              // 1 / sqrt(d_head)
+  int n_replicas, batch, seq_len, heads, d_model;
+};
+bool hdet_attn_fusable(int seq_len, int d_model, int heads);     // head size 64, S a multiple of 64 up to 256
+hipError_t hdet_launch_attn_fwd(const hdet_attn_desc& a, hipStream_t stream);
+hipError_t hdet_launch_attn_bwd(const hdet_attn_desc& a, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
 // Host handle

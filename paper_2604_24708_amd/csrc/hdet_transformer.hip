@@ -502,6 +502,9 @@ struct hdet_tf_plan {
   std::vector<float*> st1_mean, st1_rstd, st2_mean, st2_rstd;
   char *hf, *tmp_d, *dxa, *dxb, *dtmp, *dtmp2, *dff, *dqkv, *ds, *dlogits;
   float *stf_mean, *stf_rstd, *scores, *logits, *row_loss;
+  std::vector<float*> att_max, att_inv;      // [L] row statistics of the fused attention
+  float* att_dot;
+  bool fused_attn;                           // bf16, head size 64, S a multiple of 64 up to 256
   float *part1, *part2;      // partial column sums [N][row chunks][cols]
   int nrc;                   // row chunks of the two-stage column sums
 };
@@ -519,6 +522,7 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   p->x_in.assign(L + 1, nullptr); p->x_mid.assign(L, nullptr); p->h1.assign(L, nullptr); p->h2.assign(L, nullptr);
   p->qkv.assign(L, nullptr); p->p.assign(L, nullptr); p->a.assign(L, nullptr); p->z.assign(L, nullptr); p->f.assign(L, nullptr);
   p->st1_mean.assign(L, nullptr); p->st1_rstd.assign(L, nullptr); p->st2_mean.assign(L, nullptr); p->st2_rstd.assign(L, nullptr);
+  p->att_max.assign(L, nullptr); p->att_inv.assign(L, nullptr);
   for (int l = 0; l <= L; ++l) p->x_in[l] = take(N * M * d * e);
   for (int l = 0; l < L; ++l) {
     p->x_mid[l] = take(N * M * d * e); p->h1[l] = take(N * M * d * e); p->h2[l] = take(N * M * d * e);
@@ -526,6 +530,7 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
     p->z[l] = take(N * M * ff * e); p->f[l] = take(N * M * ff * e);
     p->st1_mean[l] = (float*)take(N * M * 4); p->st1_rstd[l] = (float*)take(N * M * 4);
     p->st2_mean[l] = (float*)take(N * M * 4); p->st2_rstd[l] = (float*)take(N * M * 4);
+    p->att_max[l] = (float*)take(N * heads * S * 4); p->att_inv[l] = (float*)take(N * heads * S * 4);
   }
   p->hf = take(N * M * d * e); p->tmp_d = take(N * M * d * e);
   p->dxa = take(N * M * d * e); p->dxb = take(N * M * d * e); p->dtmp = take(N * M * d * e); p->dtmp2 = take(N * M * d * e);
@@ -534,6 +539,7 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   p->stf_mean = (float*)take(N * M * 4); p->stf_rstd = (float*)take(N * M * 4);
   p->scores = (float*)take(N * heads * S * S * 4); p->logits = (float*)take(N * M * V * 4);
   p->row_loss = (float*)take(N * M * 4);
+  p->att_dot = (float*)take(N * heads * S * 4);
   p->nrc = (int)((M + kColsumRows - 1) / kColsumRows);
   size_t maxc = V > 3 * d ? V : 3 * d;
   if (ff > maxc) maxc = ff;
@@ -548,6 +554,7 @@ static void tf_dims(hdet_tf_plan* p, const hdet_config& cfg) {
   p->N = cfg.n_replicas; p->B = cfg.dims.batch; p->S = cfg.dims.seq_len; p->M = p->B * p->S;
   p->d = cfg.dims.d_model; p->nh = cfg.dims.n_heads; p->dh = p->d / p->nh; p->ff = cfg.dims.d_ff;
   p->V = cfg.dims.vocab; p->L = cfg.dims.n_blocks;
+  p->fused_attn = p->bf16 && hdet_attn_fusable(p->S, p->d, p->nh);
 }
 
 int64_t hdet_tf_param_count(const hdet_config& cfg) {
@@ -606,6 +613,10 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
 }
 
 void hdet_tf_destroy(hdet_tf_plan* p) { delete p; }
+
+void hdet_tf_set_fused_attention(hdet_tf_plan* p, bool on) {
+  p->fused_attn = on && p->bf16 && hdet_attn_fusable(p->S, p->d, p->nh);
+}
 
 namespace {
 
@@ -769,6 +780,14 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     mat t = {base, d, {(int64_t)M * d, (int64_t)S * d, dh}};
     return t;
   };
+  auto attn_desc = [&](int l) {
+    hdet_attn_desc ad;
+    ad.qkv = (const uint16_t*)p->qkv[l]; ad.a = (uint16_t*)p->a[l]; ad.da = (const uint16_t*)p->dtmp; ad.dqkv = (uint16_t*)p->dqkv;
+    ad.row_max = p->att_max[l]; ad.row_inv = p->att_inv[l]; ad.row_dot = p->att_dot;
+    ad.ctrl = ctrl; ad.temp_channel = p->temp_channel; ad.scale = scale;
+    ad.n_replicas = N; ad.batch = B; ad.seq_len = S; ad.heads = nh; ad.d_model = d;
+    return ad;
+  };
   const int64_t act_d[3] = {(int64_t)M * d, 0, 0}, act_3d[3] = {(int64_t)M * 3 * d, 0, 0}, act_ff[3] = {(int64_t)M * ff, 0, 0},
                 act_v[3] = {(int64_t)M * V, 0, 0}, plane[3] = {ps, 0, 0};
 
@@ -778,14 +797,19 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     const tf_block_off& o = p->blk[l];
     launch_ln_fwd<T>(p, p->x_in[l], o.ln1_g, o.ln1_b, p->h1[l], p->st1_mean[l], p->st1_rstd[l], s);
     TF_CHECK(gemm<T>(p, NT, act(p->h1[l], d), wt(o.w_qkv, d), p->qkv[l], 3 * d, act_3d, true, M, 3 * d, d, 1, 1, theta + o.b_qkv, ps, s));
-    {   // scores = q k^T per (replica, sequence, head)
-      const mat sc = head_sq(p->scores);
-      TF_CHECK(gemm<T>(p, NT, qkv_part(p->qkv[l], 0), qkv_part(p->qkv[l], 1), p->scores, S, sc.s, false, S, S, dh, B, nh, nullptr, 0, s));
-    }
-    launch_softmax_fwd<T>(p->scores, heads_rows, S, scale, ta, p->p[l], s);
-    {   // a = p v
-      const mat ac = head_cols(p->a[l]);
-      TF_CHECK(gemm<T>(p, NN, head_sq(p->p[l]), qkv_part(p->qkv[l], 2), p->a[l], d, ac.s, true, S, dh, S, B, nh, nullptr, 0, s));
+    if (p->fused_attn) {
+      hdet_attn_desc ad = attn_desc(l);
+      TF_CHECK(hdet_launch_attn_fwd(ad, s));
+    } else {
+      {   // scores = q k^T per (replica, sequence, head)
+        const mat sc = head_sq(p->scores);
+        TF_CHECK(gemm<T>(p, NT, qkv_part(p->qkv[l], 0), qkv_part(p->qkv[l], 1), p->scores, S, sc.s, false, S, S, dh, B, nh, nullptr, 0, s));
+      }
+      launch_softmax_fwd<T>(p->scores, heads_rows, S, scale, ta, p->p[l], s);
+      {   // a = p v
+        const mat ac = head_cols(p->a[l]);
+        TF_CHECK(gemm<T>(p, NN, head_sq(p->p[l]), qkv_part(p->qkv[l], 2), p->a[l], d, ac.s, true, S, dh, S, B, nh, nullptr, 0, s));
+      }
     }
     TF_CHECK(gemm<T>(p, NT, act(p->a[l], d), wt(o.w_o, d), p->tmp_d, d, act_d, true, M, d, d, 1, 1, theta + o.b_o, ps, s));
     da.site = 2 * l;
@@ -856,7 +880,10 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(wgrad(dob, d, p->a[l], d, o.w_o));
     colsum(dob, d, o.b_o);
     TF_CHECK(gemm<T>(p, NN, act(dob, d), wt(o.w_o, d), p->dtmp, d, act_d, true, M, d, d, 1, 1, nullptr, 0, s));   // da
-    {
+    if (p->fused_attn) {
+      hdet_attn_desc ad = attn_desc(l);
+      TF_CHECK(hdet_launch_attn_bwd(ad, s));
+    } else {
       const mat sc = head_sq(p->scores);
       const mat dq = qkv_part(p->dqkv, 0), dk = qkv_part(p->dqkv, 1), dv = qkv_part(p->dqkv, 2);
       // dp = da v^T

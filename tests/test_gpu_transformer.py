@@ -17,6 +17,11 @@ SMALL = dict(n_blocks=2, d_model=64, n_heads=4, d_ff=256, seq_len=32, vocab=512)
 ODD = dict(n_blocks=1, d_model=24, n_heads=3, d_ff=50, seq_len=70, vocab=131)        # ragged everywhere
 # two register chunks per lane in LayerNorm (d > 512) and softmax (S > 256), wide-row cross-entropy
 MID = dict(n_blocks=1, d_model=576, n_heads=9, d_ff=1152, seq_len=264, vocab=2304)
+# head size 64 and sequence lengths that are multiples of 64: the shapes the fused attention kernels take
+# (one, three and four 64-row blocks per sequence; one and two heads)
+FUSE1 = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=64, vocab=50)
+FUSE3 = dict(n_blocks=2, d_model=128, n_heads=2, d_ff=96, seq_len=192, vocab=61)
+FUSE4 = dict(n_blocks=1, d_model=128, n_heads=2, d_ff=64, seq_len=256, vocab=40)
 
 
 def norm_err(a, b):
@@ -225,3 +230,32 @@ def test_fp32_label_smoothing_and_attention_temperature_channels(cfg, batch):
     assert np.min(np.abs(gl0 - gl1)) > 1e-4
     for x in (run, plain, run2):
         x.close()
+
+
+@pytest.mark.parametrize("cfg,batch,n", [(FUSE1, 2, 2), (FUSE3, 2, 3), (FUSE4, 3, 2)])
+def test_bf16_fused_attention_against_oracle_and_unfused_path(cfg, batch, n):
+    """The fused attention kernels (scores kept on chip) against the oracle, at the mixed-precision
+    bar, and against the library's own path through separate GEMM and softmax kernels, with which
+    they share every bf16 rounding point: those two agree far more closely.  An attention
+    temperature channel makes the score scale differ per replica."""
+    extra = [(O.CH_ATTN_TEMP, 1.2, 0.4, 0.5, 0.25, 4.0)]
+    d = base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, extra=extra)
+    fused, plain = TfRun(d, cfg, batch, bf16=True), TfRun(d, cfg, batch, bf16=True)
+    H.hdet_set_launch_shape(plain.h, 2, 0)                # separate kernels, scores in device memory
+    for t in range(1, 4):
+        ids, tgt, gl = fused.forward_backward(t)
+        losses, grads = fused.oracle_grads(fused.orc.theta, ids, tgt, t)
+        assert np.max(np.abs(gl - losses)) <= 1e-2
+        gf = fused.g.cpu().numpy()[:, :fused.P]
+        for r in range(n):
+            bad = {k: v for k, v in per_tensor_errors(cfg, gf[r], grads[r]).items() if v > 4e-2}
+            assert not bad, ("oracle", t, r, bad)
+        if t == 1:      # same parameters on both handles only before the first update
+            _, _, gl_plain = plain.forward_backward(t)
+            assert np.max(np.abs(gl - gl_plain)) <= 5e-4    # a few bf16 roundings flip with the order of the fp32 row sums
+            gp = plain.g.cpu().numpy()[:, :fused.P]
+            for r in range(n):
+                bad = {k: v for k, v in per_tensor_errors(cfg, gf[r], gp[r]).items() if v > 5e-3}
+                assert not bad, ("unfused", t, r, bad)
+        fused.finish_step(t, grads, losses)
+    fused.close(); plain.close()
