@@ -1,6 +1,6 @@
 // Causal self-attention of the transformer replicas in mixed precision, forward and backward,
 // with the scores kept on chip ("Forward + backward" of Algorithm 1 for the attention part of a
-// block).  For head size 64 and sequence lengths that are multiples of 64 up to 256 this
+// block).  For head size 64 and sequence lengths that are multiples of 64 up to 512 this
 // replaces five batched GEMMs, two softmax kernels and the [S][S] score and probability tensors
 // in HBM by three kernels that read q, k, v (and the output gradient) once per 64-row block.
 //
@@ -19,6 +19,7 @@
 // conflicts; operands that are contracted along their row index are read with the transposing
 // LDS load, so nothing is transposed in memory.
 //   forward  : block = (64 queries, sequence, head, replica); wavefront w owns key block w
+//              (4 wavefronts for S <= 256, 8 beyond)
 //   backward : 1. same mapping: rebuilds p, forms dp, the row dots (kept for step 2), ds and dq
 //                 (q and da fragments go from global memory straight to registers)
 //              2. block = (64 keys, sequence, head, replica), loop over the query blocks at or
@@ -39,8 +40,7 @@ typedef unsigned short us8 __attribute__((ext_vector_type(8)));
 constexpr int DH = 64;            // head size
 constexpr int QB = 64;            // rows per block
 constexpr int PT = DH + 8;        // pitch of a [rows][64] tile
-constexpr int SMAX = 256;         // longest sequence (4 wavefronts x 64 keys)
-constexpr int PP = SMAX + 8;      // pitch of a [64][S] tile
+constexpr int SMAX = 512;         // longest sequence: one key block of 64 per wavefront, at most 8 wavefronts
 
 __device__ __forceinline__ unsigned short f2bf(float x) { return __builtin_bit_cast(unsigned short, (__bf16)x); }
 __device__ __forceinline__ float bf2f(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
@@ -74,29 +74,29 @@ __device__ __forceinline__ f16v zero16() {
 // accumulator element e of lane l sits at (row = (e / 4) * 8 + (l / 32) * 4 + e % 4, col = l % 32) of its 32x32 block
 __device__ __forceinline__ int acc_row(int e, int lane) { return ((e >> 2) << 3) + ((lane >> 5) << 2) + (e & 3); }
 
-// rows x 64 bf16 from global (row pitch `ld` elements) into an LDS tile of pitch PT by 256 threads,
+// rows x 64 bf16 from global (row pitch `ld` elements) into an LDS tile of pitch PT by THREADS threads,
 // in two phases so that all loads of a block are in flight together: fetch() issues up to NC
 // 16-byte loads per thread, commit() writes them to LDS.
-template <int NC>
+template <int NC, int THREADS = 256>
 struct tile_loader {
   us8 v[NC];
   __device__ __forceinline__ void fetch(const uint16_t* src, int64_t ld, int rows, int tid) {
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-      const int c = tid + i * 256;
+      const int c = tid + i * THREADS;
       if (c < rows * 8) v[i] = *reinterpret_cast<const us8*>(src + (int64_t)(c >> 3) * ld + ((c & 7) << 3));
     }
   }
   __device__ __forceinline__ void commit(uint16_t* dst, int rows, int tid) const {
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-      const int c = tid + i * 256;
+      const int c = tid + i * THREADS;
       if (c < rows * 8) *reinterpret_cast<us8*>(dst + (c >> 3) * PT + ((c & 7) << 3)) = v[i];
     }
   }
 };
-constexpr int NCQ = QB * 8 / 256;        // chunks per thread of a 64-row tile
-constexpr int NCK = SMAX * 8 / 256;      // ... of all keys / values of a sequence
+constexpr int NCQ = QB * 8 / 256;        // chunks per thread of a 64-row tile (256 threads)
+constexpr int NCK = 8;                   // ... of all keys / values of a sequence (64 rows per wavefront)
 struct attn_args {
   const uint16_t* qkv;      // [N][B][S][3d]
   uint16_t* a;              // forward: [N][B][S][d] output
@@ -149,11 +149,14 @@ __device__ __forceinline__ float exp_fast(float x) { return __expf(x); }
 // ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const attn_args g) {
+// NW wavefronts: sequences of up to 64 NW keys (4: two blocks per CU; 8: one)
+template <int NW>
+__global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const attn_args g) {
+  constexpr int PP = 64 * NW + 8;                                        // pitch of the [64][S] tile
   __shared__ __attribute__((aligned(16))) uint16_t Qs[QB * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t KVs[SMAX * PT];      // keys, then values
+  __shared__ __attribute__((aligned(16))) uint16_t KVs[64 * NW * PT];   // keys, then values
   __shared__ __attribute__((aligned(16))) uint16_t Ps[QB * PP];
-  __shared__ float red[4][QB];
+  __shared__ float red[NW][QB];
   __shared__ float stat[2][QB];                                          // row max, 1 / row sum
   const int qb = blockIdx.x, bh = blockIdx.y, r = blockIdx.z;
   const int b = bh / g.heads, h = bh - b * g.heads;
@@ -163,8 +166,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const attn_args g) {
   const uint16_t* base = g.qkv + (((int64_t)r * g.B + b) * g.S) * ld + h * DH;
   const float scale = replica_scale(g, r);
 
-  tile_loader<NCQ> lq;
-  tile_loader<NCK> lk, lv;
+  tile_loader<QB * 8 / (64 * NW), 64 * NW> lq;
+  tile_loader<NCK, 64 * NW> lk, lv;
   lq.fetch(base + (int64_t)qb * QB * ld, ld, QB, tid);
   lk.fetch(base + g.d, ld, kmax, tid);
   lv.fetch(base + 2 * g.d, ld, kmax, tid);          // consumed after the softmax
@@ -195,7 +198,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const attn_args g) {
     if (lane < 32) red[w][q] = m;
   }
   __syncthreads();
-  if (tid < QB) stat[0][tid] = fmaxf(fmaxf(red[0][tid], red[1][tid]), fmaxf(red[2][tid], red[3][tid]));
+  if (tid < QB) {
+    float m = red[0][tid];
+#pragma unroll
+    for (int x = 1; x < NW; ++x) m = fmaxf(m, red[x][tid]);
+    stat[0][tid] = m;
+  }
   __syncthreads();
   // exponentials and row sums
 #pragma unroll
@@ -214,7 +222,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const attn_args g) {
   }
   __syncthreads();
   if (tid < QB) {
-    const float inv = 1.f / (((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid]);
+    float sum = red[0][tid];
+#pragma unroll
+    for (int x = 1; x < NW; ++x) sum += red[x][tid];
+    const float inv = 1.f / sum;
     stat[1][tid] = inv;
     const int64_t gr = (((int64_t)r * g.B + b) * g.heads + h) * g.S + qb * QB + tid;
     g.row_max[gr] = stat[0][tid];
@@ -240,7 +251,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const attn_args g) {
   __syncthreads();                       // all reads of the keys are done as well
   lv.commit(KVs, kmax, tid);
   __syncthreads();
-  // a = p v: wavefront w owns the 32 x 32 block (w / 2, w % 2) of the 64 x 64 output
+  // a = p v: wavefront w < 4 owns the 32 x 32 block (w / 2, w % 2) of the 64 x 64 output
+  if (w >= 4) return;
   const int r0 = (w >> 1) * 32, c0 = (w & 1) * 32;
   f16v out = zero16();
   for (int ks = 0; ks < kmax; ks += 16) out = mfma(frag_k(Ps, PP, r0, ks, lane), frag_t(KVs, PT, c0, ks, lane), out);
@@ -256,12 +268,14 @@ __device__ __forceinline__ float prob(float s, float mx, float inv) { return bf1
 // ---------------------------------------------------------------------------------------------
 // backward, step 1: dq and the row dots
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const attn_args g) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[SMAX * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[SMAX * PT];       // values, then ds [query][key] with pitch PP
-  __shared__ float red[4][QB];
+template <int NW>
+__global__ __launch_bounds__(64 * NW, 2) void attn_bwd_dq_kernel(const attn_args g) {
+  constexpr int PP = 64 * NW + 8;
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * NW * PT];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * NW * PT];    // values, then ds [query][key] with pitch PP
+  __shared__ float red[NW][QB];
   __shared__ float stat[3][QB];                                          // row max, 1 / row sum, row dot
-  static_assert(QB * PP <= SMAX * PT, "ds must fit into the value tile");
+  static_assert(QB * PP <= 64 * NW * PT, "ds must fit into the value tile");
   uint16_t* dSs = Vs;
   const int qb = blockIdx.x, bh = blockIdx.y, r = blockIdx.z;
   const int b = bh / g.heads, h = bh - b * g.heads;
@@ -275,10 +289,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const attn_args g) 
 
   // The 64 queries and their output gradients are operands of every wavefront's two products and
   // of nothing else: each wavefront takes its fragments straight from global memory into
-  // registers, which leaves the LDS to the keys and values (two blocks per CU).
+  // registers, which leaves the LDS to the keys and values (two 4-wavefront blocks per CU).
   bf16x8 fq[2][4], fda[2][4];
   {
-    tile_loader<NCK> lk, lv;
+    tile_loader<NCK, 64 * NW> lk, lv;
     lk.fetch(base + g.d, ld, kmax, tid);
     lv.fetch(base + 2 * g.d, ld, kmax, tid);
     const uint16_t* qsrc = base + (int64_t)qb * QB * ld;
@@ -343,7 +357,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const attn_args g) 
   }
   __syncthreads();                       // also: every wavefront is done with the values
   if (tid < QB) {
-    const float dot = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+    float dot = red[0][tid];
+#pragma unroll
+    for (int x = 1; x < NW; ++x) dot += red[x][tid];
     stat[2][tid] = dot;
     g.row_dot[gr0 + tid] = dot;
   }
@@ -365,7 +381,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const attn_args g) 
     }
   }
   __syncthreads();
-  // dq = ds k: wavefront w owns the 32 x 32 block (w / 2, w % 2); keys are the contraction
+  // dq = ds k: wavefront w < 4 owns the 32 x 32 block (w / 2, w % 2); keys are the contraction
+  if (w >= 4) return;
   const int r0 = (w >> 1) * 32, c0 = (w & 1) * 32;
   f16v out = zero16();
   for (int ks = 0; ks < kmax; ks += 16) out = mfma(frag_k(dSs, PP, r0, ks, lane), frag_t(Ks, PT, c0, ks, lane), out);
@@ -480,14 +497,16 @@ bool hdet_attn_fusable(int seq_len, int d_model, int heads) {
 hipError_t hdet_launch_attn_fwd(const hdet_attn_desc& a, hipStream_t s) {
   if (!hdet_attn_fusable(a.seq_len, a.d_model, a.heads)) return hipErrorInvalidValue;
   const dim3 grid(a.seq_len / QB, a.batch * a.heads, a.n_replicas);
-  hipLaunchKernelGGL(attn_fwd_kernel, grid, dim3(256), 0, s, make_args(a));
+  if (a.seq_len <= 256) hipLaunchKernelGGL(attn_fwd_kernel<4>, grid, dim3(256), 0, s, make_args(a));
+  else hipLaunchKernelGGL(attn_fwd_kernel<8>, grid, dim3(512), 0, s, make_args(a));
   return hipGetLastError();
 }
 
 hipError_t hdet_launch_attn_bwd(const hdet_attn_desc& a, hipStream_t s) {
   if (!hdet_attn_fusable(a.seq_len, a.d_model, a.heads)) return hipErrorInvalidValue;
   const dim3 grid(a.seq_len / QB, a.batch * a.heads, a.n_replicas);
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, dim3(256), 0, s, make_args(a));
+  if (a.seq_len <= 256) hipLaunchKernelGGL(attn_bwd_dq_kernel<4>, grid, dim3(256), 0, s, make_args(a));
+  else hipLaunchKernelGGL(attn_bwd_dq_kernel<8>, grid, dim3(512), 0, s, make_args(a));
   hipLaunchKernelGGL(attn_bwd_dkv_kernel, grid, dim3(256), 0, s, make_args(a));
   return hipGetLastError();
 }

@@ -504,7 +504,7 @@ struct hdet_tf_plan {
   float *stf_mean, *stf_rstd, *scores, *logits, *row_loss;
   std::vector<float*> att_max, att_inv;      // [L] row statistics of the fused attention
   float* att_dot;
-  bool fused_attn;                           // bf16, head size 64, S a multiple of 64 up to 256
+  bool fused_attn;                           // bf16, head size 64, S a multiple of 64 up to 512
   float *part1, *part2;      // partial column sums [N][row chunks][cols]
   int nrc;                   // row chunks of the two-stage column sums
 };
