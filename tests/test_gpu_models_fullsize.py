@@ -1,0 +1,104 @@
+"""Parity of the mixed-precision forward/backward at the benchmark's full model sizes, in the launch
+configuration bench.py times (N = 8 replicas, bf16 GEMMs, fp32 master weights).  The oracle is run
+for sampled replicas only (its cost is per replica): the replicas are independent in
+forward/backward, so a replica checks the same kernels, tile shapes and batch strides as all
+eight do, and the first and the last one bound the replica indexing."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import hdet_inputs as I
+import paper_2604_24708_amd as H
+from harness import library_config, oracle_config
+from oracle import hdet_oracle as O
+from oracle import mlp_oracle as M
+from oracle import transformer_oracle as T
+
+pytestmark = pytest.mark.gpu
+
+
+def norm_err(a, b):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def base(**kw):
+    d = dict(n_replicas=8, total_steps=1000, sync_interval=16, warm_steps=300, lr_max=3e-4, alpha=0.1,
+             autolr_enabled=True, optimizer=O.ADAMW, weight_decay=0.01, grad_mode=O.GRAD_PER_REPLICA,
+             seed=I.SEED_PERM)
+    d.update(kw)
+    return d
+
+
+def test_mlp_1024_4096x3_1000_batch_256():
+    """The MLP workload: 1024-4096-4096-4096-1000, 256 rows per replica."""
+    widths, batch, n = [1024, 4096, 4096, 4096, 1000], 256, 8
+    P = I.mlp_param_count(widths)
+    assert P == 41_858_024
+    stride = (P + 3) // 4 * 4
+    dev = "cuda:0"
+    th0 = I.mlp_init(1, widths, I.SEED_INIT)[0]
+    theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
+    theta[:, :P] = torch.from_numpy(th0).to(dev)
+    m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.full_like(theta, 7.0)
+    shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
+    d = base()
+    cfg = library_config(d, widths=widths, batch=batch, model_kind=H.HDET_MLP, precision=H.HDET_BF16_GEMM_FP32_MASTER)
+    _, _, ws = H.hdet_workspace_bytes(cfg, stride)
+    wsb = torch.empty(ws, dtype=torch.uint8, device=dev)
+    h = H.hdet_create(cfg, theta, m, v, grads=g, params_bf16=shadow, workspace=wsb, plane_stride=stride)
+    x, y = I.mlp_batch(n, batch, widths[0], I.SEED_DATA, 1, widths, I.SEED_TEACHER)
+    out = H.hdet_forward_backward(h, torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev), want_losses=True)
+    for r in (0, 7):
+        loss, ref = M.mlp_loss_and_grad(th0, x[r], y[r], widths, bf16=True)
+        assert abs(out[r] - loss) <= 2e-3
+        g_dev = g[r, :P].cpu().numpy()
+        off = 0
+        for i in range(len(widths) - 1):
+            for size in (widths[i + 1] * widths[i], widths[i + 1]):
+                assert norm_err(g_dev[off:off + size], ref[off:off + size]) <= 2e-2, (r, i, size)
+                off += size
+    assert torch.all(g[:, P:] == 7.0)
+    H.hdet_destroy(h)
+
+
+def test_transformer_6l_d512_seq256_vocab32000():
+    """The transformer workload: 6 layers, d_model 512, 8 heads, FFN 2048, 16 sequences of 256
+    Zipf tokens per replica, vocabulary 32000 (fused attention, wide-row cross-entropy, every GEMM
+    tile shape).  Replica 0 against the oracle (one replica is about 1 TFLOP of fp64 work)."""
+    cfg = dict(n_blocks=6, d_model=512, n_heads=8, d_ff=2048, seq_len=256, vocab=32000)
+    n, B = 8, 16
+    P = I.transformer_param_count(cfg)
+    stride = (P + 3) // 4 * 4
+    dev = "cuda:0"
+    th0 = I.transformer_init(1, cfg, I.SEED_INIT)[0]
+    theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
+    theta[:, :P] = torch.from_numpy(th0).to(dev)
+    m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.full_like(theta, 7.0)
+    shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
+    d = base(total_steps=2000, sync_interval=32, warm_steps=600, lr_max=6e-4, alpha=0.15)
+    lc = library_config(d, model_kind=H.HDET_TRANSFORMER, batch=B, precision=H.HDET_BF16_GEMM_FP32_MASTER, **cfg)
+    _, _, ws = H.hdet_workspace_bytes(lc, stride)
+    wsb = torch.empty(ws, dtype=torch.uint8, device=dev)
+    h = H.hdet_create(lc, theta, m, v, grads=g, params_bf16=shadow, workspace=wsb, plane_stride=stride)
+    ids, tgt = I.zipf_tokens(n, B, cfg["seq_len"], cfg["vocab"], I.SEED_DATA, 0)
+    out = H.hdet_forward_backward(h, torch.from_numpy(ids).to(dev), torch.from_numpy(tgt).to(dev), want_losses=True)
+    losses = np.array([out[r] for r in range(n)])
+    assert np.all(np.isfinite(losses)) and np.all(np.abs(losses - np.log(cfg["vocab"])) < 1.0)
+    t0 = time.time()
+    loss, ref = T.loss_and_grad(th0, ids[0], tgt[0], cfg, bf16=True)
+    print(f"oracle: one replica in {time.time() - t0:.1f} s")
+    assert abs(losses[0] - loss) <= 1e-2
+    g_dev = g[0, :P].cpu().numpy()
+    off, bad = 0, {}
+    for name, shape in I.transformer_shapes(cfg):
+        k = int(np.prod(shape))
+        e = norm_err(g_dev[off:off + k], ref[off:off + k])
+        if e > 4e-2:
+            bad[name] = e
+        off += k
+    assert not bad, bad
+    assert torch.all(g[:, P:] == 7.0) if stride > P else True
+    H.hdet_destroy(h)
