@@ -85,7 +85,7 @@ def mlp_workload(args):
     n, B, T = 8, 256, 16
     widths = [1024, 4096, 4096, 4096, 1000]
     P = I.mlp_param_count(widths)
-    stride = (P + 3) // 4 * 4
+    stride = (P + 63) // 64 * 64          # planes start on 256-byte boundaries
     total = max(1000, args.warmup + args.steps)
     theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
     theta[:, :P] = torch.from_numpy(I.mlp_init(1, widths, I.SEED_INIT)).to(dev)
@@ -165,7 +165,7 @@ def transformer_workload(args):
         lr_max = 3e-4
         extra = [(H.HDET_CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (H.HDET_CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
     P = I.transformer_param_count(cfg)
-    stride = (P + 3) // 4 * 4
+    stride = (P + 63) // 64 * 64          # planes start on 256-byte boundaries
     total = max(2000, args.warmup + args.steps)
     theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
     theta[:, :P] = torch.from_numpy(I.transformer_init(1, cfg, I.SEED_INIT)).to(dev)
@@ -308,7 +308,7 @@ def main():
         print(json.dumps(transformer_workload(args)))
         return
     n, P, T = args.replicas, int(args.params), args.sync_interval
-    stride = (P + 3) // 4 * 4
+    stride = (P + 63) // 64 * 64          # planes start on 256-byte boundaries
     total = args.warmup + args.steps
 
     if args.shared_state and args.grad_mode != "shared":
