@@ -86,6 +86,8 @@ struct lds_tile {
   static constexpr int NI = ROWS * TK * 2 / (THREADS * 16);   // load instructions per thread and stage
   static constexpr int RCH = ROWS / 8;                        // chunks per k-row of a [k][ROWS] tile
   static constexpr int CPR = TK / 8;                          // chunks per row of a [row][TK] tile
+  static_assert(KMAJOR || ROWS >= 128, "the chunk permutation of a [k][ROWS] tile needs at least 16 chunks per k-row");
+  static_assert(TK == 32 || TK == 64, "K step");
   // chunk permutation inside a [row][TK] row: 64-byte rows by row / 4, 128-byte rows by row / 2
   static __device__ __forceinline__ int swz(int r) { return TK == 32 ? (r >> 2) & 3 : (r >> 1) & 7; }
   uint32_t off[NI];     // byte offset of this lane's chunk at K step 0, or kAbsent
