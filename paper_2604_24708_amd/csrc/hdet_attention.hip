@@ -1,8 +1,8 @@
 // Causal self-attention of the transformer replicas in mixed precision, forward and backward,
 // with the scores kept on chip ("Forward + backward" of Algorithm 1 for the attention part of a
-// block).  For head size 64 and sequence lengths that are multiples of 64 up to 512 this
-// replaces five batched GEMMs, two softmax kernels and the [S][S] score and probability tensors
-// in HBM by three kernels that read q, k, v (and the output gradient) once per 64-row block.
+// block).  For head size 64 and sequence lengths that are multiples of 64 this replaces five
+// batched GEMMs, two softmax kernels and the [S][S] score and probability tensors in HBM by
+// three kernels that stream 64-row tiles of k, v (or q and the output gradient) through LDS.
 //
 // Arithmetic follows the unfused path operation by operation, so both agree to the rounding
 // of the bf16 tensors they share:
@@ -10,37 +10,55 @@
 //   backward  dp = da v^T, dot = sum_j dp_j p_j, ds = bf16(p (dp - dot) scale),
 //             dq = bf16(ds k), dk = bf16(ds^T q), dv = bf16(p^T da)
 // with scale = 1 / (sqrt(d_head) tau_r), tau_r the replica's attention temperature when that is
-// an explored channel (Remark 1).  The row maximum and 1/sum of the forward are kept ([rows]
-// fp32 each) so that the backward rebuilds p without a reduction.
+// an explored channel (Remark 1).  Because p is rounded after the normalisation, every kernel
+// that needs a row-wide quantity first (max and sum in the forward, dot in the backward) walks
+// its tiles twice: once for the quantity, once for the product.  The exponential is the
+// hardware's exp2 of (s * scale * log2 e - max); the row maximum (in that scaled form) and
+// 1/sum of the forward are kept ([rows] fp32 each) and the backward rebuilds p from them with
+// the same expression, hence bit for bit.
 //
 // Layout: qkv [N][B][S][3d] bf16 (q | k | v, head h in columns h*64..), a and da [N][B][S][d],
-// dqkv like qkv.  A block is 4 wavefronts; tiles are v_mfma_f32_32x32x16_bf16 blocks fed from
-// LDS tiles of pitch 72 (or S + 8) elements, which keeps the 128-bit fragment reads free of bank
-// conflicts; operands that are contracted along their row index are read with the transposing
-// LDS load, so nothing is transposed in memory.
-//   forward  : block = (64 queries, sequence, head, replica); wavefront w owns key block w
-//              (4 wavefronts for S <= 256, 8 beyond)
-//   backward : 1. same mapping: rebuilds p, forms dp, the row dots (kept for step 2), ds and dq
-//                 (q and da fragments go from global memory straight to registers)
-//              2. block = (64 keys, sequence, head, replica), loop over the query blocks at or
-//                 below the diagonal: dk, dv accumulate in registers in ascending query order
+// dqkv like qkv.  A block is 4 wavefronts; a wavefront owns 32 rows (queries in the forward and
+// in the dq kernel, keys in the dk/dv kernel) whose operand fragments it loads once from global
+// memory into registers, and walks the 64-row tiles of the other side, which the block stages
+// in LDS (pitch 72 elements: the 128-bit fragment reads are free of bank conflicts) one tile
+// ahead, with one barrier per tile.  Tiles are v_mfma_f32_32x32x16_bf16 blocks.  The first
+// product is formed with the wavefront's own rows as the accumulator's COLUMNS, so that a lane
+// holds one of its rows and 16 entries of the other side per block: row reductions stay inside
+// a lane (plus one exchange between the half-wavefronts at the very end), and the accumulator
+// registers, rounded to bf16, are directly the second product's B operand (contraction index =
+// accumulator row) -- probabilities and ds never pass through LDS.  The accumulator keeps the
+// rows of a 16-row step in the order (0..3, 8..11 | 4..7, 12..15) over the two half-wavefronts;
+// the A operand of the second product is read from its LDS tile in that same order with the
+// transposing LDS load, so nothing is transposed or permuted in memory.
 // Every sum has a fixed order: results do not depend on scheduling.
 
 #include "hdet_internal.h"
 #include "hdet_elem.h"
 
+// the forward and the two backward kernels must evaluate s * c - max identically: no contraction into an fma
+#pragma clang fp contract(off)
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f4 __attribute__((ext_vector_type(4)));
 typedef short s4 __attribute__((ext_vector_type(4)));
 typedef short s8 __attribute__((ext_vector_type(8)));
 typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+typedef unsigned short us4 __attribute__((ext_vector_type(4)));
 
 constexpr int DH = 64;            // head size
-constexpr int QB = 64;            // rows per block
+constexpr int TB = 64;            // rows of a streamed LDS tile
 constexpr int PT = DH + 8;        // pitch of a [rows][64] tile
-constexpr int SMAX = 512;         // longest sequence: one key block of 64 per wavefront, at most 8 wavefronts
+constexpr int WR = 32;            // rows a wavefront owns
+constexpr int NWV = 4;            // wavefronts per block
+constexpr int RB = WR * NWV;      // rows a block owns
+constexpr int THREADS = 64 * NWV;
+constexpr int TILE = TB * PT;     // elements of one LDS tile
+constexpr int SMAX = 16384;       // longest sequence accepted
+constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ unsigned short f2bf(float x) { return __builtin_bit_cast(unsigned short, (__bf16)x); }
 __device__ __forceinline__ float bf2f(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
@@ -51,16 +69,22 @@ __device__ __forceinline__ float bf16_round(float x) { return bf2f(f2bf(x)); }
 __device__ __forceinline__ bf16x8 frag_k(const uint16_t* t, int pitch, int r0, int ks, int lane) {
   return *reinterpret_cast<const bf16x8*>(t + (r0 + (lane & 31)) * pitch + ks + ((lane >> 5) << 3));
 }
-// The same fragment from a tile stored [k][row] (contracted along the tile's row index): within a
-// 16-lane group, lane p points at the 4 elements (k = kb + p / 4, rows rb + 4 * (p % 4) .. + 3) and lane i
-// receives (k = kb .. kb + 3, row rb + i) from the transposing read.
-__device__ __forceinline__ bf16x8 frag_t(const uint16_t* t, int pitch, int r0, int ks, int lane) {
+// The same kind of fragment from global memory (row pitch ld elements)
+__device__ __forceinline__ bf16x8 frag_g(const uint16_t* src, int64_t ld, int ks, int lane) {
+  return *reinterpret_cast<const bf16x8*>(src + (int64_t)(lane & 31) * ld + ks + ((lane >> 5) << 3));
+}
+// Fragment of an operand that is contracted along its tile's ROW index (tile stored [k][row]),
+// with the 16 k of the step in accumulator order: half-wavefront h holds k = ks + 4h + 0..3 and
+// ks + 8 + 4h + 0..3.  Within a 16-lane group, lane p points at the 4 elements
+// (k = kb + p / 4, rows rb + 4 * (p % 4) .. + 3) and lane i receives (k = kb .. kb + 3, row rb + i)
+// from the transposing read.
+__device__ __forceinline__ bf16x8 frag_tp(const uint16_t* t, int pitch, int r0, int ks, int lane) {
   const int p = lane & 15;
   const int row = r0 + (((lane >> 4) & 1) << 4) + ((p & 3) << 2);
-  const int k = ks + ((lane >> 5) << 3) + (p >> 2);
+  const int k = ks + ((lane >> 5) << 2) + (p >> 2);
   const uint16_t* q = t + k * pitch + row;
   const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)(q));
-  const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)(q + 4 * pitch));
+  const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)(q + 8 * pitch));
   const s8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   return __builtin_bit_cast(bf16x8, both);
 }
@@ -73,30 +97,39 @@ __device__ __forceinline__ f16v zero16() {
 }
 // accumulator element e of lane l sits at (row = (e / 4) * 8 + (l / 32) * 4 + e % 4, col = l % 32) of its 32x32 block
 __device__ __forceinline__ int acc_row(int e, int lane) { return ((e >> 2) << 3) + ((lane >> 5) << 2) + (e & 3); }
-
-// rows x 64 bf16 from global (row pitch `ld` elements) into an LDS tile of pitch PT by THREADS threads,
-// in two phases so that all loads of a block are in flight together: fetch() issues up to NC
-// 16-byte loads per thread, commit() writes them to LDS.
-template <int NC, int THREADS = 256>
-struct tile_loader {
-  us8 v[NC];
-  __device__ __forceinline__ void fetch(const uint16_t* src, int64_t ld, int rows, int tid) {
+// elements 8 j .. 8 j + 7 of an accumulator block as the B fragment of contraction step j
+__device__ __forceinline__ bf16x8 acc_frag(const float (&x)[16], int j) {
+  bf16x8 f;
 #pragma unroll
-    for (int i = 0; i < NC; ++i) {
+  for (int t = 0; t < 8; ++t) f[t] = (__bf16)x[8 * j + t];
+  return f;
+}
+__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+// The probability as the unfused path stores it (bf16), from the raw score s, c = scale log2 e,
+// the row's maximum of s c and 1 / (row sum)
+__device__ __forceinline__ float prob(float s, float c, float mx, float inv) { return bf16_round(exp2_fast(s * c - mx) * inv); }
+
+// One 64 x 64 bf16 tile from global memory (row pitch ld) to LDS (pitch PT) by the block's 256
+// threads, in two phases so that the loads are in flight while the previous tile is worked on.
+struct tile64 {
+  us8 v[2];
+  __device__ __forceinline__ void fetch(const uint16_t* src, int64_t ld, int tid) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
       const int c = tid + i * THREADS;
-      if (c < rows * 8) v[i] = *reinterpret_cast<const us8*>(src + (int64_t)(c >> 3) * ld + ((c & 7) << 3));
+      v[i] = *reinterpret_cast<const us8*>(src + (int64_t)(c >> 3) * ld + ((c & 7) << 3));
     }
   }
-  __device__ __forceinline__ void commit(uint16_t* dst, int rows, int tid) const {
+  __device__ __forceinline__ void commit(uint16_t* dst, int tid) const {
 #pragma unroll
-    for (int i = 0; i < NC; ++i) {
+    for (int i = 0; i < 2; ++i) {
       const int c = tid + i * THREADS;
-      if (c < rows * 8) *reinterpret_cast<us8*>(dst + (c >> 3) * PT + ((c & 7) << 3)) = v[i];
+      *reinterpret_cast<us8*>(dst + (c >> 3) * PT + ((c & 7) << 3)) = v[i];
     }
   }
 };
-constexpr int NCQ = QB * 8 / 256;        // chunks per thread of a 64-row tile (256 threads)
-constexpr int NCK = 8;                   // ... of all keys / values of a sequence (64 rows per wavefront)
+
 struct attn_args {
   const uint16_t* qkv;      // [N][B][S][3d]
   uint16_t* a;              // forward: [N][B][S][d] output
@@ -115,368 +148,338 @@ __device__ __forceinline__ float replica_scale(const attn_args& g, int r) {
   return g.temp_channel >= 0 ? g.scale / (float)hdet_channel_value(g.ctrl, g.temp_channel, r, 0.0) : g.scale;
 }
 
-// 64 x 64 scores of (query block in A, key block in B): 2 x 2 accumulator blocks, contraction 64
-__device__ __forceinline__ void qk_tile(f16v (&acc)[2][2], const uint16_t* rows_a, const uint16_t* rows_b, int lane) {
+// The wavefront's [32 rows][64] result, held transposed in two accumulator blocks (block dt:
+// columns 32 dt .., lane = row), goes to `dst` (row pitch ld) through the wavefront's LDS strip
+// so that every global store writes 16 bytes of a row.
+__device__ __forceinline__ void store_rows(const f16v (&o)[2], uint16_t* stg, uint16_t* dst, int64_t ld, bool on, int lane) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
-#pragma unroll
-  for (int ks = 0; ks < DH; ks += 16) {
-    bf16x8 fa[2], fb[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) fa[i] = frag_k(rows_a, PT, i * 32, ks, lane);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) fb[j] = frag_k(rows_b, PT, j * 32, ks, lane);
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fa[i], fb[j], acc[i][j]);
-  }
-}
-
-// Score tiles are formed transposed, keys x queries: a lane then holds ONE query (column l % 32 of
-// the accumulator block) and 16 keys of it per block, in runs of 4 consecutive keys.  Row
-// statistics of a query are in-lane reductions plus one exchange between the two half-wavefronts,
-// and the probabilities go to LDS 4 keys (8 bytes) at a time.
-// local key index of accumulator element e in key block i: i * 32 + acc_row(e, lane); query: j * 32 + lane % 32
-typedef unsigned short us4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
-// exp on the hardware exp2 (relative error about 1e-7); forward and backward use the same one, so
-// the backward rebuilds exactly the probabilities of the forward
-__device__ __forceinline__ float exp_fast(float x) { return __expf(x); }
-
-// ---------------------------------------------------------------------------------------------
-// forward
-// ---------------------------------------------------------------------------------------------
-// NW wavefronts: sequences of up to 64 NW keys (4: two blocks per CU; 8: one)
-template <int NW>
-__global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const attn_args g) {
-  constexpr int PP = 64 * NW + 8;                                        // pitch of the [64][S] tile
-  __shared__ __attribute__((aligned(16))) uint16_t Qs[QB * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t KVs[64 * NW * PT];   // keys, then values
-  __shared__ __attribute__((aligned(16))) uint16_t Ps[QB * PP];
-  __shared__ float red[NW][QB];
-  __shared__ float stat[2][QB];                                          // row max, 1 / row sum
-  const int qb = blockIdx.x, bh = blockIdx.y, r = blockIdx.z;
-  const int b = bh / g.heads, h = bh - b * g.heads;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int kmax = (qb + 1) * QB;
-  const int64_t ld = 3 * (int64_t)g.d;
-  const uint16_t* base = g.qkv + (((int64_t)r * g.B + b) * g.S) * ld + h * DH;
-  const float scale = replica_scale(g, r);
-
-  tile_loader<QB * 8 / (64 * NW), 64 * NW> lq;
-  tile_loader<NCK, 64 * NW> lk, lv;
-  lq.fetch(base + (int64_t)qb * QB * ld, ld, QB, tid);
-  lk.fetch(base + g.d, ld, kmax, tid);
-  lv.fetch(base + 2 * g.d, ld, kmax, tid);          // consumed after the softmax
-  lq.commit(Qs, QB, tid);
-  lk.commit(KVs, kmax, tid);
-  __syncthreads();
-
-  // wavefront w: scores of key block w (if it is at or below the diagonal), [key][query]
-  const bool active = w <= qb;
-  f16v sc[2][2];
-  if (active) qk_tile(sc, KVs + w * QB * PT, Qs, lane);
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int q = j * 32 + (lane & 31);
-    float m = -INFINITY;
-    if (active) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int key = i * 32 + acc_row(e, lane);
-          const bool keep = w < qb || key <= q;                          // causal: key <= query
-          sc[i][j][e] = keep ? sc[i][j][e] * scale : -INFINITY;
-          m = fmaxf(m, sc[i][j][e]);
-        }
-    }
-    m = fmaxf(m, other_half(m));
-    if (lane < 32) red[w][q] = m;
-  }
-  __syncthreads();
-  if (tid < QB) {
-    float m = red[0][tid];
-#pragma unroll
-    for (int x = 1; x < NW; ++x) m = fmaxf(m, red[x][tid]);
-    stat[0][tid] = m;
-  }
-  __syncthreads();
-  // exponentials and row sums
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int q = j * 32 + (lane & 31);
-    const float mx = stat[0][q];
-    float sum = 0.f;
-    if (active) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { sc[i][j][e] = exp_fast(sc[i][j][e] - mx); sum += sc[i][j][e]; }
-    }
-    sum += other_half(sum);
-    if (lane < 32) red[w][q] = sum;
-  }
-  __syncthreads();
-  if (tid < QB) {
-    float sum = red[0][tid];
-#pragma unroll
-    for (int x = 1; x < NW; ++x) sum += red[x][tid];
-    const float inv = 1.f / sum;
-    stat[1][tid] = inv;
-    const int64_t gr = (((int64_t)r * g.B + b) * g.heads + h) * g.S + qb * QB + tid;
-    g.row_max[gr] = stat[0][tid];
-    g.row_inv[gr] = inv;
-  }
-  __syncthreads();
-  // probabilities as the second product reads them: bf16 [query][key]
-  if (active) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int q = j * 32 + (lane & 31);
-      const float inv = stat[1][q];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const us4 o = {f2bf(sc[i][j][4 * e4] * inv), f2bf(sc[i][j][4 * e4 + 1] * inv), f2bf(sc[i][j][4 * e4 + 2] * inv),
-                         f2bf(sc[i][j][4 * e4 + 3] * inv)};
-          *reinterpret_cast<us4*>(Ps + q * PP + w * QB + i * 32 + acc_row(4 * e4, lane)) = o;
-        }
-    }
-  }
-  __syncthreads();                       // all reads of the keys are done as well
-  lv.commit(KVs, kmax, tid);
-  __syncthreads();
-  // a = p v: wavefront w < 4 owns the 32 x 32 block (w / 2, w % 2) of the 64 x 64 output
-  if (w >= 4) return;
-  const int r0 = (w >> 1) * 32, c0 = (w & 1) * 32;
-  f16v out = zero16();
-  for (int ks = 0; ks < kmax; ks += 16) out = mfma(frag_k(Ps, PP, r0, ks, lane), frag_t(KVs, PT, c0, ks, lane), out);
-  uint16_t* dst = g.a + (((int64_t)r * g.B + b) * g.S + qb * QB) * g.d + h * DH;
-#pragma unroll
-  for (int e = 0; e < 16; ++e) dst[(int64_t)(r0 + acc_row(e, lane)) * g.d + c0 + (lane & 31)] = f2bf(out[e]);
-}
-
-// The probability as the unfused path stores it (bf16), rebuilt from the scaled score and the
-// row statistics of the forward.
-__device__ __forceinline__ float prob(float s, float mx, float inv) { return bf16_round(exp_fast(s - mx) * inv); }
-
-// ---------------------------------------------------------------------------------------------
-// backward, step 1: dq and the row dots
-// ---------------------------------------------------------------------------------------------
-template <int NW>
-__global__ __launch_bounds__(64 * NW, 2) void attn_bwd_dq_kernel(const attn_args g) {
-  constexpr int PP = 64 * NW + 8;
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * NW * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * NW * PT];    // values, then ds [query][key] with pitch PP
-  __shared__ float red[NW][QB];
-  __shared__ float stat[3][QB];                                          // row max, 1 / row sum, row dot
-  static_assert(QB * PP <= 64 * NW * PT, "ds must fit into the value tile");
-  uint16_t* dSs = Vs;
-  const int qb = blockIdx.x, bh = blockIdx.y, r = blockIdx.z;
-  const int b = bh / g.heads, h = bh - b * g.heads;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int kmax = (qb + 1) * QB;
-  const int64_t ld = 3 * (int64_t)g.d;
-  const int64_t tok0 = ((int64_t)r * g.B + b) * g.S;
-  const uint16_t* base = g.qkv + tok0 * ld + h * DH;
-  const int64_t gr0 = (((int64_t)r * g.B + b) * g.heads + h) * g.S + qb * QB;
-  const float scale = replica_scale(g, r);
-
-  // The 64 queries and their output gradients are operands of every wavefront's two products and
-  // of nothing else: each wavefront takes its fragments straight from global memory into
-  // registers, which leaves the LDS to the keys and values (two 4-wavefront blocks per CU).
-  bf16x8 fq[2][4], fda[2][4];
-  {
-    tile_loader<NCK, 64 * NW> lk, lv;
-    lk.fetch(base + g.d, ld, kmax, tid);
-    lv.fetch(base + 2 * g.d, ld, kmax, tid);
-    const uint16_t* qsrc = base + (int64_t)qb * QB * ld;
-    const uint16_t* dasrc = g.da + (tok0 + qb * QB) * g.d + h * DH;
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int k4 = 0; k4 < 4; ++k4) {
-        const int row = j * 32 + (lane & 31), col = k4 * 16 + ((lane >> 5) << 3);
-        fq[j][k4] = *reinterpret_cast<const bf16x8*>(qsrc + (int64_t)row * ld + col);
-        fda[j][k4] = *reinterpret_cast<const bf16x8*>(dasrc + (int64_t)row * g.d + col);
-      }
-    if (tid < QB) { stat[0][tid] = g.row_max[gr0 + tid]; stat[1][tid] = g.row_inv[gr0 + tid]; }
-    lk.commit(Ks, kmax, tid);
-    lv.commit(Vs, kmax, tid);
-  }
-  __syncthreads();
-
-  // p and dp = da v^T of key block w, both [key][query]
-  const bool active = w <= qb;
-  f16v p[2][2], dp[2][2];
-  if (active) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) { p[i][j] = zero16(); dp[i][j] = zero16(); }
-#pragma unroll
-    for (int k4 = 0; k4 < 4; ++k4) {
-      bf16x8 fk[2], fv[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fk[i] = frag_k(Ks + w * QB * PT, PT, i * 32, k4 * 16, lane);
-        fv[i] = frag_k(Vs + w * QB * PT, PT, i * 32, k4 * 16, lane);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          p[i][j] = mfma(fk[i], fq[j][k4], p[i][j]);
-          dp[i][j] = mfma(fv[i], fda[j][k4], dp[i][j]);
-        }
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int q = j * 32 + (lane & 31);
-    const float mx = stat[0][q], inv = stat[1][q];
-    float sum = 0.f;
-    if (active) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int key = i * 32 + acc_row(e, lane);
-          const bool keep = w < qb || key <= q;
-          p[i][j][e] = keep ? prob(p[i][j][e] * scale, mx, inv) : 0.f;
-          sum += dp[i][j][e] * p[i][j][e];
-        }
-    }
-    sum += other_half(sum);
-    if (lane < 32) red[w][q] = sum;
-  }
-  __syncthreads();                       // also: every wavefront is done with the values
-  if (tid < QB) {
-    float dot = red[0][tid];
-#pragma unroll
-    for (int x = 1; x < NW; ++x) dot += red[x][tid];
-    stat[2][tid] = dot;
-    g.row_dot[gr0 + tid] = dot;
-  }
-  __syncthreads();
-  if (active) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int q = j * 32 + (lane & 31);
-      const float dot = stat[2][q];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          us4 o;
-#pragma unroll
-          for (int u = 0; u < 4; ++u) o[u] = f2bf(p[i][j][4 * e4 + u] * (dp[i][j][4 * e4 + u] - dot) * scale);
-          *reinterpret_cast<us4*>(dSs + q * PP + w * QB + i * 32 + acc_row(4 * e4, lane)) = o;
-        }
-    }
-  }
-  __syncthreads();
-  // dq = ds k: wavefront w < 4 owns the 32 x 32 block (w / 2, w % 2); keys are the contraction
-  if (w >= 4) return;
-  const int r0 = (w >> 1) * 32, c0 = (w & 1) * 32;
-  f16v out = zero16();
-  for (int ks = 0; ks < kmax; ks += 16) out = mfma(frag_k(dSs, PP, r0, ks, lane), frag_t(Ks, PT, c0, ks, lane), out);
-  uint16_t* dst = g.dqkv + (tok0 + qb * QB) * ld + h * DH;
-#pragma unroll
-  for (int e = 0; e < 16; ++e) dst[(int64_t)(r0 + acc_row(e, lane)) * ld + c0 + (lane & 31)] = f2bf(out[e]);
-}
-
-// ---------------------------------------------------------------------------------------------
-// backward, step 2: dk and dv of one key block
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const attn_args g) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[QB * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[QB * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t Qs[QB * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t dAs[QB * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t Ps[QB * PT];          // [query][key]
-  __shared__ __attribute__((aligned(16))) uint16_t dSs[QB * PT];
-  __shared__ float stat[3][QB];
-  const int kb = blockIdx.x, bh = blockIdx.y, r = blockIdx.z;
-  const int b = bh / g.heads, h = bh - b * g.heads;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int nqb = g.S / QB;
-  const int64_t ld = 3 * (int64_t)g.d;
-  const int64_t tok0 = ((int64_t)r * g.B + b) * g.S;
-  const uint16_t* base = g.qkv + tok0 * ld + h * DH;
-  const int64_t gr0 = (((int64_t)r * g.B + b) * g.heads + h) * g.S;
-  const float scale = replica_scale(g, r);
-
-  tile_loader<NCQ> lq, la;
-  {
-    tile_loader<NCQ> lk, lv;
-    lk.fetch(base + g.d + (int64_t)kb * QB * ld, ld, QB, tid);
-    lv.fetch(base + 2 * g.d + (int64_t)kb * QB * ld, ld, QB, tid);
-    lq.fetch(base + (int64_t)kb * QB * ld, ld, QB, tid);
-    la.fetch(g.da + (tok0 + kb * QB) * g.d + h * DH, g.d, QB, tid);
-    lk.commit(Ks, QB, tid);
-    lv.commit(Vs, QB, tid);
-  }
-  // the wavefront's 32 x 32 block of every 64 x 64 tile: keys k0.. x queries q0.. of p and ds,
-  // keys k0.. x columns q0.. of dk and dv
-  const int k0 = (w >> 1) * 32, q0 = (w & 1) * 32;
-  f16v dk = zero16(), dv = zero16();
-  for (int qb = kb; qb < nqb; ++qb) {
-    __syncthreads();                                     // the previous round's tiles are no longer read
-    lq.commit(Qs, QB, tid);                              // fetched one round ahead
-    la.commit(dAs, QB, tid);
-    if (tid < QB) {
-      stat[0][tid] = g.row_max[gr0 + qb * QB + tid];
-      stat[1][tid] = g.row_inv[gr0 + qb * QB + tid];
-      stat[2][tid] = g.row_dot[gr0 + qb * QB + tid];
-    }
-    if (qb + 1 < nqb) {
-      lq.fetch(base + (int64_t)(qb + 1) * QB * ld, ld, QB, tid);
-      la.fetch(g.da + (tok0 + (qb + 1) * QB) * g.d + h * DH, g.d, QB, tid);
-    }
-    __syncthreads();
-    f16v s = zero16(), dp = zero16();                    // [key][query]
-#pragma unroll
-    for (int ks = 0; ks < DH; ks += 16) {
-      s = mfma(frag_k(Ks, PT, k0, ks, lane), frag_k(Qs, PT, q0, ks, lane), s);
-      dp = mfma(frag_k(Vs, PT, k0, ks, lane), frag_k(dAs, PT, q0, ks, lane), dp);
-    }
-    const int q = q0 + (lane & 31);
-    const float mx = stat[0][q], inv = stat[1][q], dot = stat[2][q];
+  for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int e4 = 0; e4 < 4; ++e4) {
-      us4 po, so;
+      const us4 x = {f2bf(o[dt][4 * e4]), f2bf(o[dt][4 * e4 + 1]), f2bf(o[dt][4 * e4 + 2]), f2bf(o[dt][4 * e4 + 3])};
+      *reinterpret_cast<us4*>(stg + (lane & 31) * PT + dt * 32 + acc_row(4 * e4, lane)) = x;
+    }
+  __syncthreads();
+  if (on) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int key = k0 + acc_row(4 * e4 + u, lane);
-        const bool keep = kb < qb || key <= q;
-        const float pv = keep ? prob(s[4 * e4 + u] * scale, mx, inv) : 0.f;
-        po[u] = f2bf(pv);
-        so[u] = f2bf(pv * (dp[4 * e4 + u] - dot) * scale);
+    for (int i = 0; i < 4; ++i) {
+      const int c = lane + 64 * i, row = c >> 3, col = (c & 7) << 3;
+      *reinterpret_cast<us8*>(dst + (int64_t)row * ld + col) = *reinterpret_cast<const us8*>(stg + row * PT + col);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward: block = 128 queries of one (replica, sequence, head)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g) {
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];        // keys x 2, values x 2
+  const int qblk = gridDim.x - 1 - blockIdx.x;                             // longest blocks first
+  const int bh = blockIdx.y, r = blockIdx.z;
+  const int b = bh / g.heads, h = bh - b * g.heads;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, qi = lane & 31;
+  const int64_t ld = 3 * (int64_t)g.d;
+  const int64_t tok0 = ((int64_t)r * g.B + b) * g.S;
+  const uint16_t* base = g.qkv + tok0 * ld + h * DH;
+  const uint16_t* ksrc = base + g.d;
+  const uint16_t* vsrc = base + 2 * g.d;
+  const int q0 = qblk * RB, wq0 = q0 + w * WR;
+  const bool on = wq0 < g.S;                                               // S is a multiple of 64, not of 128
+  const int nkb = (q0 + RB < g.S ? q0 + RB : g.S) / TB;                    // key tiles the block walks
+  const int nkw = on ? (wq0 + WR - 1) / TB + 1 : 0;                        // ... and this wavefront
+  const float c = replica_scale(g, r) * kLog2e;
+
+  bf16x8 fq[4];
+#pragma unroll
+  for (int k4 = 0; k4 < 4; ++k4) fq[k4] = frag_g(base + (int64_t)(on ? wq0 : 0) * ld, ld, k4 * 16, lane);
+
+  // scores of key block i of tile kb, [key][query], as exponents: s c, or -inf above the diagonal.
+  // false when the whole block lies above the diagonal.
+  auto scores = [&](const uint16_t* kt, int kb, int i, float (&t)[16]) -> bool {
+    const int key0 = kb * TB + 32 * i;
+    if (key0 > wq0 + WR - 1) return false;
+    f16v s = zero16();
+#pragma unroll
+    for (int k4 = 0; k4 < 4; ++k4) s = mfma(frag_k(kt, PT, 32 * i, k4 * 16, lane), fq[k4], s);
+    const bool diag = key0 + 31 > wq0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) t[e] = (diag && key0 + acc_row(e, lane) > wq0 + qi) ? -INFINITY : s[e] * c;
+    return true;
+  };
+
+  // pass 1: row maximum and sum, each half-wavefront over its own keys
+  tile64 lk, lv;
+  float m = -1e30f, l = 0.f;
+  lk.fetch(ksrc, ld, tid);
+  lk.commit(smem, tid);
+  if (nkb > 1) lk.fetch(ksrc + (int64_t)TB * ld, ld, tid);
+  __syncthreads();
+  for (int kb = 0; kb < nkb; ++kb) {
+    if (kb + 1 < nkb) lk.commit(smem + ((kb + 1) & 1) * TILE, tid);
+    if (kb + 2 < nkb) lk.fetch(ksrc + (int64_t)(kb + 2) * TB * ld, ld, tid);
+    if (kb < nkw) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        float t[16];
+        if (!scores(smem + (kb & 1) * TILE, kb, i, t)) continue;
+        float mx = m;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, t[e]);
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sum += exp2_fast(t[e] - mx);
+        l = l * exp2_fast(m - mx) + sum;
+        m = mx;
       }
-      *reinterpret_cast<us4*>(Ps + q * PT + k0 + acc_row(4 * e4, lane)) = po;
-      *reinterpret_cast<us4*>(dSs + q * PT + k0 + acc_row(4 * e4, lane)) = so;
     }
     __syncthreads();
-    // dv += p^T da, dk += ds^T q: block (keys k0.., columns q0..), queries are the contraction
+  }
+  const float mo = other_half(m), lo = other_half(l);
+  const float mx = fmaxf(m, mo);
+  const float inv = 1.f / (l * exp2_fast(m - mx) + lo * exp2_fast(mo - mx));
+  if (on && lane < 32) {
+    const int64_t gr = (((int64_t)r * g.B + b) * g.heads + h) * g.S + wq0 + qi;
+    g.row_max[gr] = mx;
+    g.row_inv[gr] = inv;
+  }
+
+  // pass 2: a^T = v^T p^T, [column][query]
+  f16v o[2] = {zero16(), zero16()};
+  lk.fetch(ksrc, ld, tid);
+  lv.fetch(vsrc, ld, tid);
+  lk.commit(smem, tid);
+  lv.commit(smem + 2 * TILE, tid);
+  if (nkb > 1) { lk.fetch(ksrc + (int64_t)TB * ld, ld, tid); lv.fetch(vsrc + (int64_t)TB * ld, ld, tid); }
+  __syncthreads();
+  for (int kb = 0; kb < nkb; ++kb) {
+    if (kb + 1 < nkb) { lk.commit(smem + ((kb + 1) & 1) * TILE, tid); lv.commit(smem + (2 + ((kb + 1) & 1)) * TILE, tid); }
+    if (kb + 2 < nkb) { lk.fetch(ksrc + (int64_t)(kb + 2) * TB * ld, ld, tid); lv.fetch(vsrc + (int64_t)(kb + 2) * TB * ld, ld, tid); }
+    if (kb < nkw) {
+      const uint16_t* vt = smem + (2 + (kb & 1)) * TILE;
 #pragma unroll
-    for (int ks = 0; ks < QB; ks += 16) {
-      dv = mfma(frag_t(Ps, PT, k0, ks, lane), frag_t(dAs, PT, q0, ks, lane), dv);
-      dk = mfma(frag_t(dSs, PT, k0, ks, lane), frag_t(Qs, PT, q0, ks, lane), dk);
+      for (int i = 0; i < 2; ++i) {
+        float t[16];
+        if (!scores(smem + (kb & 1) * TILE, kb, i, t)) continue;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) t[e] = exp2_fast(t[e] - mx) * inv;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const bf16x8 pf = acc_frag(t, j);
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) o[dt] = mfma(frag_tp(vt, PT, 32 * dt, 32 * i + 16 * j, lane), pf, o[dt]);
+        }
+      }
     }
+    __syncthreads();
   }
-  uint16_t* dst = g.dqkv + (tok0 + kb * QB) * ld + h * DH;
+  store_rows(o, smem + w * WR * PT, g.a + (tok0 + (on ? wq0 : 0)) * g.d + h * DH, g.d, on, lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward, step 1: the row dots and dq; block = 128 queries
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(THREADS, 2) void attn_bwd_dq_kernel(const attn_args g) {
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];        // keys x 2, values x 2
+  const int qblk = gridDim.x - 1 - blockIdx.x;
+  const int bh = blockIdx.y, r = blockIdx.z;
+  const int b = bh / g.heads, h = bh - b * g.heads;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, qi = lane & 31;
+  const int64_t ld = 3 * (int64_t)g.d;
+  const int64_t tok0 = ((int64_t)r * g.B + b) * g.S;
+  const uint16_t* base = g.qkv + tok0 * ld + h * DH;
+  const uint16_t* ksrc = base + g.d;
+  const uint16_t* vsrc = base + 2 * g.d;
+  const int q0 = qblk * RB, wq0 = q0 + w * WR;
+  const bool on = wq0 < g.S;
+  const int nkb = (q0 + RB < g.S ? q0 + RB : g.S) / TB;
+  const int nkw = on ? (wq0 + WR - 1) / TB + 1 : 0;
+  const float scale = replica_scale(g, r);
+  const float c = scale * kLog2e;
+  const int64_t gr = (((int64_t)r * g.B + b) * g.heads + h) * g.S + (on ? wq0 : 0) + qi;
+  const float mx = g.row_max[gr], inv = g.row_inv[gr];
+
+  bf16x8 fq[4], fda[4];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int64_t o = (int64_t)(k0 + acc_row(e, lane)) * ld + q0 + (lane & 31);
-    dst[o + g.d] = f2bf(dk[e]);
-    dst[o + 2 * g.d] = f2bf(dv[e]);
+  for (int k4 = 0; k4 < 4; ++k4) {
+    fq[k4] = frag_g(base + (int64_t)(on ? wq0 : 0) * ld, ld, k4 * 16, lane);
+    fda[k4] = frag_g(g.da + (tok0 + (on ? wq0 : 0)) * g.d + h * DH, g.d, k4 * 16, lane);
   }
+
+  // p and dp = v da^T of key block i of tile kb, both [key][query]; false above the diagonal
+  auto p_and_dp = [&](const uint16_t* kt, const uint16_t* vt, int kb, int i, float (&p)[16], f16v& dp) -> bool {
+    const int key0 = kb * TB + 32 * i;
+    if (key0 > wq0 + WR - 1) return false;
+    f16v s = zero16();
+    dp = zero16();
+#pragma unroll
+    for (int k4 = 0; k4 < 4; ++k4) {
+      s = mfma(frag_k(kt, PT, 32 * i, k4 * 16, lane), fq[k4], s);
+      dp = mfma(frag_k(vt, PT, 32 * i, k4 * 16, lane), fda[k4], dp);
+    }
+    const bool diag = key0 + 31 > wq0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) p[e] = (diag && key0 + acc_row(e, lane) > wq0 + qi) ? 0.f : prob(s[e], c, mx, inv);
+    return true;
+  };
+
+  tile64 lk, lv;
+  auto prologue = [&]() {
+    lk.fetch(ksrc, ld, tid);
+    lv.fetch(vsrc, ld, tid);
+    lk.commit(smem, tid);
+    lv.commit(smem + 2 * TILE, tid);
+    if (nkb > 1) { lk.fetch(ksrc + (int64_t)TB * ld, ld, tid); lv.fetch(vsrc + (int64_t)TB * ld, ld, tid); }
+    __syncthreads();
+  };
+  auto advance = [&](int kb) {
+    if (kb + 1 < nkb) { lk.commit(smem + ((kb + 1) & 1) * TILE, tid); lv.commit(smem + (2 + ((kb + 1) & 1)) * TILE, tid); }
+    if (kb + 2 < nkb) { lk.fetch(ksrc + (int64_t)(kb + 2) * TB * ld, ld, tid); lv.fetch(vsrc + (int64_t)(kb + 2) * TB * ld, ld, tid); }
+  };
+
+  // pass 1: dot = sum over the keys of dp p
+  float dot = 0.f;
+  prologue();
+  for (int kb = 0; kb < nkb; ++kb) {
+    advance(kb);
+    if (kb < nkw) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        float p[16];
+        f16v dp;
+        if (!p_and_dp(smem + (kb & 1) * TILE, smem + (2 + (kb & 1)) * TILE, kb, i, p, dp)) continue;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dot += dp[e] * p[e];
+      }
+    }
+    __syncthreads();
+  }
+  dot += other_half(dot);
+  if (on && lane < 32) g.row_dot[gr] = dot;
+
+  // pass 2: dq^T = k^T ds^T, [column][query]
+  f16v o[2] = {zero16(), zero16()};
+  prologue();
+  for (int kb = 0; kb < nkb; ++kb) {
+    advance(kb);
+    if (kb < nkw) {
+      const uint16_t* kt = smem + (kb & 1) * TILE;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        float p[16];
+        f16v dp;
+        if (!p_and_dp(kt, smem + (2 + (kb & 1)) * TILE, kb, i, p, dp)) continue;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) p[e] = p[e] * (dp[e] - dot) * scale;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const bf16x8 dsf = acc_frag(p, j);
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) o[dt] = mfma(frag_tp(kt, PT, 32 * dt, 32 * i + 16 * j, lane), dsf, o[dt]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  store_rows(o, smem + w * WR * PT, g.dqkv + (tok0 + (on ? wq0 : 0)) * ld + h * DH, ld, on, lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward, step 2: dk and dv; block = 128 keys, walks the query tiles at or below the diagonal
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(THREADS, 2) void attn_bwd_dkv_kernel(const attn_args g) {
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];        // queries x 2, output gradients x 2
+  __shared__ __attribute__((aligned(16))) float st[2][3][TB];             // row max, 1 / row sum, row dot of the tile's queries
+  const int kblk = blockIdx.x;                                             // the first blocks walk the most tiles
+  const int bh = blockIdx.y, r = blockIdx.z;
+  const int b = bh / g.heads, h = bh - b * g.heads;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, ki = lane & 31;
+  const int64_t ld = 3 * (int64_t)g.d;
+  const int64_t tok0 = ((int64_t)r * g.B + b) * g.S;
+  const uint16_t* base = g.qkv + tok0 * ld + h * DH;
+  const uint16_t* dasrc = g.da + tok0 * g.d + h * DH;
+  const int64_t gr0 = (((int64_t)r * g.B + b) * g.heads + h) * g.S;
+  const int k0 = kblk * RB, wk0 = k0 + w * WR;
+  const bool on = wk0 < g.S;
+  const int qb0 = k0 / TB, nqb = g.S / TB;
+  const float scale = replica_scale(g, r);
+  const float c = scale * kLog2e;
+
+  bf16x8 fk[4], fv[4];
+#pragma unroll
+  for (int k4 = 0; k4 < 4; ++k4) {
+    fk[k4] = frag_g(base + g.d + (int64_t)(on ? wk0 : 0) * ld, ld, k4 * 16, lane);
+    fv[k4] = frag_g(base + 2 * g.d + (int64_t)(on ? wk0 : 0) * ld, ld, k4 * 16, lane);
+  }
+
+  tile64 lq, la;
+  float sv = 0.f;                                                          // one row statistic per thread < 192
+  const float* ssrc = tid < TB ? g.row_max : tid < 2 * TB ? g.row_inv : g.row_dot;
+  auto fetch = [&](int qb) {
+    lq.fetch(base + (int64_t)qb * TB * ld, ld, tid);
+    la.fetch(dasrc + (int64_t)qb * TB * g.d, g.d, tid);
+    if (tid < 3 * TB) sv = ssrc[gr0 + qb * TB + (tid & (TB - 1))];
+  };
+  auto commit = [&](int buf) {
+    lq.commit(smem + buf * TILE, tid);
+    la.commit(smem + (2 + buf) * TILE, tid);
+    if (tid < 3 * TB) st[buf][tid >> 6][tid & (TB - 1)] = sv;
+  };
+
+  f16v dk[2] = {zero16(), zero16()}, dv[2] = {zero16(), zero16()};        // [column][key]
+  fetch(qb0);
+  commit(0);
+  if (qb0 + 1 < nqb) fetch(qb0 + 1);
+  __syncthreads();
+  for (int qb = qb0; qb < nqb; ++qb) {
+    const int buf = (qb - qb0) & 1;
+    if (qb + 1 < nqb) commit(buf ^ 1);
+    if (qb + 2 < nqb) fetch(qb + 2);
+    if (on && qb * TB + TB - 1 >= wk0) {
+      const uint16_t* qt = smem + buf * TILE;
+      const uint16_t* dat = smem + (2 + buf) * TILE;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int qr0 = qb * TB + 32 * i;                                  // first query of the block
+        if (qr0 + 31 < wk0) continue;                                      // all its queries precede the keys
+        f16v s = zero16(), dp = zero16();                                  // [query][key]
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+          s = mfma(frag_k(qt, PT, 32 * i, k4 * 16, lane), fk[k4], s);
+          dp = mfma(frag_k(dat, PT, 32 * i, k4 * 16, lane), fv[k4], dp);
+        }
+        const bool diag = qr0 < wk0 + WR - 1;
+        float p[16], ds[16];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int row = 32 * i + acc_row(4 * e4, lane);                  // 4 consecutive queries of the tile
+          const f4 mx = *reinterpret_cast<const f4*>(&st[buf][0][row]);
+          const f4 inv = *reinterpret_cast<const f4*>(&st[buf][1][row]);
+          const f4 dot = *reinterpret_cast<const f4*>(&st[buf][2][row]);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int e = 4 * e4 + u;
+            const bool keep = !diag || wk0 + ki <= qb * TB + row + u;      // causal: key <= query
+            p[e] = keep ? prob(s[e], c, mx[u], inv[u]) : 0.f;
+            ds[e] = p[e] * (dp[e] - dot[u]) * scale;
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const bf16x8 pf = acc_frag(p, j), dsf = acc_frag(ds, j);
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) {
+            dv[dt] = mfma(frag_tp(dat, PT, 32 * dt, 32 * i + 16 * j, lane), pf, dv[dt]);
+            dk[dt] = mfma(frag_tp(qt, PT, 32 * dt, 32 * i + 16 * j, lane), dsf, dk[dt]);
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  uint16_t* dst = g.dqkv + (tok0 + (on ? wk0 : 0)) * ld + h * DH;
+  store_rows(dk, smem + w * WR * PT, dst + g.d, ld, on, lane);
+  __syncthreads();
+  store_rows(dv, smem + w * WR * PT, dst + 2 * g.d, ld, on, lane);
 }
 
 attn_args make_args(const hdet_attn_desc& a) {
@@ -488,25 +491,24 @@ attn_args make_args(const hdet_attn_desc& a) {
   return g;
 }
 
+dim3 attn_grid(const hdet_attn_desc& a) { return dim3((a.seq_len + RB - 1) / RB, a.batch * a.heads, a.n_replicas); }
+
 }  // namespace
 
-bool hdet_attn_fusable(int seq_len, int d_model, int heads) {
-  return heads > 0 && d_model == heads * DH && seq_len % QB == 0 && seq_len >= QB && seq_len <= SMAX && d_model % 8 == 0;
+bool hdet_attn_fusable(int seq_len, int d_model, int heads, int batch) {
+  return heads > 0 && batch > 0 && d_model == heads * DH && seq_len % TB == 0 && seq_len >= TB && seq_len <= SMAX &&
+         (int64_t)batch * heads <= 65535;
 }
 
 hipError_t hdet_launch_attn_fwd(const hdet_attn_desc& a, hipStream_t s) {
-  if (!hdet_attn_fusable(a.seq_len, a.d_model, a.heads)) return hipErrorInvalidValue;
-  const dim3 grid(a.seq_len / QB, a.batch * a.heads, a.n_replicas);
-  if (a.seq_len <= 256) hipLaunchKernelGGL(attn_fwd_kernel<4>, grid, dim3(256), 0, s, make_args(a));
-  else hipLaunchKernelGGL(attn_fwd_kernel<8>, grid, dim3(512), 0, s, make_args(a));
+  if (!hdet_attn_fusable(a.seq_len, a.d_model, a.heads, a.batch)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(attn_fwd_kernel, attn_grid(a), dim3(THREADS), 0, s, make_args(a));
   return hipGetLastError();
 }
 
 hipError_t hdet_launch_attn_bwd(const hdet_attn_desc& a, hipStream_t s) {
-  if (!hdet_attn_fusable(a.seq_len, a.d_model, a.heads)) return hipErrorInvalidValue;
-  const dim3 grid(a.seq_len / QB, a.batch * a.heads, a.n_replicas);
-  if (a.seq_len <= 256) hipLaunchKernelGGL(attn_bwd_dq_kernel<4>, grid, dim3(256), 0, s, make_args(a));
-  else hipLaunchKernelGGL(attn_bwd_dq_kernel<8>, grid, dim3(512), 0, s, make_args(a));
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel, grid, dim3(256), 0, s, make_args(a));
+  if (!hdet_attn_fusable(a.seq_len, a.d_model, a.heads, a.batch)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, attn_grid(a), dim3(THREADS), 0, s, make_args(a));
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel, attn_grid(a), dim3(THREADS), 0, s, make_args(a));
   return hipGetLastError();
 }

@@ -206,7 +206,7 @@ struct hdet_attn_desc {
   float scale;              // 1 / sqrt(d_head)
   int n_replicas, batch, seq_len, heads, d_model;
 };
-bool hdet_attn_fusable(int seq_len, int d_model, int heads);     // head size 64, S a multiple of 64 up to 512
+bool hdet_attn_fusable(int seq_len, int d_model, int heads, int batch);     // head size 64, S a multiple of 64
 hipError_t hdet_launch_attn_fwd(const hdet_attn_desc& a, hipStream_t stream);
 hipError_t hdet_launch_attn_bwd(const hdet_attn_desc& a, hipStream_t stream);
 

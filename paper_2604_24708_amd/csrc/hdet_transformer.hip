@@ -504,7 +504,7 @@ struct hdet_tf_plan {
   float *stf_mean, *stf_rstd, *scores, *logits, *row_loss;
   std::vector<float*> att_max, att_inv;      // [L] row statistics of the fused attention
   float* att_dot;
-  bool fused_attn;                           // bf16, head size 64, S a multiple of 64 up to 512
+  bool fused_attn;                           // bf16, head size 64, S a multiple of 64
   float *part1, *part2;      // partial column sums [N][row chunks][cols]
   int nrc;                   // row chunks of the two-stage column sums
 };
@@ -554,7 +554,7 @@ static void tf_dims(hdet_tf_plan* p, const hdet_config& cfg) {
   p->N = cfg.n_replicas; p->B = cfg.dims.batch; p->S = cfg.dims.seq_len; p->M = p->B * p->S;
   p->d = cfg.dims.d_model; p->nh = cfg.dims.n_heads; p->dh = p->d / p->nh; p->ff = cfg.dims.d_ff;
   p->V = cfg.dims.vocab; p->L = cfg.dims.n_blocks;
-  p->fused_attn = p->bf16 && hdet_attn_fusable(p->S, p->d, p->nh);
+  p->fused_attn = p->bf16 && hdet_attn_fusable(p->S, p->d, p->nh, p->B);
 }
 
 int64_t hdet_tf_param_count(const hdet_config& cfg) {
@@ -615,7 +615,7 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
 void hdet_tf_destroy(hdet_tf_plan* p) { delete p; }
 
 void hdet_tf_set_fused_attention(hdet_tf_plan* p, bool on) {
-  p->fused_attn = on && p->bf16 && hdet_attn_fusable(p->S, p->d, p->nh);
+  p->fused_attn = on && p->bf16 && hdet_attn_fusable(p->S, p->d, p->nh, p->B);
 }
 
 namespace {

@@ -22,8 +22,9 @@ MID = dict(n_blocks=1, d_model=576, n_heads=9, d_ff=1152, seq_len=264, vocab=230
 FUSE1 = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=64, vocab=50)
 FUSE3 = dict(n_blocks=2, d_model=128, n_heads=2, d_ff=96, seq_len=192, vocab=61)
 FUSE4 = dict(n_blocks=1, d_model=128, n_heads=2, d_ff=64, seq_len=256, vocab=40)
-FUSE5 = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=320, vocab=40)      # 8-wavefront blocks, 5 in use
+FUSE5 = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=320, vocab=40)      # last 128-row block half empty
 FUSE8 = dict(n_blocks=1, d_model=128, n_heads=2, d_ff=64, seq_len=512, vocab=40)
+FUSE16 = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=1024, vocab=40)
 
 
 def norm_err(a, b):
@@ -234,7 +235,7 @@ def test_fp32_label_smoothing_and_attention_temperature_channels(cfg, batch):
         x.close()
 
 
-@pytest.mark.parametrize("cfg,batch,n", [(FUSE1, 2, 2), (FUSE3, 2, 3), (FUSE4, 3, 2), (FUSE5, 2, 2), (FUSE8, 2, 2)])
+@pytest.mark.parametrize("cfg,batch,n", [(FUSE1, 2, 2), (FUSE3, 2, 3), (FUSE4, 3, 2), (FUSE5, 2, 2), (FUSE8, 2, 2), (FUSE16, 1, 2)])
 def test_bf16_fused_attention_against_oracle_and_unfused_path(cfg, batch, n):
     """The fused attention kernels (scores kept on chip) against the oracle, at the mixed-precision
     bar, and against the library's own path through separate GEMM and softmax kernels, with which
