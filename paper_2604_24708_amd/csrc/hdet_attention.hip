@@ -13,7 +13,7 @@
 // an explored channel (Remark 1).  Because p is rounded after the normalisation, every kernel
 // that needs a row-wide quantity first (max and sum in the forward, dot in the backward) walks
 // its tiles twice: once for the quantity, once for the product.  The exponential is the
-// hardware's exp2 of (s * scale * log2 e - max); the row maximum (in that scaled form) and
+// hardware's exp2 of fma(s, scale * log2 e, -max); the row maximum (in that scaled form) and
 // 1/sum of the forward are kept ([rows] fp32 each) and the backward rebuilds p from them with
 // the same expression, hence bit for bit.
 //
@@ -36,7 +36,7 @@
 #include "hdet_internal.h"
 #include "hdet_elem.h"
 
-// the forward and the two backward kernels must evaluate s * c - max identically: no contraction into an fma
+// the forward and the two backward kernels must evaluate the exponent identically: one explicit fma, nothing contracted
 #pragma clang fp contract(off)
 
 namespace {
@@ -108,7 +108,7 @@ __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32);
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 // The probability as the unfused path stores it (bf16), from the raw score s, c = scale log2 e,
 // the row's maximum of s c and 1 / (row sum)
-__device__ __forceinline__ float prob(float s, float c, float mx, float inv) { return bf16_round(exp2_fast(s * c - mx) * inv); }
+__device__ __forceinline__ float prob(float s, float c, float mx, float inv) { return bf16_round(exp2_fast(__builtin_fmaf(s, c, -mx)) * inv); }
 
 // One 64 x 64 bf16 tile from global memory (row pitch ld) to LDS (pitch PT) by the block's 256
 // threads, in two phases so that the loads are in flight while the previous tile is worked on.
@@ -148,6 +148,26 @@ __device__ __forceinline__ float replica_scale(const attn_args& g, int r) {
   return g.temp_channel >= 0 ? g.scale / (float)hdet_channel_value(g.ctrl, g.temp_channel, r, 0.0) : g.scale;
 }
 
+// Blocks reach the chip's 8 XCDs round-robin in launch order, and with causal masking the work of
+// a block grows with its position in the sequence: left alone, an XCD would always receive the
+// same position.  Launch index -> (row block, sequence and head, replica) such that every XCD
+// works through a contiguous range of (replica, sequence, head) with all row blocks of each,
+// which also keeps the tiles those share in one L2.
+struct block_id { int x, bh, r; };
+__device__ __forceinline__ block_id remap_block() {
+  const unsigned nx = gridDim.x, ny = gridDim.y, total = nx * ny * gridDim.z;
+  unsigned lin = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+  if ((total & 7u) == 0u) lin = (lin & 7u) * (total >> 3) + (lin >> 3);
+  block_id b;
+  const unsigned grp = lin / nx;
+  // within an XCD the blocks go round-robin over shader engines and their CUs as well: rotate the
+  // row block from one (sequence, head) to the next so that no unit keeps seeing the same one
+  b.x = (lin % nx + grp + (grp >> 3) + (grp >> 6)) % nx;
+  b.bh = grp % ny;
+  b.r = grp / ny;
+  return b;
+}
+
 // The wavefront's [32 rows][64] result, held transposed in two accumulator blocks (block dt:
 // columns 32 dt .., lane = row), goes to `dst` (row pitch ld) through the wavefront's LDS strip
 // so that every global store writes 16 bytes of a row.
@@ -174,10 +194,11 @@ __device__ __forceinline__ void store_rows(const f16v (&o)[2], uint16_t* stg, ui
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g) {
   __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];        // keys x 2, values x 2
-  const int qblk = gridDim.x - 1 - blockIdx.x;                             // longest blocks first
-  const int bh = blockIdx.y, r = blockIdx.z;
+  const block_id blk = remap_block();
+  const int qblk = gridDim.x - 1 - blk.x, bh = blk.bh, r = blk.r;         // longest blocks first
   const int b = bh / g.heads, h = bh - b * g.heads;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, qi = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, qi = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t ld = 3 * (int64_t)g.d;
   const int64_t tok0 = ((int64_t)r * g.B + b) * g.S;
   const uint16_t* base = g.qkv + tok0 * ld + h * DH;
@@ -193,21 +214,29 @@ __global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g)
 #pragma unroll
   for (int k4 = 0; k4 < 4; ++k4) fq[k4] = frag_g(base + (int64_t)(on ? wq0 : 0) * ld, ld, k4 * 16, lane);
 
-  // scores of key block i of tile kb, [key][query], as exponents: s c, or -inf above the diagonal.
-  // false when the whole block lies above the diagonal.
-  auto scores = [&](const uint16_t* kt, int kb, int i, float (&t)[16]) -> bool {
-    const int key0 = kb * TB + 32 * i;
-    if (key0 > wq0 + WR - 1) return false;
-    f16v s = zero16();
+  // raw scores of key tile kb, [key][query] in two 32-key blocks, -inf above the diagonal;
+  // returns how many of the blocks reach the diagonal or lie below it (1 or 2)
+  auto scores = [&](const uint16_t* kt, int kb, f16v (&s)[2]) -> int {
+    const int key0 = kb * TB;
+    const int n = key0 + 32 > wq0 + WR - 1 ? 1 : 2;
+    s[0] = zero16();
+    s[1] = zero16();
 #pragma unroll
-    for (int k4 = 0; k4 < 4; ++k4) s = mfma(frag_k(kt, PT, 32 * i, k4 * 16, lane), fq[k4], s);
-    const bool diag = key0 + 31 > wq0;
+    for (int k4 = 0; k4 < 4; ++k4) {
+      s[0] = mfma(frag_k(kt, PT, 0, k4 * 16, lane), fq[k4], s[0]);
+      if (n == 2) s[1] = mfma(frag_k(kt, PT, 32, k4 * 16, lane), fq[k4], s[1]);
+    }
 #pragma unroll
-    for (int e = 0; e < 16; ++e) t[e] = (diag && key0 + acc_row(e, lane) > wq0 + qi) ? -INFINITY : s[e] * c;
-    return true;
+    for (int i = 0; i < 2; ++i)
+      if (i < n && key0 + 32 * i + 31 > wq0) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (key0 + 32 * i + acc_row(e, lane) > wq0 + qi) s[i][e] = -INFINITY;
+      }
+    return n;
   };
 
-  // pass 1: row maximum and sum, each half-wavefront over its own keys
+  // pass 1: row maximum (of the raw scores) and sum, each half-wavefront over its own keys
   tile64 lk, lv;
   float m = -1e30f, l = 0.f;
   lk.fetch(ksrc, ld, tid);
@@ -218,25 +247,32 @@ __global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g)
     if (kb + 1 < nkb) lk.commit(smem + ((kb + 1) & 1) * TILE, tid);
     if (kb + 2 < nkb) lk.fetch(ksrc + (int64_t)(kb + 2) * TB * ld, ld, tid);
     if (kb < nkw) {
+      f16v s[2];
+      const int n = scores(smem + (kb & 1) * TILE, kb, s);
+      float top = m;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        float t[16];
-        if (!scores(smem + (kb & 1) * TILE, kb, i, t)) continue;
-        float mx = m;
+      for (int i = 0; i < 2; ++i)
+        if (i < n) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, t[e]);
-        float sum = 0.f;
+          for (int e = 0; e < 16; ++e) top = fmaxf(top, s[i][e]);
+        }
+      const float tc = top * c;
+      float sum = 0.f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sum += exp2_fast(t[e] - mx);
-        l = l * exp2_fast(m - mx) + sum;
-        m = mx;
-      }
+      for (int i = 0; i < 2; ++i)
+        if (i < n) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sum += exp2_fast(__builtin_fmaf(s[i][e], c, -tc));
+        }
+      l = l * exp2_fast((m - top) * c) + sum;
+      m = top;
     }
     __syncthreads();
   }
   const float mo = other_half(m), lo = other_half(l);
-  const float mx = fmaxf(m, mo);
-  const float inv = 1.f / (l * exp2_fast(m - mx) + lo * exp2_fast(mo - mx));
+  const float top = fmaxf(m, mo);
+  const float mx = top * c;
+  const float inv = 1.f / (l * exp2_fast((m - top) * c) + lo * exp2_fast((mo - top) * c));
   if (on && lane < 32) {
     const int64_t gr = (((int64_t)r * g.B + b) * g.heads + h) * g.S + wq0 + qi;
     g.row_max[gr] = mx;
@@ -256,19 +292,21 @@ __global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g)
     if (kb + 2 < nkb) { lk.fetch(ksrc + (int64_t)(kb + 2) * TB * ld, ld, tid); lv.fetch(vsrc + (int64_t)(kb + 2) * TB * ld, ld, tid); }
     if (kb < nkw) {
       const uint16_t* vt = smem + (2 + (kb & 1)) * TILE;
+      f16v s[2];
+      const int n = scores(smem + (kb & 1) * TILE, kb, s);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        float t[16];
-        if (!scores(smem + (kb & 1) * TILE, kb, i, t)) continue;
+      for (int i = 0; i < 2; ++i)
+        if (i < n) {
+          float t[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) t[e] = exp2_fast(t[e] - mx) * inv;
+          for (int e = 0; e < 16; ++e) t[e] = exp2_fast(__builtin_fmaf(s[i][e], c, -mx)) * inv;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const bf16x8 pf = acc_frag(t, j);
+          for (int j = 0; j < 2; ++j) {
+            const bf16x8 pf = acc_frag(t, j);
 #pragma unroll
-          for (int dt = 0; dt < 2; ++dt) o[dt] = mfma(frag_tp(vt, PT, 32 * dt, 32 * i + 16 * j, lane), pf, o[dt]);
+            for (int dt = 0; dt < 2; ++dt) o[dt] = mfma(frag_tp(vt, PT, 32 * dt, 32 * i + 16 * j, lane), pf, o[dt]);
+          }
         }
-      }
     }
     __syncthreads();
   }
@@ -280,10 +318,11 @@ __global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(THREADS, 2) void attn_bwd_dq_kernel(const attn_args g) {
   __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];        // keys x 2, values x 2
-  const int qblk = gridDim.x - 1 - blockIdx.x;
-  const int bh = blockIdx.y, r = blockIdx.z;
+  const block_id blk = remap_block();
+  const int qblk = gridDim.x - 1 - blk.x, bh = blk.bh, r = blk.r;
   const int b = bh / g.heads, h = bh - b * g.heads;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, qi = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, qi = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t ld = 3 * (int64_t)g.d;
   const int64_t tok0 = ((int64_t)r * g.B + b) * g.S;
   const uint16_t* base = g.qkv + tok0 * ld + h * DH;
@@ -389,10 +428,11 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bwd_dq_kernel(const attn_args
 __global__ __launch_bounds__(THREADS, 2) void attn_bwd_dkv_kernel(const attn_args g) {
   __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];        // queries x 2, output gradients x 2
   __shared__ __attribute__((aligned(16))) float st[2][3][TB];             // row max, 1 / row sum, row dot of the tile's queries
-  const int kblk = blockIdx.x;                                             // the first blocks walk the most tiles
-  const int bh = blockIdx.y, r = blockIdx.z;
+  const block_id blk = remap_block();
+  const int kblk = blk.x, bh = blk.bh, r = blk.r;                          // the first blocks walk the most tiles
   const int b = bh / g.heads, h = bh - b * g.heads;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, ki = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, ki = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t ld = 3 * (int64_t)g.d;
   const int64_t tok0 = ((int64_t)r * g.B + b) * g.S;
   const uint16_t* base = g.qkv + tok0 * ld + h * DH;
