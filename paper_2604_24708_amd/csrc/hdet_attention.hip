@@ -110,6 +110,17 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 // the row's maximum of s c and 1 / (row sum)
 __device__ __forceinline__ float prob(float s, float c, float mx, float inv) { return bf16_round(exp2_fast(__builtin_fmaf(s, c, -mx)) * inv); }
 
+// entries of an accumulator block whose row index (row0 + row in block) exceeds `limit` become `fill`
+__device__ __forceinline__ void fill_above(float (&x)[16], int row0, int limit, int lane, float fill) {
+#pragma unroll
+  for (int e = 0; e < 16; ++e) x[e] = row0 + acc_row(e, lane) > limit ? fill : x[e];
+}
+// ... whose row index is below `limit`
+__device__ __forceinline__ void fill_below(float (&x)[16], int row0, int limit, int lane, float fill) {
+#pragma unroll
+  for (int e = 0; e < 16; ++e) x[e] = row0 + acc_row(e, lane) < limit ? fill : x[e];
+}
+
 // One 64 x 64 bf16 tile from global memory (row pitch ld) to LDS (pitch PT) by the block's 256
 // threads, in two phases so that the loads are in flight while the previous tile is worked on.
 struct tile64 {
@@ -192,7 +203,7 @@ __device__ __forceinline__ void store_rows(const f16v (&o)[2], uint16_t* stg, ui
 // ---------------------------------------------------------------------------------------------
 // forward: block = 128 queries of one (replica, sequence, head)
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g) {
+__global__ __launch_bounds__(THREADS, 4) void attn_fwd_kernel(const attn_args g) {
   __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];        // keys x 2, values x 2
   const block_id blk = remap_block();
   const int qblk = gridDim.x - 1 - blk.x, bh = blk.bh, r = blk.r;         // longest blocks first
@@ -214,27 +225,18 @@ __global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g)
 #pragma unroll
   for (int k4 = 0; k4 < 4; ++k4) fq[k4] = frag_g(base + (int64_t)(on ? wq0 : 0) * ld, ld, k4 * 16, lane);
 
-  // raw scores of key tile kb, [key][query] in two 32-key blocks, -inf above the diagonal;
-  // returns how many of the blocks reach the diagonal or lie below it (1 or 2)
-  auto scores = [&](const uint16_t* kt, int kb, f16v (&s)[2]) -> int {
-    const int key0 = kb * TB;
-    const int n = key0 + 32 > wq0 + WR - 1 ? 1 : 2;
-    s[0] = zero16();
-    s[1] = zero16();
+  // Raw scores of 32-key block i of key tile kb, [key][query], -inf above the diagonal
+  auto scores = [&](const uint16_t* kt, int kb, int i, float (&x)[16]) {
+    f16v s = zero16();
 #pragma unroll
-    for (int k4 = 0; k4 < 4; ++k4) {
-      s[0] = mfma(frag_k(kt, PT, 0, k4 * 16, lane), fq[k4], s[0]);
-      if (n == 2) s[1] = mfma(frag_k(kt, PT, 32, k4 * 16, lane), fq[k4], s[1]);
-    }
+    for (int k4 = 0; k4 < 4; ++k4) s = mfma(frag_k(kt, PT, 32 * i, k4 * 16, lane), fq[k4], s);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-      if (i < n && key0 + 32 * i + 31 > wq0) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (key0 + 32 * i + acc_row(e, lane) > wq0 + qi) s[i][e] = -INFINITY;
-      }
-    return n;
+    for (int e = 0; e < 16; ++e) x[e] = s[e];
+    const int key0 = kb * TB + 32 * i;
+    if (key0 + 31 > wq0) fill_above(x, key0, wq0 + qi, lane, -INFINITY);
   };
+  // the second block of a tile is left out when it lies above the diagonal altogether
+  auto blocks_of = [&](int kb) { return kb * TB + 32 > wq0 + WR - 1 ? 1 : 2; };
 
   // pass 1: row maximum (of the raw scores) and sum, each half-wavefront over its own keys
   tile64 lk, lv;
@@ -247,25 +249,20 @@ __global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g)
     if (kb + 1 < nkb) lk.commit(smem + ((kb + 1) & 1) * TILE, tid);
     if (kb + 2 < nkb) lk.fetch(ksrc + (int64_t)(kb + 2) * TB * ld, ld, tid);
     if (kb < nkw) {
-      f16v s[2];
-      const int n = scores(smem + (kb & 1) * TILE, kb, s);
-      float top = m;
+      const int nb = blocks_of(kb);
+      for (int i = 0; i < nb; ++i) {
+        float x[16];
+        scores(smem + (kb & 1) * TILE, kb, i, x);
+        float top = m;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        if (i < n) {
+        for (int e = 0; e < 16; ++e) top = fmaxf(top, x[e]);
+        const float tc = top * c;
+        float sum = 0.f;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) top = fmaxf(top, s[i][e]);
-        }
-      const float tc = top * c;
-      float sum = 0.f;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-        if (i < n) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e) sum += exp2_fast(__builtin_fmaf(s[i][e], c, -tc));
-        }
-      l = l * exp2_fast((m - top) * c) + sum;
-      m = top;
+        for (int e = 0; e < 16; ++e) sum += exp2_fast(__builtin_fmaf(x[e], c, -tc));
+        l = l * exp2_fast((m - top) * c) + sum;
+        m = top;
+      }
     }
     __syncthreads();
   }
@@ -292,21 +289,19 @@ __global__ __launch_bounds__(THREADS, 3) void attn_fwd_kernel(const attn_args g)
     if (kb + 2 < nkb) { lk.fetch(ksrc + (int64_t)(kb + 2) * TB * ld, ld, tid); lv.fetch(vsrc + (int64_t)(kb + 2) * TB * ld, ld, tid); }
     if (kb < nkw) {
       const uint16_t* vt = smem + (2 + (kb & 1)) * TILE;
-      f16v s[2];
-      const int n = scores(smem + (kb & 1) * TILE, kb, s);
+      const int nb = blocks_of(kb);
+      for (int i = 0; i < nb; ++i) {
+        float x[16];
+        scores(smem + (kb & 1) * TILE, kb, i, x);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        if (i < n) {
-          float t[16];
+        for (int e = 0; e < 16; ++e) x[e] = exp2_fast(__builtin_fmaf(x[e], c, -mx)) * inv;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) t[e] = exp2_fast(__builtin_fmaf(s[i][e], c, -mx)) * inv;
+        for (int j = 0; j < 2; ++j) {
+          const bf16x8 pf = acc_frag(x, j);
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            const bf16x8 pf = acc_frag(t, j);
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) o[dt] = mfma(frag_tp(vt, PT, 32 * dt, 32 * i + 16 * j, lane), pf, o[dt]);
-          }
+          for (int dt = 0; dt < 2; ++dt) o[dt] = mfma(frag_tp(vt, PT, 32 * dt, 32 * i + 16 * j, lane), pf, o[dt]);
         }
+      }
     }
     __syncthreads();
   }
@@ -355,9 +350,9 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bwd_dq_kernel(const attn_args
       s = mfma(frag_k(kt, PT, 32 * i, k4 * 16, lane), fq[k4], s);
       dp = mfma(frag_k(vt, PT, 32 * i, k4 * 16, lane), fda[k4], dp);
     }
-    const bool diag = key0 + 31 > wq0;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) p[e] = (diag && key0 + acc_row(e, lane) > wq0 + qi) ? 0.f : prob(s[e], c, mx, inv);
+    for (int e = 0; e < 16; ++e) p[e] = prob(s[e], c, mx, inv);
+    if (key0 + 31 > wq0) fill_above(p, key0, wq0 + qi, lane, 0.f);
     return true;
   };
 
@@ -387,7 +382,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bwd_dq_kernel(const attn_args
         f16v dp;
         if (!p_and_dp(smem + (kb & 1) * TILE, smem + (2 + (kb & 1)) * TILE, kb, i, p, dp)) continue;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) dot += dp[e] * p[e];
+        for (int e = 0; e < 16; ++e) dot = __builtin_fmaf(dp[e], p[e], dot);
       }
     }
     __syncthreads();
@@ -487,21 +482,21 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bwd_dkv_kernel(const attn_arg
           s = mfma(frag_k(qt, PT, 32 * i, k4 * 16, lane), fk[k4], s);
           dp = mfma(frag_k(dat, PT, 32 * i, k4 * 16, lane), fv[k4], dp);
         }
-        const bool diag = qr0 < wk0 + WR - 1;
         float p[16], ds[16];
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
           const int row = 32 * i + acc_row(4 * e4, lane);                  // 4 consecutive queries of the tile
           const f4 mx = *reinterpret_cast<const f4*>(&st[buf][0][row]);
           const f4 inv = *reinterpret_cast<const f4*>(&st[buf][1][row]);
-          const f4 dot = *reinterpret_cast<const f4*>(&st[buf][2][row]);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int e = 4 * e4 + u;
-            const bool keep = !diag || wk0 + ki <= qb * TB + row + u;      // causal: key <= query
-            p[e] = keep ? prob(s[e], c, mx[u], inv[u]) : 0.f;
-            ds[e] = p[e] * (dp[e] - dot[u]) * scale;
-          }
+          for (int u = 0; u < 4; ++u) p[4 * e4 + u] = prob(s[4 * e4 + u], c, mx[u], inv[u]);
+        }
+        if (qr0 < wk0 + WR - 1) fill_below(p, qr0, wk0 + ki, lane, 0.f);   // causal: query >= key
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const f4 dot = *reinterpret_cast<const f4*>(&st[buf][2][32 * i + acc_row(4 * e4, lane)]);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) ds[4 * e4 + u] = p[4 * e4 + u] * (dp[4 * e4 + u] - dot[u]) * scale;
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
