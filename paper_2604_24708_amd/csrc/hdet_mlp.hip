@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const in
 // Wide rows (2048 <= classes <= 32768, classes % 4 == 0): one block of BS threads per row, the row
 // held in registers (thread t owns the 4-element chunks t, t + BS, ...), so the logits are
 // read once; logits and their gradient are streamed past the caches.  Same formulas as
-// xent_kernel.
+// xent_kernel, with the exponential on the hardware's exp2 (relative error about 1e-7).
 template <typename T, int BS, int NV>
 __global__ __launch_bounds__(BS) void xent_row_kernel(const float* logits, const int32_t* labels, int rows, int classes,
                                                       T* dlogits, float* row_loss, const hdet_ctrl* ctrl, int ls_channel) {
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(BS) void xent_row_kernel(const float* logits, const
   for (int i = 0; i < NV; ++i)
     if (tid + BS * i < c4) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { sz += v[i].v[j] - mx; v[i].v[j] = expf(v[i].v[j] - mx); se += v[i].v[j]; }
+      for (int j = 0; j < 4; ++j) { sz += v[i].v[j] - mx; v[i].v[j] = __expf(v[i].v[j] - mx); se += v[i].v[j]; }
     }
   se = wave_sum(se);
   sz = wave_sum(sz);
