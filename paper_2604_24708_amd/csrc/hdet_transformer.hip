@@ -203,58 +203,93 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_vec_kernel(const T* dy, const T
 }
 
 // Two-stage column reduction for cols % 8 == 0: stage 1, block (512 columns x rows_per_block
-// rows x replica), wavefront w adds rows w, w+4, ... of the chunk, the four partial sums are
-// added in the order w = 0..3 and written to part[replica][row chunk][col]; stage 2 adds the
-// row chunks in ascending order.  Same two modes as colsum_kernel.
+// rows x replica), wavefront w adds rows w, w+4, ... of the chunk (loaded eight rows at a time,
+// added in ascending order), the four partial sums are added in the order w = 0..3 and written
+// to part[replica][row chunk][col] (MODE 1: a second array of the same shape right behind the
+// first); stage 2, once per backward pass for all reductions together, adds the row chunks in
+// ascending order.  Same two modes as colsum_kernel.
 template <typename T, int MODE>
 __global__ __launch_bounds__(256) void colsum_part_kernel(const T* src, int64_t src_rs, int64_t src_bs, int M, int cols,
                                                           int rows_per_block, const T* x, const float* mean,
-                                                          const float* rstd, float* part1, float* part2) {
+                                                          const float* rstd, float* part) {
   __shared__ float l1[4][512], l2[4][512];
+  constexpr int U = 8;
   const int r = blockIdx.z, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int col = blockIdx.x * 512 + lane * 8;
   const int m0 = blockIdx.y * rows_per_block;
   const int m1 = m0 + rows_per_block < M ? m0 + rows_per_block : M;
   float a1[8] = {0, 0, 0, 0, 0, 0, 0, 0}, a2[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (col < cols) {
-    for (int m = m0 + w; m < m1; m += 4) {
-      const hdet_f8 v = hdet_ld8(src + (int64_t)r * src_bs + (int64_t)m * src_rs + col);
-      if (MODE == 1) {
-        const hdet_f8 xv = hdet_ld8(x + ((int64_t)r * M + m) * cols + col);
-        const float mu = mean[(int64_t)r * M + m], rs = rstd[(int64_t)r * M + m];
+    for (int mb = m0 + w; mb < m1; mb += 4 * U) {
+      hdet_f8 v[U], xv[U];
+      float mu[U], rs[U];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { a1[j] += v.v[j] * ((xv.v[j] - mu) * rs); a2[j] += v.v[j]; }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) a1[j] += v.v[j];
+      for (int u = 0; u < U; ++u) {
+        const int m = mb + 4 * u;
+        if (m < m1) {
+          v[u] = hdet_ld8(src + (int64_t)r * src_bs + (int64_t)m * src_rs + col);
+          if (MODE == 1) {
+            xv[u] = hdet_ld8(x + ((int64_t)r * M + m) * cols + col);
+            mu[u] = mean[(int64_t)r * M + m];
+            rs[u] = rstd[(int64_t)r * M + m];
+          }
+        }
       }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (mb + 4 * u < m1) {
+          if (MODE == 1) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { a1[j] += v[u].v[j] * ((xv[u].v[j] - mu[u]) * rs[u]); a2[j] += v[u].v[j]; }
+          } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a1[j] += v[u].v[j];
+          }
+        }
     }
   }
 #pragma unroll
   for (int j = 0; j < 8; ++j) { l1[w][lane * 8 + j] = a1[j]; l2[w][lane * 8 + j] = a2[j]; }
   __syncthreads();
   const int64_t pbase = ((int64_t)r * gridDim.y + blockIdx.y) * cols;
+  const int64_t second = (int64_t)gridDim.z * gridDim.y * cols;
   for (int c = threadIdx.x; c < 512; c += 256) {
     const int gc = blockIdx.x * 512 + c;
     if (gc < cols) {
-      part1[pbase + gc] = ((l1[0][c] + l1[1][c]) + l1[2][c]) + l1[3][c];
-      if (MODE == 1) part2[pbase + gc] = ((l2[0][c] + l2[1][c]) + l2[2][c]) + l2[3][c];
+      part[pbase + gc] = ((l1[0][c] + l1[1][c]) + l1[2][c]) + l1[3][c];
+      if (MODE == 1) part[second + pbase + gc] = ((l2[0][c] + l2[1][c]) + l2[2][c]) + l2[3][c];
     }
   }
 }
 
-template <int MODE>
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float* part1, const float* part2, int nchunks, int cols,
-                                                           float* out, float* out2, int64_t out_bs) {
-  const int r = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= cols) return;
-  float a = 0.f, b = 0.f;
-  for (int k = 0; k < nchunks; ++k) {
-    a += part1[((int64_t)r * nchunks + k) * cols + c];
-    if (MODE == 1) b += part2[((int64_t)r * nchunks + k) * cols + c];
+// Stage 2 of every two-stage column reduction of a backward pass in one launch.  Job j owns the
+// blocks first_block .. of the grid's x range, 256 columns each; grid.y = replica.
+struct colsum_job {
+  int64_t part_off;       // floats from the head of the partial-sum area
+  int64_t out_off;        // offset of the result inside a gradient plane (second result of MODE 1: out2_off)
+  int64_t out2_off;
+  int32_t cols, mode, first_block, pad;
+};
+__global__ __launch_bounds__(256) void colsum_final_kernel(const colsum_job* jobs, int njobs, const float* part, int nchunks,
+                                                           int n_replicas, float* grads, int64_t ps) {
+  int lo = 0, hi = njobs - 1;                       // last job whose first block is <= blockIdx.x
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (jobs[mid].first_block <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
   }
-  out[(int64_t)r * out_bs + c] = a;
-  if (MODE == 1) out2[(int64_t)r * out_bs + c] = b;
+  const colsum_job j = jobs[lo];
+  const int r = blockIdx.y, c = (blockIdx.x - j.first_block) * 256 + threadIdx.x;
+  if (c >= j.cols) return;
+  const float* p1 = part + j.part_off + (int64_t)r * nchunks * j.cols + c;
+  float a = 0.f;
+  for (int k = 0; k < nchunks; ++k) a += p1[(int64_t)k * j.cols];
+  grads[(int64_t)r * ps + j.out_off + c] = a;
+  if (j.mode == 1) {
+    const float* p2 = p1 + (int64_t)n_replicas * nchunks * j.cols;
+    float b = 0.f;
+    for (int k = 0; k < nchunks; ++k) b += p2[(int64_t)k * j.cols];
+    grads[(int64_t)r * ps + j.out2_off + c] = b;
+  }
 }
 
 // Column reductions over the M rows: block = 64 columns x 16 row phases; thread (c, q) adds
@@ -505,8 +540,11 @@ struct hdet_tf_plan {
   std::vector<float*> att_max, att_inv;      // [L] row statistics of the fused attention
   float* att_dot;
   bool fused_attn;                           // bf16, head size 64, S a multiple of 64
-  float *part1, *part2;      // partial column sums [N][row chunks][cols]
+  float* part;               // partial column sums, one [N][row chunks][cols] array (two for LayerNorm) per reduction
   int nrc;                   // row chunks of the two-stage column sums
+  std::vector<colsum_job> jobs;   // the two-stage reductions of a backward pass, by position in the parameter plane
+  colsum_job* jobs_dev;
+  int final_blocks;          // x extent of the stage-2 launch
 };
 
 static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -541,10 +579,10 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   p->row_loss = (float*)take(N * M * 4);
   p->att_dot = (float*)take(N * heads * S * 4);
   p->nrc = (int)((M + kColsumRows - 1) / kColsumRows);
-  size_t maxc = V > 3 * d ? V : 3 * d;
-  if (ff > maxc) maxc = ff;
-  p->part1 = (float*)take(N * p->nrc * maxc * 4);
-  p->part2 = (float*)take(N * p->nrc * d * 4);
+  // per block: biases of the four Linear layers (3d + d + ff + d columns) and two LayerNorms (2 x 2d); then final LayerNorm, head bias
+  const size_t sum_cols = (size_t)L * (9 * d + ff) + 2 * d + V;
+  p->part = (float*)take(N * p->nrc * sum_cols * 4);
+  p->jobs_dev = (colsum_job*)take((6 * (size_t)L + 2) * sizeof(colsum_job));
   return off;
 }
 
@@ -609,6 +647,32 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
   }
   p->lnf_g = off; off += d; p->lnf_b = off; off += d;
   p->w_head = off; off += V * d; p->b_head = off; off += V;
+  // stage 2 of the column reductions: one job per bias vector and LayerNorm parameter pair
+  int64_t part_off = 0;
+  int first_block = 0;
+  auto add_job = [&](int cols, int mode, int64_t out_off, int64_t out2_off) {
+    if (cols % 8 != 0) return;                       // such widths take the single-stage kernel
+    colsum_job j = {part_off, out_off, out2_off, cols, mode, first_block, 0};
+    p->jobs.push_back(j);
+    part_off += (int64_t)(mode == 1 ? 2 : 1) * p->N * p->nrc * cols;
+    first_block += (cols + 255) / 256;
+  };
+  add_job((int)V, 0, p->b_head, 0);
+  add_job((int)d, 1, p->lnf_g, p->lnf_b);
+  for (int l = 0; l < p->L; ++l) {
+    const tf_block_off& b = p->blk[l];
+    add_job((int)d, 0, b.b_2, 0);
+    add_job((int)ff, 0, b.b_1, 0);
+    add_job((int)d, 1, b.ln2_g, b.ln2_b);
+    add_job((int)d, 0, b.b_o, 0);
+    add_job(3 * (int)d, 0, b.b_qkv, 0);
+    add_job((int)d, 1, b.ln1_g, b.ln1_b);
+  }
+  p->final_blocks = first_block;
+  if (!p->jobs.empty() &&
+      hipMemcpy(p->jobs_dev, p->jobs.data(), p->jobs.size() * sizeof(colsum_job), hipMemcpyHostToDevice) != hipSuccess) {
+    *err = "could not upload the column-reduction table"; delete p; return nullptr;
+  }
   return p;
 }
 
@@ -683,20 +747,33 @@ void launch_softmax_bwd(const float* dp, const void* prob, int64_t rows, int S, 
   }
 }
 
-// out[c] (and out2[c]) of the column reductions described at colsum_kernel, per replica
+// Column reductions described at colsum_kernel into the gradient plane offsets out_off (and out2_off),
+// per replica.  Widths that are multiples of 8 only run stage 1 here; launch_colsum_final ends the pass.
 template <typename T, int MODE>
-void launch_colsum(const hdet_tf_plan* p, const void* src, int cols, const void* x, const float* mean, const float* rstd,
-                   float* out, float* out2, hipStream_t s) {
+hipError_t launch_colsum(const hdet_tf_plan* p, const void* src, int cols, const void* x, const float* mean, const float* rstd,
+                         int64_t out_off, int64_t out2_off, hipStream_t s) {
   const int M = p->M, N = p->N;
   const int64_t ps = p->buf.plane_stride;
+  float* grads = p->buf.grads_dev;
   if (cols % 8 == 0) {
+    const colsum_job* job = nullptr;
+    for (const colsum_job& j : p->jobs)
+      if (j.out_off == out_off && j.cols == cols && j.mode == MODE) { job = &j; break; }
+    if (!job) return hipErrorInvalidValue;
     hipLaunchKernelGGL((colsum_part_kernel<T, MODE>), dim3((cols + 511) / 512, p->nrc, N), dim3(256), 0, s, (const T*)src, (int64_t)cols,
-                       (int64_t)M * cols, M, cols, kColsumRows, (const T*)x, mean, rstd, p->part1, p->part2);
-    hipLaunchKernelGGL((colsum_final_kernel<MODE>), dim3((cols + 255) / 256, N), dim3(256), 0, s, p->part1, p->part2, p->nrc, cols, out, out2, ps);
+                       (int64_t)M * cols, M, cols, kColsumRows, (const T*)x, mean, rstd, p->part + job->part_off);
   } else {
     hipLaunchKernelGGL((colsum_kernel<T, MODE>), dim3((cols + 63) / 64, N), dim3(1024), 0, s, (const T*)src, (int64_t)cols, (int64_t)M * cols, M, cols,
-                       (const T*)x, mean, rstd, out, out2, ps);
+                       (const T*)x, mean, rstd, grads + out_off, grads + out2_off, ps);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum_final(const hdet_tf_plan* p, hipStream_t s) {
+  if (p->jobs.empty()) return hipSuccess;
+  hipLaunchKernelGGL(colsum_final_kernel, dim3(p->final_blocks, p->N), dim3(256), 0, s, p->jobs_dev, (int)p->jobs.size(), p->part, p->nrc,
+                     p->N, p->buf.grads_dev, p->buf.plane_stride);
+  return hipGetLastError();
 }
 
 enum { NT = 0, NN = 1, TN = 2 };      // forward / dgrad / wgrad operand orders (see the GEMM files)
@@ -833,19 +910,19 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
 
   // ---- backward -----------------------------------------------------------------------
   auto colsum = [&](const void* src, int cols, int64_t out_off) {
-    launch_colsum<T, 0>(p, src, cols, nullptr, nullptr, nullptr, grads + out_off, nullptr, s);
+    return launch_colsum<T, 0>(p, src, cols, nullptr, nullptr, nullptr, out_off, 0, s);
   };
   auto ln_params = [&](const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off, int64_t b_off) {
-    launch_colsum<T, 1>(p, dy, d, x, mean, rstd, grads + g_off, grads + b_off, s);
+    return launch_colsum<T, 1>(p, dy, d, x, mean, rstd, g_off, b_off, s);
   };
   auto wgrad = [&](const void* dy, int wy, const void* x, int wx, int64_t w_off) {      // dW[wy][wx] = dy^T x
     return gemm<T>(p, TN, act(dy, wy), act(x, wx), grads + w_off, wx, plane, false, wy, wx, M, 1, 1, nullptr, 0, s);
   };
 
   TF_CHECK(wgrad(p->dlogits, V, p->hf, d, p->w_head));
-  colsum(p->dlogits, V, p->b_head);
+  TF_CHECK(colsum(p->dlogits, V, p->b_head));
   TF_CHECK(gemm<T>(p, NN, act(p->dlogits, V), wt(p->w_head, d), p->dtmp, d, act_d, true, M, d, V, 1, 1, nullptr, 0, s));
-  ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b);
+  TF_CHECK(ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b));
   launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, nullptr, p->dxa, s);
   for (int l = L - 1; l >= 0; --l) {
     const tf_block_off& o = p->blk[l];
@@ -857,7 +934,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       dy = p->dtmp2;
     }
     TF_CHECK(wgrad(dy, d, p->f[l], ff, o.w_2));
-    colsum(dy, d, o.b_2);
+    TF_CHECK(colsum(dy, d, o.b_2));
     {
       bool fused = false;
       const gelu_fusion gf = {nullptr, p->z[l], &fused};
@@ -866,9 +943,9 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
         hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->dff, (const T*)p->z[l], (T*)p->dff, (int64_t)N * nff);
     }
     TF_CHECK(wgrad(p->dff, ff, p->h2[l], d, o.w_1));
-    colsum(p->dff, ff, o.b_1);
+    TF_CHECK(colsum(p->dff, ff, o.b_1));
     TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
-    ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b);
+    TF_CHECK(ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b));
     launch_ln_bwd_dx<T>(p, p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, p->dxa, p->dxb, s);
     // attention branch: x_mid = x_in + drop(o)
     const void* dob = p->dxb;
@@ -878,7 +955,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       dob = p->dtmp2;
     }
     TF_CHECK(wgrad(dob, d, p->a[l], d, o.w_o));
-    colsum(dob, d, o.b_o);
+    TF_CHECK(colsum(dob, d, o.b_o));
     TF_CHECK(gemm<T>(p, NN, act(dob, d), wt(o.w_o, d), p->dtmp, d, act_d, true, M, d, d, 1, 1, nullptr, 0, s));   // da
     if (p->fused_attn) {
       hdet_attn_desc ad = attn_desc(l);
@@ -896,14 +973,15 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       TF_CHECK(gemm<T>(p, TN, head_sq(p->ds), qkv_part(p->qkv[l], 0), (void*)dk.p, 3 * d, dk.s, true, S, dh, S, B, nh, nullptr, 0, s));
     }
     TF_CHECK(wgrad(p->dqkv, 3 * d, p->h1[l], d, o.w_qkv));
-    colsum(p->dqkv, 3 * d, o.b_qkv);
+    TF_CHECK(colsum(p->dqkv, 3 * d, o.b_qkv));
     TF_CHECK(gemm<T>(p, NN, act(p->dqkv, 3 * d), wt(o.w_qkv, d), p->dtmp, d, act_d, true, M, d, 3 * d, 1, 1, nullptr, 0, s));
-    ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b);
+    TF_CHECK(ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b));
     launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s);
   }
   const int64_t emb = (int64_t)(V + S) * d;      // tok_emb and pos_emb are adjacent at the head of the plane
   hipLaunchKernelGGL(zero_kernel, dim3(grid_for(emb), N), dim3(256), 0, s, grads, ps, p->tok, emb);
   hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3(grid_for(nd), N), dim3(256), 0, s, grads, ps, p->tok, p->pos, ids, M, S, d, (const T*)p->dxa);
+  TF_CHECK(launch_colsum_final(p, s));
   return hipGetLastError();
 }
 
