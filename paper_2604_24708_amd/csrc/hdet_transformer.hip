@@ -202,6 +202,101 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_vec_kernel(const T* dy, const T
   }
 }
 
+// LayerNorm backward with the parameter gradients' stage 1 fused in: block = kLnRows consecutive
+// rows of a replica, wavefront w takes rows w, w+4, ... (one or two in flight), writes dx like the
+// kernel above and keeps, per column it holds, sum dy xhat and sum dy over its rows in ascending
+// order; the four wavefronts' sums are added in the order w = 0..3 and written as row chunk
+// blockIdx.x of part[replica][row chunk][col] (sum dy: a second array right behind the first).
+constexpr int kLnRows = 32;
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
+                                                           const float* theta, int64_t ps, int64_t g_off, int M, int d,
+                                                           const T* resid, T* dx, float* part) {
+  __shared__ float l1[4][NCH * 512], l2[4][NCH * 512];
+  const int r = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const float* g = theta + (int64_t)r * ps + g_off;
+  const int d8 = d >> 3;
+  hdet_f8 gv[NCH], ag[NCH], ab[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int ch = lane + 64 * i;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { ag[i].v[j] = 0.f; ab[i].v[j] = 0.f; gv[i].v[j] = 0.f; }
+    if (ch < d8) gv[i] = hdet_ld8(g + 8 * ch);
+  }
+  const int row0 = blockIdx.x * kLnRows + w;
+  constexpr int U = NCH == 1 ? 2 : 1;                 // rows in flight per wavefront, by register budget
+  for (int it = 0; it < kLnRows / 4; it += U) {
+    hdet_f8 dyv[U][NCH], xh[U][NCH];
+    float mu[U], rs[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = row0 + 4 * (it + u);
+      if (row < M) {
+        const int64_t base = ((int64_t)r * M + row) * d;
+        mu[u] = mean[(int64_t)r * M + row];
+        rs[u] = rstd[(int64_t)r * M + row];
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+          if (lane + 64 * i < d8) { dyv[u][i] = hdet_ld8(dy + base + 8 * (lane + 64 * i)); xh[u][i] = hdet_ld8(x + base + 8 * (lane + 64 * i)); }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = row0 + 4 * (it + u);
+      if (row >= M) continue;                         // uniform over the wavefront
+      const int64_t base = ((int64_t)r * M + row) * d;
+      hdet_f8 rv[NCH];                                // in flight while the row's sums are formed
+      if (resid) {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+          if (lane + 64 * i < d8) rv[i] = hdet_ld8(resid + base + 8 * (lane + 64 * i));
+      }
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i)
+        if (lane + 64 * i < d8) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float dyj = dyv[u][i].v[j];
+            xh[u][i].v[j] = (xh[u][i].v[j] - mu[u]) * rs[u];
+            ag[i].v[j] += dyj * xh[u][i].v[j];
+            ab[i].v[j] += dyj;
+            dyv[u][i].v[j] = dyj * gv[i].v[j];
+            s1 += dyv[u][i].v[j];
+            s2 += dyv[u][i].v[j] * xh[u][i].v[j];
+          }
+        }
+      const float m1 = hdet_wave_sum(s1) / (float)d, m2 = hdet_wave_sum(s2) / (float)d;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int ch = lane + 64 * i;
+        if (ch < d8) {
+          hdet_f8 o;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o.v[j] = rs[u] * (dyv[u][i].v[j] - m1 - xh[u][i].v[j] * m2);
+          if (resid) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o.v[j] += rv[i].v[j];
+          }
+          hdet_st8(dx + base + 8 * ch, o);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { l1[w][(lane + 64 * i) * 8 + j] = ag[i].v[j]; l2[w][(lane + 64 * i) * 8 + j] = ab[i].v[j]; }
+  __syncthreads();
+  const int64_t pbase = ((int64_t)r * gridDim.x + blockIdx.x) * d;
+  const int64_t second = (int64_t)gridDim.y * gridDim.x * d;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    part[pbase + c] = ((l1[0][c] + l1[1][c]) + l1[2][c]) + l1[3][c];
+    part[second + pbase + c] = ((l2[0][c] + l2[1][c]) + l2[2][c]) + l2[3][c];
+  }
+}
+
 // Two-stage column reduction for cols % 8 == 0: stage 1, block (512 columns x rows_per_block
 // rows x replica), wavefront w adds rows w, w+4, ... of the chunk (loaded eight rows at a time,
 // added in ascending order), the four partial sums are added in the order w = 0..3 and written
@@ -268,9 +363,9 @@ struct colsum_job {
   int64_t part_off;       // floats from the head of the partial-sum area
   int64_t out_off;        // offset of the result inside a gradient plane (second result of MODE 1: out2_off)
   int64_t out2_off;
-  int32_t cols, mode, first_block, pad;
+  int32_t cols, mode, first_block, nchunks;   // nchunks: row chunks stage 1 produced
 };
-__global__ __launch_bounds__(256) void colsum_final_kernel(const colsum_job* jobs, int njobs, const float* part, int nchunks,
+__global__ __launch_bounds__(256) void colsum_final_kernel(const colsum_job* jobs, int njobs, const float* part,
                                                            int n_replicas, float* grads, int64_t ps) {
   int lo = 0, hi = njobs - 1;                       // last job whose first block is <= blockIdx.x
   while (lo < hi) {
@@ -278,6 +373,7 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const colsum_job* job
     if (jobs[mid].first_block <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
   }
   const colsum_job j = jobs[lo];
+  const int nchunks = j.nchunks;
   const int r = blockIdx.y, c = (blockIdx.x - j.first_block) * 256 + threadIdx.x;
   if (c >= j.cols) return;
   const float* p1 = part + j.part_off + (int64_t)r * nchunks * j.cols + c;
@@ -580,8 +676,9 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   p->att_dot = (float*)take(N * heads * S * 4);
   p->nrc = (int)((M + kColsumRows - 1) / kColsumRows);
   // per block: biases of the four Linear layers (3d + d + ff + d columns) and two LayerNorms (2 x 2d); then final LayerNorm, head bias
-  const size_t sum_cols = (size_t)L * (9 * d + ff) + 2 * d + V;
-  p->part = (float*)take(N * p->nrc * sum_cols * 4);
+  // (the LayerNorm pairs in chunks of kLnRows rows when their backward kernel produces them itself)
+  const size_t ln_chunks = (M + kLnRows - 1) / kLnRows;
+  p->part = (float*)take(N * (p->nrc * ((size_t)L * (5 * d + ff) + V) + ln_chunks * 2 * d * (2 * (size_t)L + 1)) * 4);
   p->jobs_dev = (colsum_job*)take((6 * (size_t)L + 2) * sizeof(colsum_job));
   return off;
 }
@@ -619,6 +716,14 @@ int hdet_tf_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* 
   return HDET_OK;
 }
 
+// whether the LayerNorm with its gain at g_off takes the vector kernels, and whether its backward kernel
+// also produces stage 1 of the parameter gradients (up to d = 1024: beyond, the registers that takes
+// cost more than the separate reduction)
+static bool hdet_tf_ln_vector(const hdet_tf_plan* p, int64_t g_off) {
+  return p->d % 8 == 0 && p->d <= 2048 && g_off % 4 == 0 && p->buf.plane_stride % 4 == 0;
+}
+static bool hdet_tf_ln_fused(const hdet_tf_plan* p, int64_t g_off) { return hdet_tf_ln_vector(p, g_off) && p->d <= 1024; }
+
 hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, int drop_channel, int ls_channel,
                              int temp_channel, std::string* err) {
   if (hdet_tf_validate(cfg, err) != HDET_OK) return nullptr;
@@ -652,9 +757,10 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
   int first_block = 0;
   auto add_job = [&](int cols, int mode, int64_t out_off, int64_t out2_off) {
     if (cols % 8 != 0) return;                       // such widths take the single-stage kernel
-    colsum_job j = {part_off, out_off, out2_off, cols, mode, first_block, 0};
+    const int nchunks = mode == 1 && hdet_tf_ln_fused(p, out_off) ? (p->M + kLnRows - 1) / kLnRows : p->nrc;
+    colsum_job j = {part_off, out_off, out2_off, cols, mode, first_block, nchunks};
     p->jobs.push_back(j);
-    part_off += (int64_t)(mode == 1 ? 2 : 1) * p->N * p->nrc * cols;
+    part_off += (int64_t)(mode == 1 ? 2 : 1) * p->N * nchunks * cols;
     first_block += (cols + 255) / 256;
   };
   add_job((int)V, 0, p->b_head, 0);
@@ -704,21 +810,35 @@ void launch_ln_fwd(const hdet_tf_plan* p, const void* x, int64_t g_off, int64_t 
   }
 }
 
+// dx of a LayerNorm (plus `resid`); true when the launch also produced stage 1 of the parameter gradients
 template <typename T>
-void launch_ln_bwd_dx(const hdet_tf_plan* p, const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off,
+bool launch_ln_bwd_dx(const hdet_tf_plan* p, const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off,
                       const void* resid, void* dx, hipStream_t s) {
   const int M = p->M, d = p->d;
   const int64_t ps = p->buf.plane_stride;
   const float* theta = p->buf.params_dev;
-  const dim3 grid((M + 3) / 4, p->N);
-  if (d % 8 == 0 && d <= 2048 && g_off % 4 == 0 && ps % 4 == 0) {
+  if (hdet_tf_ln_vector(p, g_off)) {
+    const colsum_job* job = nullptr;
+    if (hdet_tf_ln_fused(p, g_off))
+      for (const colsum_job& j : p->jobs)
+        if (j.out_off == g_off && j.mode == 1) { job = &j; break; }
     const int nch = (d / 8 + 63) / 64;
+    if (job) {
+      const dim3 grid(job->nchunks, p->N);
+#define CALL(K) hipLaunchKernelGGL((ln_bwd_fused_kernel<T, K>), grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx, p->part + job->part_off)
+      if (nch == 1) CALL(1); else CALL(2);
+#undef CALL
+      return true;
+    }
+    const dim3 grid((M + 3) / 4, p->N);
 #define CALL(K) hipLaunchKernelGGL((ln_bwd_dx_vec_kernel<T, K>), grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx)
     HDET_NCH_SWITCH(nch, CALL)
 #undef CALL
   } else {
+    const dim3 grid((M + 3) / 4, p->N);
     hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx);
   }
+  return false;
 }
 
 template <typename T>
@@ -771,7 +891,7 @@ hipError_t launch_colsum(const hdet_tf_plan* p, const void* src, int cols, const
 
 hipError_t launch_colsum_final(const hdet_tf_plan* p, hipStream_t s) {
   if (p->jobs.empty()) return hipSuccess;
-  hipLaunchKernelGGL(colsum_final_kernel, dim3(p->final_blocks, p->N), dim3(256), 0, s, p->jobs_dev, (int)p->jobs.size(), p->part, p->nrc,
+  hipLaunchKernelGGL(colsum_final_kernel, dim3(p->final_blocks, p->N), dim3(256), 0, s, p->jobs_dev, (int)p->jobs.size(), p->part,
                      p->N, p->buf.grads_dev, p->buf.plane_stride);
   return hipGetLastError();
 }
@@ -922,8 +1042,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   TF_CHECK(wgrad(p->dlogits, V, p->hf, d, p->w_head));
   TF_CHECK(colsum(p->dlogits, V, p->b_head));
   TF_CHECK(gemm<T>(p, NN, act(p->dlogits, V), wt(p->w_head, d), p->dtmp, d, act_d, true, M, d, V, 1, 1, nullptr, 0, s));
-  TF_CHECK(ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b));
-  launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, nullptr, p->dxa, s);
+  if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, nullptr, p->dxa, s)) TF_CHECK(ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b));
   for (int l = L - 1; l >= 0; --l) {
     const tf_block_off& o = p->blk[l];
     // MLP branch: x_out = x_mid + drop(y)
@@ -945,8 +1064,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(wgrad(p->dff, ff, p->h2[l], d, o.w_1));
     TF_CHECK(colsum(p->dff, ff, o.b_1));
     TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
-    TF_CHECK(ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b));
-    launch_ln_bwd_dx<T>(p, p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, p->dxa, p->dxb, s);
+    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, p->dxa, p->dxb, s)) TF_CHECK(ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b));
     // attention branch: x_mid = x_in + drop(o)
     const void* dob = p->dxb;
     if (drop) {
@@ -975,8 +1093,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(wgrad(p->dqkv, 3 * d, p->h1[l], d, o.w_qkv));
     TF_CHECK(colsum(p->dqkv, 3 * d, o.b_qkv));
     TF_CHECK(gemm<T>(p, NN, act(p->dqkv, 3 * d), wt(o.w_qkv, d), p->dtmp, d, act_d, true, M, d, 3 * d, 1, 1, nullptr, 0, s));
-    TF_CHECK(ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b));
-    launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s);
+    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s)) TF_CHECK(ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b));
   }
   const int64_t emb = (int64_t)(V + S) * d;      // tok_emb and pos_emb are adjacent at the head of the plane
   hipLaunchKernelGGL(zero_kernel, dim3(grid_for(emb), N), dim3(256), 0, s, grads, ps, p->tok, emb);

@@ -17,6 +17,9 @@ SMALL = dict(n_blocks=2, d_model=64, n_heads=4, d_ff=256, seq_len=32, vocab=512)
 ODD = dict(n_blocks=1, d_model=24, n_heads=3, d_ff=50, seq_len=70, vocab=131)        # ragged everywhere
 # two register chunks per lane in LayerNorm (d > 512) and softmax (S > 256), wide-row cross-entropy
 MID = dict(n_blocks=1, d_model=576, n_heads=9, d_ff=1152, seq_len=264, vocab=2304)
+# LayerNorm widths beyond what its backward kernel reduces itself (1024) and beyond the vector kernels (2048)
+WIDE = dict(n_blocks=1, d_model=1088, n_heads=17, d_ff=64, seq_len=8, vocab=40)
+WIDER = dict(n_blocks=1, d_model=2112, n_heads=33, d_ff=32, seq_len=6, vocab=24)
 # head size 64 and sequence lengths that are multiples of 64: the shapes the fused attention kernels take
 # (one, three and four 64-row blocks per sequence; one and two heads)
 FUSE1 = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=64, vocab=50)
@@ -101,7 +104,7 @@ def per_tensor_errors(cfg, g_dev, g_ref):
     return out
 
 
-@pytest.mark.parametrize("cfg,batch,n", [(TINY, 3, 3), (SMALL, 4, 2), (ODD, 2, 2), (MID, 2, 2)])
+@pytest.mark.parametrize("cfg,batch,n", [(TINY, 3, 3), (SMALL, 4, 2), (ODD, 2, 2), (MID, 2, 2), (WIDE, 5, 2), (WIDER, 2, 2)])
 def test_fp32_loss_and_every_gradient_tensor(cfg, batch, n):
     run = TfRun(base(n_replicas=n), cfg, batch)
     ids, tgt, gl = run.forward_backward(1)
@@ -114,7 +117,9 @@ def test_fp32_loss_and_every_gradient_tensor(cfg, batch, n):
         assert not bad, (r, bad)
     # entry-wise over the whole plane (tensors of very different scale, dot products of up to
     # M or V fp32 terms): an intermediate, bounded loosely; the per-tensor norms above are the check
-    assert rel_err(g_dev, grads) <= (2e-4 if cfg is not MID else 5e-3)
+    # (not for the wide cases: a few tokens against dot products of 1000-2000 fp32 terms that cancel)
+    if cfg not in (WIDE, WIDER):
+        assert rel_err(g_dev, grads) <= (2e-4 if cfg is not MID else 5e-3)
     run.close()
 
 
