@@ -342,7 +342,7 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
     const dim3 grid((g.n + TN - 1) / TN, (g.m + TM - 1) / TM, batch);                                          \
     hipLaunchKernelGGL((hdet_bgemm_dma_kernel<AK, BK, EPI, TM, TN, WGM, WGN, NST, TK>), grid, dim3(64 * WGM * WGN), 0, s, g); \
   } while (0)
-  if (long_k && blocks(256, 256) >= kCus) HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);   // one block per CU, 128 KiB of stages
+  if ((long_k && blocks(256, 256) >= kCus) || blocks(256, 256) >= 3 * kCus) HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);   // one block per CU, 128 KiB of stages
   else if (blocks(256, 128) >= kCus) {
     if (long_k) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 64);                             // one block per CU, 144 KiB
     else HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 32);                                    // two blocks per CU, 72 KiB each
