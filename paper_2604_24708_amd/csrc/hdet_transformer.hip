@@ -44,19 +44,29 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const float* theta, int6
   }
 }
 
-// dtok[ids[m]] += dx[m], dpos[m % S] += dx[m]  (fp32 atomics; the two regions are zeroed first)
+// dtok[ids[m]] += dx[m] with fp32 atomics (the region is zeroed first): the one sum of the
+// backward pass whose order is left to the hardware.
 template <typename T>
-__global__ __launch_bounds__(256) void embed_bwd_kernel(float* grads, int64_t ps, int64_t tok_off, int64_t pos_off,
-                                                        const int32_t* ids, int M, int S, int d, const T* dx) {
+__global__ __launch_bounds__(256) void embed_bwd_kernel(float* grads, int64_t ps, int64_t tok_off, const int32_t* ids, int M, int d,
+                                                        const T* dx) {
   const int r = blockIdx.y;
   float* tok = grads + (int64_t)r * ps + tok_off;
-  float* pos = grads + (int64_t)r * ps + pos_off;
   const int64_t n = (int64_t)M * d;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const int m = (int)(i / d), c = (int)(i % d);
-    const float g = hdet_ld(dx + (int64_t)r * n + i);
-    atomicAdd(tok + (int64_t)ids[(int64_t)r * M + m] * d + c, g);
-    atomicAdd(pos + (int64_t)(m % S) * d + c, g);
+    atomicAdd(tok + (int64_t)ids[(int64_t)r * M + m] * d + c, hdet_ld(dx + (int64_t)r * n + i));
+  }
+}
+// dpos[s] = sum over the sequences b, in ascending order, of dx[b S + s]
+template <typename T>
+__global__ __launch_bounds__(256) void pos_bwd_kernel(float* grads, int64_t ps, int64_t pos_off, int B, int S, int d, const T* dx) {
+  const int r = blockIdx.y;
+  float* pos = grads + (int64_t)r * ps + pos_off;
+  const int64_t n = (int64_t)S * d;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    float a = 0.f;
+    for (int b = 0; b < B; ++b) a += hdet_ld(dx + ((int64_t)r * B + b) * n + i);
+    pos[i] = a;
   }
 }
 
@@ -1095,9 +1105,9 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(gemm<T>(p, NN, act(p->dqkv, 3 * d), wt(o.w_qkv, d), p->dtmp, d, act_d, true, M, d, 3 * d, 1, 1, nullptr, 0, s));
     if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s)) TF_CHECK(ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b));
   }
-  const int64_t emb = (int64_t)(V + S) * d;      // tok_emb and pos_emb are adjacent at the head of the plane
-  hipLaunchKernelGGL(zero_kernel, dim3(grid_for(emb), N), dim3(256), 0, s, grads, ps, p->tok, emb);
-  hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3(grid_for(nd), N), dim3(256), 0, s, grads, ps, p->tok, p->pos, ids, M, S, d, (const T*)p->dxa);
+  hipLaunchKernelGGL(zero_kernel, dim3(grid_for((int64_t)V * d), N), dim3(256), 0, s, grads, ps, p->tok, (int64_t)V * d);
+  hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3(grid_for(nd), N), dim3(256), 0, s, grads, ps, p->tok, ids, M, d, (const T*)p->dxa);
+  hipLaunchKernelGGL(pos_bwd_kernel<T>, dim3(grid_for((int64_t)S * d), N), dim3(256), 0, s, grads, ps, p->pos, B, S, d, (const T*)p->dxa);
   TF_CHECK(launch_colsum_final(p, s));
   return hipGetLastError();
 }
