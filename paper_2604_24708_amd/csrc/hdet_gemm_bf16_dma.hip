@@ -270,6 +270,22 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
   const int lr = lane / LPR, lc = (lane % LPR) * 4;
   constexpr bool kBias = EPI == HDET_EPI_BIAS_RELU_BF16 || EPI == HDET_EPI_BIAS_F32 || EPI == HDET_EPI_BIAS_BF16 ||
                          EPI == HDET_EPI_BIAS_GELU_BF16;
+  // the second operand of the gating epilogues (the activations a ReLU or GELU gradient looks at) is
+  // fetched one strip ahead, so that its latency hides behind the previous strip's pass through LDS
+  constexpr bool kGate = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16;
+  constexpr int NIT = 32 / RPI, NSTRIP = (WNT / JG) * WMT;
+  us4 gate[2][NIT];
+  auto fetch_gate = [&](int strip, us4 (&dst)[NIT]) {
+    const int col = n0 + wn + (strip / WMT) * CW + lc;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int row = m0 + wm + (strip % WMT) * 32 + it * RPI + lr;
+      dst[it] = us4{0, 0, 0, 0};
+      if (row < g.m && col < g.n)
+        dst[it] = *reinterpret_cast<const us4*>(g.mask + (int64_t)z * g.mask_bs + (int64_t)row * g.mask_ld + col);
+    }
+  };
+  if (kGate) fetch_gate(0, gate[0]);
 #pragma unroll
   for (int jg = 0; jg < WNT / JG; ++jg) {
     const int col = n0 + wn + jg * CW + lc;
@@ -278,6 +294,8 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
     if (kBias && col_ok) bias = *reinterpret_cast<const f4*>(g.bias + (int64_t)z * g.bias_bs + col);
 #pragma unroll
     for (int i = 0; i < WMT; ++i) {
+      const int strip = jg * WMT + i;
+      if (kGate && strip + 1 < NSTRIP) fetch_gate(strip + 1, gate[(strip + 1) & 1]);
       // accumulator element e of lane l is C(row, col) with row = (e / 4) * 8 + (l / 32) * 4 + e % 4,
       // col = l % 32 inside its 32x32 block
 #pragma unroll
@@ -298,12 +316,12 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
             for (int q = 0; q < 4; ++q) v[q] = v[q] > 0.f ? v[q] : 0.f;
           }
           if (EPI == HDET_EPI_MASK_BF16) {    // gradient through the ReLU of the layer below
-            const us4 a = *reinterpret_cast<const us4*>(g.mask + (int64_t)z * g.mask_bs + (int64_t)row * g.mask_ld + col);
+            const us4 a = gate[strip & 1][it];
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = bf2f(a[q]) > 0.f ? v[q] : 0.f;
           }
           if (EPI == HDET_EPI_GELUGRAD_BF16) {  // the incoming gradient is rounded as the unfused path stores it
-            const us4 a = *reinterpret_cast<const us4*>(g.mask + (int64_t)z * g.mask_bs + (int64_t)row * g.mask_ld + col);
+            const us4 a = gate[strip & 1][it];
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = bf2f(f2bf(v[q])) * hdet_gelu_tanh_grad_fast(bf2f(a[q]));
           }
@@ -342,7 +360,11 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
     const dim3 grid((g.n + TN - 1) / TN, (g.m + TM - 1) / TM, batch);                                          \
     hipLaunchKernelGGL((hdet_bgemm_dma_kernel<AK, BK, EPI, TM, TN, WGM, WGN, NST, TK>), grid, dim3(64 * WGM * WGN), 0, s, g); \
   } while (0)
-  if ((long_k && blocks(256, 256) >= kCus) || blocks(256, 256) >= 3 * kCus) HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);   // one block per CU, 128 KiB of stages
+  // short-K products with plenty of tiles also take the largest tile, unless the epilogue reads a second
+  // operand: those do better with two blocks per CU, whose epilogues and main loops overlap
+  constexpr bool gating = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16;
+  if ((long_k && blocks(256, 256) >= kCus) || (!gating && blocks(256, 256) >= 3 * kCus))
+    HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);                                         // one block per CU, 128 KiB of stages
   else if (blocks(256, 128) >= kCus) {
     if (long_k) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 64);                             // one block per CU, 144 KiB
     else HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 32);                                    // two blocks per CU, 72 KiB each
