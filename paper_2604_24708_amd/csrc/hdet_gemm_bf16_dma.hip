@@ -354,7 +354,9 @@ template <bool AK, bool BK, int EPI>
 hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
   auto blocks = [&](int tm, int tn) { return (int64_t)((g.m + tm - 1) / tm) * ((g.n + tn - 1) / tn) * batch; };
   constexpr int kCus = 256;
-  const bool long_k = g.k >= 1024;
+  // a gating epilogue is long enough to want a second block on the CU up to K = 1024
+  constexpr bool gating = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16;
+  const bool long_k = g.k >= (gating ? 2048 : 1024);
 #define HDET_DMA_LAUNCH(TM, TN, WGM, WGN, NST, TK)                                                            \
   do {                                                                                                        \
     const dim3 grid((g.n + TN - 1) / TN, (g.m + TM - 1) / TM, batch);                                          \
@@ -362,7 +364,6 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
   } while (0)
   // short-K products with plenty of tiles also take the largest tile, unless the epilogue reads a second
   // operand: those do better with two blocks per CU, whose epilogues and main loops overlap
-  constexpr bool gating = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16;
   if ((long_k && blocks(256, 256) >= kCus) || (!gating && blocks(256, 256) >= 3 * kCus))
     HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);                                         // one block per CU, 128 KiB of stages
   else if (blocks(256, 128) >= kCus) {
