@@ -102,3 +102,50 @@ def test_transformer_6l_d512_seq256_vocab32000():
     assert not bad, bad
     assert torch.all(g[:, P:] == 7.0) if stride > P else True
     H.hdet_destroy(h)
+
+
+def test_transformer_block_at_the_12_layer_shapes():
+    """One block of the larger transformer workload at its full layer shapes: d_model 1024, 16 heads,
+    FFN 4096, 16 sequences of 512 tokens per replica, with the dropout and weight-decay channels of
+    that workload.  Every kernel runs in the launch shape the 12-layer step uses it in (256x256 GEMM
+    tiles at K = 1024 and 4096, the two-blocks-per-CU tile of the GELU-gradient product, attention
+    over eight key tiles, two register chunks per lane in LayerNorm, 64 row chunks in the column sums);
+    the vocabulary is cut to 4096 and the depth to one block so that a replica of the oracle stays
+    at about 1 TFLOP.  Replica 0 against the oracle."""
+    cfg = dict(n_blocks=1, d_model=1024, n_heads=16, d_ff=4096, seq_len=512, vocab=4096)
+    n, B = 2, 16
+    P = I.transformer_param_count(cfg)
+    stride = (P + 63) // 64 * 64
+    dev = "cuda:0"
+    th0 = I.transformer_init(1, cfg, I.SEED_INIT)[0]
+    theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
+    theta[:, :P] = torch.from_numpy(th0).to(dev)
+    m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.full_like(theta, 7.0)
+    shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
+    extra = [(O.CH_DROPOUT, 0.1, 0.5, 0.5, 0.0, 0.5), (O.CH_WD, 0.01, 0.5, 0.5, 0.0, float("inf"))]
+    d = base(n_replicas=n, total_steps=4000, sync_interval=64, warm_steps=1200, lr_max=3e-4, alpha=0.15, extra=extra)
+    lc = library_config(d, model_kind=H.HDET_TRANSFORMER, batch=B, precision=H.HDET_BF16_GEMM_FP32_MASTER, **cfg)
+    _, _, ws = H.hdet_workspace_bytes(lc, stride)
+    wsb = torch.empty(ws, dtype=torch.uint8, device=dev)
+    h = H.hdet_create(lc, theta, m, v, grads=g, params_bf16=shadow, workspace=wsb, plane_stride=stride)
+    orc = O.HDETOracle(oracle_config(d), np.stack([th0] * n))
+    ids, tgt = I.zipf_tokens(n, B, cfg["seq_len"], cfg["vocab"], I.SEED_DATA, 0)
+    out = H.hdet_forward_backward(h, torch.from_numpy(ids).to(dev), torch.from_numpy(tgt).to(dev), want_losses=True)
+    p = orc.dropout_table()
+    assert p[0] > 0
+    t0 = time.time()
+    loss, ref = T.loss_and_grad(th0, ids[0], tgt[0], cfg, bf16=True,
+                                dropout=dict(p=float(p[0]), seed=d["seed"], step=1, replica=0))
+    print(f"oracle: one replica in {time.time() - t0:.1f} s")
+    assert abs(out[0] - loss) <= 1e-2
+    g_dev = g[0, :P].cpu().numpy()
+    off, bad = 0, {}
+    for name, shape in I.transformer_shapes(cfg):
+        k = int(np.prod(shape))
+        e = norm_err(g_dev[off:off + k], ref[off:off + k])
+        if e > 4e-2:
+            bad[name] = e
+        off += k
+    assert not bad, bad
+    assert torch.all(g[:, P:] == 7.0) if stride > P else True
+    H.hdet_destroy(h)
