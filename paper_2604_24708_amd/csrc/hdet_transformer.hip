@@ -44,8 +44,8 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const float* theta, int6
   }
 }
 
-// dtok[ids[m]] += dx[m] with fp32 atomics (the region is zeroed first): the one sum of the
-// backward pass whose order is left to the hardware.
+// dtok[ids[m]] += dx[m] with fp32 atomics (the region is zeroed first), for the shapes the ordered
+// kernels below do not take: the one sum of the backward pass whose order is then left to the hardware.
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(float* grads, int64_t ps, int64_t tok_off, const int32_t* ids, int M, int d,
                                                         const T* dx) {
@@ -57,6 +57,132 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(float* grads, int64_t ps
     atomicAdd(tok + (int64_t)ids[(int64_t)r * M + m] * d + c, hdet_ld(dx + (int64_t)r * n + i));
   }
 }
+// The same sum in a fixed order, for M up to 16384 rows per replica and d a multiple of 8 up to 2048:
+// (1) one block per replica sorts the keys (token id, row) in LDS (bitonic network over the next power
+// of two, padded with all-ones keys), so that the rows of a token id are adjacent and ascending;
+// (2) one wavefront per sorted position: where a new id starts, it adds that id's rows of dx in
+// ascending row order and writes the token's gradient row (the region is zeroed first for the ids
+// that do not occur).
+template <int P2>
+__global__ __launch_bounds__(1024) void tok_sort_kernel(const int32_t* ids, int M, unsigned long long* sorted) {
+  __shared__ unsigned long long keys[P2];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  for (int i = tid; i < P2; i += 1024)
+    keys[i] = i < M ? ((unsigned long long)(uint32_t)ids[(int64_t)r * M + i] << 32) | (uint32_t)i : ~0ull;
+  __syncthreads();
+  for (int k = 2; k <= P2; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < P2 / 2; t += 1024) {
+        const int i = 2 * j * (t / j) + (t % j);
+        const unsigned long long a = keys[i], b = keys[i + j];
+        if ((a > b) == ((i & k) == 0)) { keys[i] = b; keys[i + j] = a; }
+      }
+      __syncthreads();
+    }
+  for (int i = tid; i < M; i += 1024) sorted[(int64_t)r * M + i] = keys[i];
+}
+// Step (2) runs in two levels so that a frequent token does not serialise one wavefront: level 1
+// sums the rows of every segment -- a maximal run of one id inside a block of kTokChunk sorted
+// positions -- into seg[first position of the segment]; level 2 adds the segments of each id in
+// ascending order and writes the token's gradient row.
+constexpr int kTokChunk = 32;
+__device__ __forceinline__ uint32_t key_id(unsigned long long key) { return (uint32_t)(key >> 32); }
+template <int NCH>
+__device__ __forceinline__ void add_row(hdet_f8 (&acc)[NCH], const hdet_f8 (&v)[NCH], int lane, int d8) {
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+    if (lane + 64 * i < d8) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[i].v[c] += v[i].v[c];
+    }
+}
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void tok_segment_kernel(const unsigned long long* sorted, int M, int d, const T* dx, float* seg) {
+  constexpr int U = NCH == 1 ? 8 : 4;               // rows in flight, by register budget
+  const int r = blockIdx.y, lane = threadIdx.x & 63;
+  const int j0 = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j0 >= M) return;
+  const unsigned long long* sk = sorted + (int64_t)r * M;
+  const uint32_t id = key_id(sk[j0]);
+  if (j0 % kTokChunk != 0 && key_id(sk[j0 - 1]) == id) return;      // inside a segment
+  const int jend = (j0 / kTokChunk + 1) * kTokChunk < M ? (j0 / kTokChunk + 1) * kTokChunk : M;
+  const int d8 = d >> 3;
+  const T* src = dx + (int64_t)r * M * d;
+  hdet_f8 acc[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[i].v[c] = 0.f;
+  for (int j = j0; j < jend; j += U) {
+    hdet_f8 v[U][NCH];
+    unsigned long long key[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) key[u] = sk[j + u < jend ? j + u : jend - 1];
+    int n = 0;                                                       // rows of this id among the next U positions
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (n == u && j + u < jend && key_id(key[u]) == id) n = u + 1;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (u < n) {
+        const int64_t row = (int64_t)(uint32_t)key[u] * d;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+          if (lane + 64 * i < d8) v[u][i] = hdet_ld8(src + row + 8 * (lane + 64 * i));
+      }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (u < n) add_row<NCH>(acc, v[u], lane, d8);
+    if (n < U) break;
+  }
+  float* dst = seg + ((int64_t)r * M + j0) * d;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+    if (lane + 64 * i < d8) hdet_st8(dst + 8 * (lane + 64 * i), acc[i]);
+}
+template <int NCH>
+__global__ __launch_bounds__(256) void tok_total_kernel(const unsigned long long* sorted, int M, int d, const float* seg, float* grads,
+                                                        int64_t ps, int64_t tok_off) {
+  constexpr int U = NCH == 1 ? 8 : 4;               // rows in flight, by register budget
+  const int r = blockIdx.y, lane = threadIdx.x & 63;
+  const int j0 = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j0 >= M) return;
+  const unsigned long long* sk = sorted + (int64_t)r * M;
+  const uint32_t id = key_id(sk[j0]);
+  if (j0 > 0 && key_id(sk[j0 - 1]) == id) return;                    // not the first row of its id
+  const int d8 = d >> 3;
+  const float* src = seg + (int64_t)r * M * d;
+  hdet_f8 acc[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) acc[i] = hdet_ld8(src + (int64_t)j0 * d + 8 * (lane + 64 * i < d8 ? lane + 64 * i : 0));
+  // the id's further segments start at the multiples of kTokChunk behind j0, as long as the id goes on
+  for (int j = (j0 / kTokChunk + 1) * kTokChunk; j < M; j += U * kTokChunk) {
+    hdet_f8 v[U][NCH];
+    uint32_t kid[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) kid[u] = key_id(sk[j + u * kTokChunk < M ? j + u * kTokChunk : M - 1]);
+    int n = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (n == u && j + u * kTokChunk < M && kid[u] == id) n = u + 1;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (u < n) {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+          if (lane + 64 * i < d8) v[u][i] = hdet_ld8(src + (int64_t)(j + u * kTokChunk) * d + 8 * (lane + 64 * i));
+      }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (u < n) add_row<NCH>(acc, v[u], lane, d8);
+    if (n < U) break;
+  }
+  float* dst = grads + (int64_t)r * ps + tok_off + (int64_t)id * d;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+    if (lane + 64 * i < d8) hdet_st8(dst + 8 * (lane + 64 * i), acc[i]);
+}
+
 // dpos[s] = sum over the sequences b, in ascending order, of dx[b S + s]
 template <typename T>
 __global__ __launch_bounds__(256) void pos_bwd_kernel(float* grads, int64_t ps, int64_t pos_off, int B, int S, int d, const T* dx) {
@@ -645,6 +771,8 @@ struct hdet_tf_plan {
   float *stf_mean, *stf_rstd, *scores, *logits, *row_loss;
   std::vector<float*> att_max, att_inv;      // [L] row statistics of the fused attention
   float* att_dot;
+  unsigned long long* tok_sorted;            // [N][M] keys (token id, row) in ascending order
+  float* tok_seg;                            // [N][M][d] partial rows of the token-embedding gradient
   bool fused_attn;                           // bf16, head size 64, S a multiple of 64
   float* part;               // partial column sums, one [N][row chunks][cols] array (two for LayerNorm) per reduction
   int nrc;                   // row chunks of the two-stage column sums
@@ -684,6 +812,8 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   p->scores = (float*)take(N * heads * S * S * 4); p->logits = (float*)take(N * M * V * 4);
   p->row_loss = (float*)take(N * M * 4);
   p->att_dot = (float*)take(N * heads * S * 4);
+  p->tok_sorted = (unsigned long long*)take(N * M * 8);
+  p->tok_seg = (float*)take(N * M * d * 4);
   p->nrc = (int)((M + kColsumRows - 1) / kColsumRows);
   // per block: biases of the four Linear layers (3d + d + ff + d columns) and two LayerNorms (2 x 2d); then final LayerNorm, head bias
   // (the LayerNorm pairs in chunks of kLnRows rows when their backward kernel produces them itself)
@@ -1106,7 +1236,21 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s)) TF_CHECK(ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b));
   }
   hipLaunchKernelGGL(zero_kernel, dim3(grid_for((int64_t)V * d), N), dim3(256), 0, s, grads, ps, p->tok, (int64_t)V * d);
-  hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3(grid_for(nd), N), dim3(256), 0, s, grads, ps, p->tok, ids, M, d, (const T*)p->dxa);
+  if (M <= 16384 && d % 8 == 0 && d <= 2048 && p->tok % 4 == 0 && ps % 4 == 0) {
+#define SORT(P2) hipLaunchKernelGGL(tok_sort_kernel<P2>, dim3(N), dim3(1024), 0, s, ids, M, p->tok_sorted)
+    if (M <= 1024) SORT(1024); else if (M <= 2048) SORT(2048); else if (M <= 4096) SORT(4096); else if (M <= 8192) SORT(8192); else SORT(16384);
+#undef SORT
+    const int nch = (d / 8 + 63) / 64;
+    float* seg = p->tok_seg;
+#define CALL(K) hipLaunchKernelGGL((tok_segment_kernel<T, K>), dim3((M + 3) / 4, N), dim3(256), 0, s, p->tok_sorted, M, d, (const T*)p->dxa, seg)
+    HDET_NCH_SWITCH(nch, CALL)
+#undef CALL
+#define CALL(K) hipLaunchKernelGGL((tok_total_kernel<K>), dim3((M + 3) / 4, N), dim3(256), 0, s, p->tok_sorted, M, d, seg, grads, ps, p->tok)
+    HDET_NCH_SWITCH(nch, CALL)
+#undef CALL
+  } else {
+    hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3(grid_for(nd), N), dim3(256), 0, s, grads, ps, p->tok, ids, M, d, (const T*)p->dxa);
+  }
   hipLaunchKernelGGL(pos_bwd_kernel<T>, dim3(grid_for((int64_t)S * d), N), dim3(256), 0, s, grads, ps, p->pos, B, S, d, (const T*)p->dxa);
   TF_CHECK(launch_colsum_final(p, s));
   return hipGetLastError();

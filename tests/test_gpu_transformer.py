@@ -267,3 +267,20 @@ def test_bf16_fused_attention_against_oracle_and_unfused_path(cfg, batch, n):
                 assert not bad, ("unfused", t, r, bad)
         fused.finish_step(t, grads, losses)
     fused.close(); plain.close()
+
+
+@pytest.mark.parametrize("cfg,batch,bf16", [(SMALL, 4, False), (FUSE3, 3, True), (MID, 2, True)])
+def test_gradients_are_bit_reproducible(cfg, batch, bf16):
+    """Every reduction of the forward/backward pass has a fixed order (the token-embedding gradient is
+    formed from sorted rows, not with atomics): two handles fed the same batch give identical bits,
+    losses included, also when other work ran on the device in between."""
+    d = base(n_replicas=3, optimizer=O.ADAMW, lr_max=2e-3)
+    a, b = TfRun(d, cfg, batch, bf16=bf16), TfRun(d, cfg, batch, bf16=bf16)
+    _, _, la = a.forward_backward(1)
+    torch.randn(1 << 22, device="cuda:0").sum().item()
+    _, _, lb = b.forward_backward(1)
+    assert np.array_equal(la, lb)
+    assert torch.equal(a.g, b.g)
+    _, _, la2 = a.forward_backward(1)
+    assert torch.equal(a.g, b.g) and np.array_equal(la, la2)
+    a.close(); b.close()
