@@ -284,3 +284,37 @@ def test_gradients_are_bit_reproducible(cfg, batch, bf16):
     _, _, la2 = a.forward_backward(1)
     assert torch.equal(a.g, b.g) and np.array_equal(la, la2)
     a.close(); b.close()
+
+
+def test_checkpoint_resume_is_bit_exact_on_the_transformer():
+    """Parameters, optimizer state and hdet_get_state after 5 steps, loaded into a fresh handle, continue
+    exactly as the uninterrupted run does for 7 more steps (mixed precision, a dropout channel whose masks
+    are keyed on the step counter, AdamW, two sync steps with the controller on either side of the break)."""
+    extra = [(O.CH_DROPOUT, 0.1, 0.5, 0.5, 0.0, 0.5)]
+    d = base(n_replicas=3, optimizer=O.ADAMW, lr_max=2e-3, weight_decay=0.01, extra=extra)
+    a = TfRun(d, FUSE3, 2, bf16=True)
+
+    def step(run, t):
+        ids, tgt = I.zipf_tokens(run.n, run.batch, run.cfg["seq_len"], run.cfg["vocab"], I.SEED_DATA, t)
+        H.hdet_forward_backward(run.h, torch.from_numpy(ids).to("cuda:0"), torch.from_numpy(tgt).to("cuda:0"))
+        H.hdet_fanout_step(run.h, None, H.HDET_FUSE_CONVERGE if t == 8 else 0)
+        if t % d["sync_interval"] == 0:
+            H.hdet_converge(run.h)
+            H.hdet_autolr_update(run.h, None)
+
+    for t in range(1, 6):
+        step(a, t)
+    st = H.hdet_get_state(a.h)
+    b = TfRun(d, FUSE3, 2, bf16=True)
+    b.theta.copy_(a.theta); b.m.copy_(a.m); b.v.copy_(a.v); b.shadow.copy_(a.shadow)
+    H.hdet_set_state(b.h, st)
+    for t in range(6, 13):
+        step(a, t)
+        step(b, t)
+    assert torch.equal(a.theta, b.theta) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v) and torch.equal(a.shadow, b.shadow)
+    sa, sb = H.hdet_get_state(a.h), H.hdet_get_state(b.h)
+    assert sa.k == sb.k and sa.t == sb.t
+    for j in range(2):
+        assert sa.base[j] == sb.base[j] and sa.vel[j] == sb.vel[j]
+        assert [sa.perm[j][r] for r in range(3)] == [sb.perm[j][r] for r in range(3)]
+    a.close(); b.close()
