@@ -512,16 +512,22 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const colsum_job* job
   const int nchunks = j.nchunks;
   const int r = blockIdx.y, c = (blockIdx.x - j.first_block) * 256 + threadIdx.x;
   if (c >= j.cols) return;
+  // chunks added in ascending order, eight loads in flight
+  auto total = [&](const float* q) {
+    float a = 0.f;
+    for (int k = 0; k < nchunks; k += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = k + u < nchunks ? q[(int64_t)(k + u) * j.cols] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (k + u < nchunks) a += v[u];
+    }
+    return a;
+  };
   const float* p1 = part + j.part_off + (int64_t)r * nchunks * j.cols + c;
-  float a = 0.f;
-  for (int k = 0; k < nchunks; ++k) a += p1[(int64_t)k * j.cols];
-  grads[(int64_t)r * ps + j.out_off + c] = a;
-  if (j.mode == 1) {
-    const float* p2 = p1 + (int64_t)n_replicas * nchunks * j.cols;
-    float b = 0.f;
-    for (int k = 0; k < nchunks; ++k) b += p2[(int64_t)k * j.cols];
-    grads[(int64_t)r * ps + j.out2_off + c] = b;
-  }
+  grads[(int64_t)r * ps + j.out_off + c] = total(p1);
+  if (j.mode == 1) grads[(int64_t)r * ps + j.out2_off + c] = total(p1 + (int64_t)n_replicas * nchunks * j.cols);
 }
 
 // Column reductions over the M rows: block = 64 columns x 16 row phases; thread (c, q) adds
