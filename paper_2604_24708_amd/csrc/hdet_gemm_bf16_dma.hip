@@ -269,10 +269,10 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
   float* stg = reinterpret_cast<float*>(S) + wave * (32 * EP);
   const int lr = lane / LPR, lc = (lane % LPR) * 4;
   constexpr bool kBias = EPI == HDET_EPI_BIAS_RELU_BF16 || EPI == HDET_EPI_BIAS_F32 || EPI == HDET_EPI_BIAS_BF16 ||
-                         EPI == HDET_EPI_BIAS_GELU_BF16;
+                         EPI == HDET_EPI_BIAS_GELU_BF16 || EPI == HDET_EPI_BIAS_RESID_BF16;
   // the second operand of the gating epilogues (the activations a ReLU or GELU gradient looks at) is
   // fetched one strip ahead, so that its latency hides behind the previous strip's pass through LDS
-  constexpr bool kGate = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16;
+  constexpr bool kGate = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16 || EPI == HDET_EPI_BIAS_RESID_BF16;
   constexpr int NIT = 32 / RPI, NSTRIP = (WNT / JG) * WMT;
   us4 gate[2][NIT];
   auto fetch_gate = [&](int strip, us4 (&dst)[NIT]) {
@@ -319,6 +319,11 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
             const us4 a = gate[strip & 1][it];
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = bf2f(a[q]) > 0.f ? v[q] : 0.f;
+          }
+          if (EPI == HDET_EPI_BIAS_RESID_BF16) {  // the layer's output is rounded as the unfused path stores it, then added
+            const us4 a = gate[strip & 1][it];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = bf2f(a[q]) + bf2f(f2bf(v[q]));
           }
           if (EPI == HDET_EPI_GELUGRAD_BF16) {  // the incoming gradient is rounded as the unfused path stores it
             const us4 a = gate[strip & 1][it];
@@ -379,7 +384,7 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
 bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi) {
   const bool f32_out = epi == HDET_EPI_F32 || epi == HDET_EPI_BIAS_F32;
   const bool has_bias = epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_BIAS_RELU_BF16 ||
-                        epi == HDET_EPI_BIAS_GELU_BF16;
+                        epi == HDET_EPI_BIAS_GELU_BF16 || epi == HDET_EPI_BIAS_RESID_BF16;
   if (g.m < 1 || g.n < 1 || g.k < 1) return false;
   // a chunk is 8 elements along the operand's contiguous axis: k if k-major, else the row axis
   if (!chunk_regular(g.a, g.lda, g.a_s, a_kmajor ? g.k : g.m)) return false;
@@ -394,14 +399,14 @@ bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kma
   if ((g.ldc & 3) || ((g.c_s[0] | g.c_s[1] | g.c_s[2]) & 3) || (g.n & 3)) return false;
   if (reinterpret_cast<uintptr_t>(g.c) & (f32_out ? 15 : 7)) return false;
   if (has_bias && ((g.bias_bs & 3) || (reinterpret_cast<uintptr_t>(g.bias) & 15))) return false;
-  if ((epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_GELUGRAD_BF16) &&
+  if ((epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_GELUGRAD_BF16 || epi == HDET_EPI_BIAS_RESID_BF16) &&
       (!g.mask || (g.mask_ld & 3) || (g.mask_bs & 3) || (reinterpret_cast<uintptr_t>(g.mask) & 7)))
     return false;
   if (epi == HDET_EPI_BIAS_GELU_BF16 && (!g.c2 || (reinterpret_cast<uintptr_t>(g.c2) & 7))) return false;
   // instantiated combinations: what the MLP and the transformer use
   if (a_kmajor && b_kmajor)
     return epi == HDET_EPI_BIAS_RELU_BF16 || epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_F32 ||
-           epi == HDET_EPI_BIAS_GELU_BF16;
+           epi == HDET_EPI_BIAS_GELU_BF16 || epi == HDET_EPI_BIAS_RESID_BF16;
   if (a_kmajor && !b_kmajor) return epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_BF16 || epi == HDET_EPI_GELUGRAD_BF16;
   if (!a_kmajor && !b_kmajor) return epi == HDET_EPI_F32 || epi == HDET_EPI_BF16;
   return false;
@@ -419,6 +424,7 @@ hipError_t hdet_launch_bgemm_dma(const hdet_bgemm_args& g_in, bool a_kmajor, boo
       case HDET_EPI_BIAS_F32: return launch_shape<true, true, HDET_EPI_BIAS_F32>(g, batch, s);
       case HDET_EPI_BIAS_BF16: return launch_shape<true, true, HDET_EPI_BIAS_BF16>(g, batch, s);
       case HDET_EPI_BIAS_GELU_BF16: return launch_shape<true, true, HDET_EPI_BIAS_GELU_BF16>(g, batch, s);
+      case HDET_EPI_BIAS_RESID_BF16: return launch_shape<true, true, HDET_EPI_BIAS_RESID_BF16>(g, batch, s);
       default: return launch_shape<true, true, HDET_EPI_F32>(g, batch, s);
     }
   }

@@ -138,7 +138,8 @@ enum { HDET_EPI_F32 = 0, HDET_EPI_BIAS_F32 = 1, HDET_EPI_BIAS_RELU_BF16 = 2, HDE
        HDET_EPI_BF16 = 4, HDET_EPI_BIAS_BF16 = 5,
        // LDS-direct kernel only (the caller checks hdet_bgemm_dma_eligible first):
        HDET_EPI_BIAS_GELU_BF16 = 6,   // c = bf16(acc + bias), c2 = bf16(gelu(c)): pre-activation and activation
-       HDET_EPI_GELUGRAD_BF16 = 7 };  // c = bf16(bf16(acc) * gelu'(mask)): gradient through the GELU at pre-activation `mask`
+       HDET_EPI_GELUGRAD_BF16 = 7,    // c = bf16(bf16(acc) * gelu'(mask)): gradient through the GELU at pre-activation `mask`
+       HDET_EPI_BIAS_RESID_BF16 = 8 }; // c = bf16(mask + bf16(acc + bias)): a Linear layer added to its residual stream `mask`
 
 struct hdet_bgemm_args {
   const uint16_t* a;       // bf16

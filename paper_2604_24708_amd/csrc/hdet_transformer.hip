@@ -1053,7 +1053,10 @@ struct mat { const void* p; int64_t ld; int64_t s[3]; };
 // (written to c) and f = gelu(z) goes to gelu_out; gelu_pre: the product is the gradient at f and
 // c receives the gradient at z = that * gelu'(gelu_pre).  `*fused` tells whether the GEMM took
 // them (it does on the LDS-direct path); otherwise the caller runs the element-wise kernel.
-struct gelu_fusion { void* gelu_out; const void* gelu_pre; bool* fused; };
+// What a GEMM may fold into its epilogue when the fast bf16 kernel takes the product: the GELU after
+// it (second output), the GELU gradient at the pre-activation, or the residual stream it is added to
+// (the sum then goes to resid_out instead of c).  *fused tells the caller whether it happened.
+struct gelu_fusion { void* gelu_out; const void* gelu_pre; bool* fused; const void* resid; void* resid_out; };
 
 template <typename T>
 hipError_t gemm(const hdet_tf_plan* pl, int form, mat A, mat B, void* c, int64_t ldc, const int64_t* c_s, bool act_out,
@@ -1073,8 +1076,9 @@ hipError_t gemm(const hdet_tf_plan* pl, int form, mat A, mat B, void* c, int64_t
       hdet_bgemm_args f = g;
       int fepi;
       if (gf->gelu_out) { f.c2 = gf->gelu_out; fepi = HDET_EPI_BIAS_GELU_BF16; }
+      else if (gf->resid) { f.c = gf->resid_out; f.mask = (const uint16_t*)gf->resid; f.mask_ld = ldc; f.mask_bs = c_s[0]; fepi = HDET_EPI_BIAS_RESID_BF16; }
       else { f.mask = (const uint16_t*)gf->gelu_pre; f.mask_ld = ldc; f.mask_bs = c_s[0]; fepi = HDET_EPI_GELUGRAD_BF16; }
-      if ((fepi != HDET_EPI_BIAS_GELU_BF16 || bias) && hdet_bgemm_dma_eligible(f, form != TN, form == NT, fepi)) {
+      if ((fepi == HDET_EPI_GELUGRAD_BF16 || bias) && hdet_bgemm_dma_eligible(f, form != TN, form == NT, fepi)) {
         *gf->fused = true;
         return hdet_launch_bgemm(f, form != TN, form == NT, fepi, batch, s);
       }
@@ -1154,20 +1158,30 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
         TF_CHECK(gemm<T>(p, NN, head_sq(p->p[l]), qkv_part(p->qkv[l], 2), p->a[l], d, ac.s, true, S, dh, S, B, nh, nullptr, 0, s));
       }
     }
-    TF_CHECK(gemm<T>(p, NT, act(p->a[l], d), wt(o.w_o, d), p->tmp_d, d, act_d, true, M, d, d, 1, 1, theta + o.b_o, ps, s));
-    da.site = 2 * l;
-    hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_in[l], (const T*)p->tmp_d, (T*)p->x_mid[l], nd, da);
+    {   // x_mid = x_in + drop(a W_o^T + b_o); without a dropout channel the sum is the GEMM's epilogue
+      bool fused = false;
+      const gelu_fusion rf = {nullptr, nullptr, &fused, p->x_in[l], p->x_mid[l]};
+      TF_CHECK(gemm<T>(p, NT, act(p->a[l], d), wt(o.w_o, d), p->tmp_d, d, act_d, true, M, d, d, 1, 1, theta + o.b_o, ps, s, drop ? nullptr : &rf));
+      da.site = 2 * l;
+      if (!fused)
+        hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_in[l], (const T*)p->tmp_d, (T*)p->x_mid[l], nd, da);
+    }
     launch_ln_fwd<T>(p, p->x_mid[l], o.ln2_g, o.ln2_b, p->h2[l], p->st2_mean[l], p->st2_rstd[l], s);
     {
       bool fused = false;
-      const gelu_fusion gf = {p->f[l], nullptr, &fused};
+      const gelu_fusion gf = {p->f[l], nullptr, &fused, nullptr, nullptr};
       TF_CHECK(gemm<T>(p, NT, act(p->h2[l], d), wt(o.w_1, d), p->z[l], ff, act_ff, true, M, ff, d, 1, 1, theta + o.b_1, ps, s, &gf));
       if (!fused)
         hipLaunchKernelGGL(gelu_fwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->z[l], (T*)p->f[l], (int64_t)N * nff);
     }
-    TF_CHECK(gemm<T>(p, NT, act(p->f[l], ff), wt(o.w_2, ff), p->tmp_d, d, act_d, true, M, d, ff, 1, 1, theta + o.b_2, ps, s));
-    da.site = 2 * l + 1;
-    hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_mid[l], (const T*)p->tmp_d, (T*)p->x_in[l + 1], nd, da);
+    {
+      bool fused = false;
+      const gelu_fusion rf = {nullptr, nullptr, &fused, p->x_mid[l], p->x_in[l + 1]};
+      TF_CHECK(gemm<T>(p, NT, act(p->f[l], ff), wt(o.w_2, ff), p->tmp_d, d, act_d, true, M, d, ff, 1, 1, theta + o.b_2, ps, s, drop ? nullptr : &rf));
+      da.site = 2 * l + 1;
+      if (!fused)
+        hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_mid[l], (const T*)p->tmp_d, (T*)p->x_in[l + 1], nd, da);
+    }
   }
   launch_ln_fwd<T>(p, p->x_in[L], p->lnf_g, p->lnf_b, p->hf, p->stf_mean, p->stf_rstd, s);
   TF_CHECK(gemm<T>(p, NT, act(p->hf, d), wt(p->w_head, d), p->logits, V, act_v, false, M, V, d, 1, 1, theta + p->b_head, ps, s));
@@ -1202,7 +1216,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(colsum(dy, d, o.b_2));
     {
       bool fused = false;
-      const gelu_fusion gf = {nullptr, p->z[l], &fused};
+      const gelu_fusion gf = {nullptr, p->z[l], &fused, nullptr, nullptr};
       TF_CHECK(gemm<T>(p, NN, act(dy, d), wt(o.w_2, ff), p->dff, ff, act_ff, true, M, ff, d, 1, 1, nullptr, 0, s, &gf));
       if (!fused)
         hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->dff, (const T*)p->z[l], (T*)p->dff, (int64_t)N * nff);
