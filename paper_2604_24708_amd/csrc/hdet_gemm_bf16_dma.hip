@@ -269,10 +269,11 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
   float* stg = reinterpret_cast<float*>(S) + wave * (32 * EP);
   const int lr = lane / LPR, lc = (lane % LPR) * 4;
   constexpr bool kBias = EPI == HDET_EPI_BIAS_RELU_BF16 || EPI == HDET_EPI_BIAS_F32 || EPI == HDET_EPI_BIAS_BF16 ||
-                         EPI == HDET_EPI_BIAS_GELU_BF16 || EPI == HDET_EPI_BIAS_RESID_BF16;
+                         EPI == HDET_EPI_BIAS_GELU_BF16 || EPI == HDET_EPI_BIAS_RESID_BF16 || EPI == HDET_EPI_BIAS_DROP_RESID_BF16;
   // the second operand of the gating epilogues (the activations a ReLU or GELU gradient looks at) is
   // fetched one strip ahead, so that its latency hides behind the previous strip's pass through LDS
-  constexpr bool kGate = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16 || EPI == HDET_EPI_BIAS_RESID_BF16;
+  constexpr bool kGate = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16 || EPI == HDET_EPI_BIAS_RESID_BF16 ||
+                         EPI == HDET_EPI_BIAS_DROP_RESID_BF16;
   constexpr int NIT = 32 / RPI, NSTRIP = (WNT / JG) * WMT;
   us4 gate[2][NIT];
   auto fetch_gate = [&](int strip, us4 (&dst)[NIT]) {
@@ -285,6 +286,13 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
         dst[it] = *reinterpret_cast<const us4*>(g.mask + (int64_t)z * g.mask_bs + (int64_t)row * g.mask_ld + col);
     }
   };
+  uint32_t drop_thresh = 0u;
+  float drop_scale = 1.f;
+  if (EPI == HDET_EPI_BIAS_DROP_RESID_BF16) {
+    const float p = (float)hdet_channel_value(g.drop_ctrl, g.drop_channel, z, 0.0);
+    drop_thresh = (uint32_t)floor((double)p * 4294967296.0);
+    drop_scale = 1.f / (1.f - p);
+  }
   if (kGate) fetch_gate(0, gate[0]);
 #pragma unroll
   for (int jg = 0; jg < WNT / JG; ++jg) {
@@ -324,6 +332,19 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
             const us4 a = gate[strip & 1][it];
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = bf2f(a[q]) + bf2f(f2bf(v[q]));
+          }
+          if (EPI == HDET_EPI_BIAS_DROP_RESID_BF16) {   // ... dropped out (one Philox block per 4 elements), then added
+            const us4 a = gate[strip & 1][it];
+            hdet_philox4 w = {{0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu}};
+            if (drop_thresh != 0u)
+              w = hdet_philox4x32_10((uint32_t)(((int64_t)row * g.ldc + col) >> 2), g.drop_step, (uint32_t)z * 65536u + g.drop_site,
+                                     g.drop_stream, g.drop_seed_lo, g.drop_seed_hi);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              float y = bf2f(f2bf(v[q]));
+              if (drop_thresh != 0u) y = w.x[q] >= drop_thresh ? y * drop_scale : 0.f;
+              v[q] = bf2f(a[q]) + y;
+            }
           }
           if (EPI == HDET_EPI_GELUGRAD_BF16) {  // the incoming gradient is rounded as the unfused path stores it
             const us4 a = gate[strip & 1][it];
@@ -384,7 +405,7 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
 bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi) {
   const bool f32_out = epi == HDET_EPI_F32 || epi == HDET_EPI_BIAS_F32;
   const bool has_bias = epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_BIAS_RELU_BF16 ||
-                        epi == HDET_EPI_BIAS_GELU_BF16 || epi == HDET_EPI_BIAS_RESID_BF16;
+                        epi == HDET_EPI_BIAS_GELU_BF16 || epi == HDET_EPI_BIAS_RESID_BF16 || epi == HDET_EPI_BIAS_DROP_RESID_BF16;
   if (g.m < 1 || g.n < 1 || g.k < 1) return false;
   // a chunk is 8 elements along the operand's contiguous axis: k if k-major, else the row axis
   if (!chunk_regular(g.a, g.lda, g.a_s, a_kmajor ? g.k : g.m)) return false;
@@ -399,14 +420,16 @@ bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kma
   if ((g.ldc & 3) || ((g.c_s[0] | g.c_s[1] | g.c_s[2]) & 3) || (g.n & 3)) return false;
   if (reinterpret_cast<uintptr_t>(g.c) & (f32_out ? 15 : 7)) return false;
   if (has_bias && ((g.bias_bs & 3) || (reinterpret_cast<uintptr_t>(g.bias) & 15))) return false;
-  if ((epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_GELUGRAD_BF16 || epi == HDET_EPI_BIAS_RESID_BF16) &&
+  if (epi == HDET_EPI_BIAS_DROP_RESID_BF16 && (!g.drop_ctrl || g.drop_channel < 0 || g.n1 * g.n2 != 1 || g.c_s[0] >= ((int64_t)1 << 34)))
+    return false;        // the replica is the batch index; the element counter has 32 bits
+  if ((epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_GELUGRAD_BF16 || epi == HDET_EPI_BIAS_RESID_BF16 || epi == HDET_EPI_BIAS_DROP_RESID_BF16) &&
       (!g.mask || (g.mask_ld & 3) || (g.mask_bs & 3) || (reinterpret_cast<uintptr_t>(g.mask) & 7)))
     return false;
   if (epi == HDET_EPI_BIAS_GELU_BF16 && (!g.c2 || (reinterpret_cast<uintptr_t>(g.c2) & 7))) return false;
   // instantiated combinations: what the MLP and the transformer use
   if (a_kmajor && b_kmajor)
     return epi == HDET_EPI_BIAS_RELU_BF16 || epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_F32 ||
-           epi == HDET_EPI_BIAS_GELU_BF16 || epi == HDET_EPI_BIAS_RESID_BF16;
+           epi == HDET_EPI_BIAS_GELU_BF16 || epi == HDET_EPI_BIAS_RESID_BF16 || epi == HDET_EPI_BIAS_DROP_RESID_BF16;
   if (a_kmajor && !b_kmajor) return epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_BF16 || epi == HDET_EPI_GELUGRAD_BF16;
   if (!a_kmajor && !b_kmajor) return epi == HDET_EPI_F32 || epi == HDET_EPI_BF16;
   return false;
@@ -425,6 +448,7 @@ hipError_t hdet_launch_bgemm_dma(const hdet_bgemm_args& g_in, bool a_kmajor, boo
       case HDET_EPI_BIAS_BF16: return launch_shape<true, true, HDET_EPI_BIAS_BF16>(g, batch, s);
       case HDET_EPI_BIAS_GELU_BF16: return launch_shape<true, true, HDET_EPI_BIAS_GELU_BF16>(g, batch, s);
       case HDET_EPI_BIAS_RESID_BF16: return launch_shape<true, true, HDET_EPI_BIAS_RESID_BF16>(g, batch, s);
+      case HDET_EPI_BIAS_DROP_RESID_BF16: return launch_shape<true, true, HDET_EPI_BIAS_DROP_RESID_BF16>(g, batch, s);
       default: return launch_shape<true, true, HDET_EPI_F32>(g, batch, s);
     }
   }

@@ -139,7 +139,8 @@ enum { HDET_EPI_F32 = 0, HDET_EPI_BIAS_F32 = 1, HDET_EPI_BIAS_RELU_BF16 = 2, HDE
        // LDS-direct kernel only (the caller checks hdet_bgemm_dma_eligible first):
        HDET_EPI_BIAS_GELU_BF16 = 6,   // c = bf16(acc + bias), c2 = bf16(gelu(c)): pre-activation and activation
        HDET_EPI_GELUGRAD_BF16 = 7,    // c = bf16(bf16(acc) * gelu'(mask)): gradient through the GELU at pre-activation `mask`
-       HDET_EPI_BIAS_RESID_BF16 = 8 }; // c = bf16(mask + bf16(acc + bias)): a Linear layer added to its residual stream `mask`
+       HDET_EPI_BIAS_RESID_BF16 = 8,  // c = bf16(mask + bf16(acc + bias)): a Linear layer added to its residual stream `mask`
+       HDET_EPI_BIAS_DROP_RESID_BF16 = 9 };   // the same with dropout of the layer's output before the sum
 
 struct hdet_bgemm_args {
   const uint16_t* a;       // bf16
@@ -152,6 +153,11 @@ struct hdet_bgemm_args {
   int64_t a_s[3], b_s[3], c_s[3];      // batch strides in elements
   const float* bias; int64_t bias_bs;  // bias[z0*bias_bs + n]
   const uint16_t* mask; int64_t mask_ld, mask_bs;   // bf16 activations gating the gradient (per replica)
+  // HDET_EPI_BIAS_DROP_RESID_BF16: inverted dropout of the layer's output at the replica's rate (value of
+  // channel drop_channel), masks from Philox-4x32-10 with counter (element / 4, drop_step,
+  // replica * 65536 + drop_site, drop_stream) and key drop_seed; element = row * ldc + column
+  const hdet_ctrl* drop_ctrl; int drop_channel;
+  uint32_t drop_step, drop_site, drop_stream, drop_seed_lo, drop_seed_hi;
 };
 
 // a_kmajor: A(m,k) at a[m*lda + k], else at a[k*lda + m]; b_kmajor: B(k,n) at b[n*ldb + k], else
