@@ -338,6 +338,23 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_vec_kernel(const T* dy, const T
   }
 }
 
+// Dropout of a residual branch.  Element e of the replica's [M][d] tensor is kept iff word
+// (e mod 4) of philox(counter = (e div 4, step, replica * 65536 + site, kDropStream), key = seed)
+// is >= floor(p * 2^32).  A thread handles the four elements of one Philox block.
+struct drop_args {
+  const hdet_ctrl* ctrl;
+  int channel;          // dropout channel index or -1 (no dropout)
+  uint32_t step, seed_lo, seed_hi;
+  int site;
+};
+
+__device__ __forceinline__ void drop_setup(const drop_args& da, int r, uint32_t* thresh, float* keep_scale) {
+  float p = 0.f;
+  if (da.channel >= 0) p = (float)hdet_channel_value(da.ctrl, da.channel, r, 0.0);
+  *thresh = (uint32_t)floor((double)p * 4294967296.0);
+  *keep_scale = 1.f / (1.f - p);
+}
+
 // LayerNorm backward with the parameter gradients' stage 1 fused in: block = kLnRows consecutive
 // rows of a replica, wavefront w takes rows w, w+4, ... (one or two in flight), writes dx like the
 // kernel above and keeps, per column it holds, sum dy xhat and sum dy over its rows in ascending
@@ -347,8 +364,11 @@ constexpr int kLnRows = 32;
 template <typename T, int NCH>
 __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
                                                            const float* theta, int64_t ps, int64_t g_off, int M, int d,
-                                                           const T* resid, T* dx, float* part) {
+                                                           const T* resid, T* dx, float* part, T* dropped, const drop_args da) {
   __shared__ float l1[4][NCH * 512], l2[4][NCH * 512];
+  uint32_t thresh = 0u;
+  float ks = 1.f;
+  if (dropped) drop_setup(da, blockIdx.y, &thresh, &ks);
   const int r = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const float* g = theta + (int64_t)r * ps + g_off;
   const int d8 = d >> 3;
@@ -416,6 +436,22 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
             for (int j = 0; j < 8; ++j) o.v[j] += rv[i].v[j];
           }
           hdet_st8(dx + base + 8 * ch, o);
+          if (dropped) {      // the gradient through the dropout of the branch below, from dx as it is stored
+            const int64_t e = (int64_t)row * d + 8 * ch;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              hdet_philox4 wd = {{0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu}};
+              if (thresh != 0u)
+                wd = hdet_philox4x32_10((uint32_t)((e >> 2) + h), da.step, (uint32_t)r * 65536u + (uint32_t)da.site, kDropStream,
+                                        da.seed_lo, da.seed_hi);
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const float stored = sizeof(T) == 2 ? __uint_as_float(hdet_bf16_bits(o.v[4 * h + j]) << 16) : o.v[4 * h + j];
+                o.v[4 * h + j] = thresh == 0u ? stored : (wd.x[j] >= thresh ? stored * ks : 0.f);
+              }
+            }
+            hdet_st8(dropped + base + 8 * ch, o);
+          }
         }
       }
     }
@@ -705,23 +741,6 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* df, const T* z, 
   if (tid < (n & 7)) hdet_st(dz + 8 * n8 + tid, hdet_ld(df + 8 * n8 + tid) * hdet_gelu_tanh_grad(hdet_ld(z + 8 * n8 + tid)));
 }
 
-// Dropout of a residual branch.  Element e of the replica's [M][d] tensor is kept iff word
-// (e mod 4) of philox(counter = (e div 4, step, replica * 65536 + site, kDropStream), key = seed)
-// is >= floor(p * 2^32).  A thread handles the four elements of one Philox block.
-struct drop_args {
-  const hdet_ctrl* ctrl;
-  int channel;          // dropout channel index or -1 (no dropout)
-  uint32_t step, seed_lo, seed_hi;
-  int site;
-};
-
-__device__ __forceinline__ void drop_setup(const drop_args& da, int r, uint32_t* thresh, float* keep_scale) {
-  float p = 0.f;
-  if (da.channel >= 0) p = (float)hdet_channel_value(da.ctrl, da.channel, r, 0.0);
-  *thresh = (uint32_t)floor((double)p * 4294967296.0);
-  *keep_scale = 1.f / (1.f - p);
-}
-
 // out = x + drop(branch)            (ADD)        forward residual add
 // out = drop'(branch) = branch * keep / (1-p)    backward through the dropout
 template <typename T, bool ADD>
@@ -959,7 +978,8 @@ void launch_ln_fwd(const hdet_tf_plan* p, const void* x, int64_t g_off, int64_t 
 // dx of a LayerNorm (plus `resid`); true when the launch also produced stage 1 of the parameter gradients
 template <typename T>
 bool launch_ln_bwd_dx(const hdet_tf_plan* p, const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off,
-                      const void* resid, void* dx, hipStream_t s) {
+                      const void* resid, void* dx, hipStream_t s, void* dropped = nullptr, const drop_args* da = nullptr,
+                      bool* dropped_done = nullptr) {
   const int M = p->M, d = p->d;
   const int64_t ps = p->buf.plane_stride;
   const float* theta = p->buf.params_dev;
@@ -971,9 +991,12 @@ bool launch_ln_bwd_dx(const hdet_tf_plan* p, const void* dy, const void* x, cons
     const int nch = (d / 8 + 63) / 64;
     if (job) {
       const dim3 grid(job->nchunks, p->N);
-#define CALL(K) hipLaunchKernelGGL((ln_bwd_fused_kernel<T, K>), grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx, p->part + job->part_off)
+      const drop_args none = {nullptr, -1, 0, 0, 0, 0};
+      const bool with_drop = dropped && da;
+#define CALL(K) hipLaunchKernelGGL((ln_bwd_fused_kernel<T, K>), grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx, p->part + job->part_off, with_drop ? (T*)dropped : (T*)nullptr, with_drop ? *da : none)
       if (nch == 1) CALL(1); else CALL(2);
 #undef CALL
+      if (dropped_done) *dropped_done = with_drop;
       return true;
     }
     const dim3 grid((M + 3) / 4, p->N);
@@ -1211,14 +1234,21 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   TF_CHECK(wgrad(p->dlogits, V, p->hf, d, p->w_head));
   TF_CHECK(colsum(p->dlogits, V, p->b_head));
   TF_CHECK(gemm<T>(p, NN, act(p->dlogits, V), wt(p->w_head, d), p->dtmp, d, act_d, true, M, d, V, 1, 1, nullptr, 0, s));
-  if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, nullptr, p->dxa, s)) TF_CHECK(ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b));
+  // With a dropout channel, the gradient that enters a residual branch is the stream's gradient passed
+  // through that branch's dropout; the LayerNorm backward kernel that produces the stream's gradient
+  // writes it as a second output where it can (dropped_done), else a separate pass does.
+  bool dropped_done = false;
+  da.site = 2 * (L - 1) + 1;
+  if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, nullptr, p->dxa, s, drop ? p->dtmp2 : nullptr, &da, &dropped_done))
+    TF_CHECK(ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b));
   for (int l = L - 1; l >= 0; --l) {
     const tf_block_off& o = p->blk[l];
     // MLP branch: x_out = x_mid + drop(y)
     const void* dy = p->dxa;
     if (drop) {
       da.site = 2 * l + 1;
-      hipLaunchKernelGGL((dropout_kernel<T, false>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)nullptr, (const T*)p->dxa, (T*)p->dtmp2, nd, da);
+      if (!dropped_done)
+        hipLaunchKernelGGL((dropout_kernel<T, false>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)nullptr, (const T*)p->dxa, (T*)p->dtmp2, nd, da);
       dy = p->dtmp2;
     }
     TF_CHECK(wgrad(dy, d, p->f[l], ff, o.w_2));
@@ -1233,12 +1263,15 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(wgrad(p->dff, ff, p->h2[l], d, o.w_1));
     TF_CHECK(colsum(p->dff, ff, o.b_1));
     TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
-    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, p->dxa, p->dxb, s)) TF_CHECK(ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b));
+    dropped_done = false;
+    da.site = 2 * l;
+    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, p->dxa, p->dxb, s, drop ? p->dtmp2 : nullptr, &da, &dropped_done))
+      TF_CHECK(ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b));
     // attention branch: x_mid = x_in + drop(o)
     const void* dob = p->dxb;
     if (drop) {
-      da.site = 2 * l;
-      hipLaunchKernelGGL((dropout_kernel<T, false>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)nullptr, (const T*)p->dxb, (T*)p->dtmp2, nd, da);
+      if (!dropped_done)
+        hipLaunchKernelGGL((dropout_kernel<T, false>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)nullptr, (const T*)p->dxb, (T*)p->dtmp2, nd, da);
       dob = p->dtmp2;
     }
     TF_CHECK(wgrad(dob, d, p->a[l], d, o.w_o));
@@ -1262,7 +1295,10 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(wgrad(p->dqkv, 3 * d, p->h1[l], d, o.w_qkv));
     TF_CHECK(colsum(p->dqkv, 3 * d, o.b_qkv));
     TF_CHECK(gemm<T>(p, NN, act(p->dqkv, 3 * d), wt(o.w_qkv, d), p->dtmp, d, act_d, true, M, d, 3 * d, 1, 1, nullptr, 0, s));
-    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s)) TF_CHECK(ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b));
+    dropped_done = false;
+    da.site = 2 * (l - 1) + 1;                     // the MLP branch of the block below
+    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s, drop && l > 0 ? p->dtmp2 : nullptr, &da, &dropped_done))
+      TF_CHECK(ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b));
   }
   hipLaunchKernelGGL(zero_kernel, dim3(grid_for((int64_t)V * d), N), dim3(256), 0, s, grads, ps, p->tok, (int64_t)V * d);
   if (M <= 16384 && d % 8 == 0 && d <= 2048 && p->tok % 4 == 0 && ps % 4 == 0) {
