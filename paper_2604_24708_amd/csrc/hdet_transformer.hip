@@ -364,7 +364,8 @@ constexpr int kLnRows = 32;
 template <typename T, int NCH>
 __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
                                                            const float* theta, int64_t ps, int64_t g_off, int M, int d,
-                                                           const T* resid, T* dx, float* part, T* dropped, const drop_args da) {
+                                                           const T* resid, T* dx, float* part, T* dropped, const drop_args da,
+                                                           float* part_out) {
   __shared__ float l1[4][NCH * 512], l2[4][NCH * 512];
   uint32_t thresh = 0u;
   float ks = 1.f;
@@ -372,12 +373,12 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
   const int r = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const float* g = theta + (int64_t)r * ps + g_off;
   const int d8 = d >> 3;
-  hdet_f8 gv[NCH], ag[NCH], ab[NCH];
+  hdet_f8 gv[NCH], ag[NCH], ab[NCH], ao[NCH];     // ao: column sums of what the next branch receives (dx, or dx dropped out), as stored
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
     const int ch = lane + 64 * i;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { ag[i].v[j] = 0.f; ab[i].v[j] = 0.f; gv[i].v[j] = 0.f; }
+    for (int j = 0; j < 8; ++j) { ag[i].v[j] = 0.f; ab[i].v[j] = 0.f; ao[i].v[j] = 0.f; gv[i].v[j] = 0.f; }
     if (ch < d8) gv[i] = hdet_ld8(g + 8 * ch);
   }
   const int row0 = blockIdx.x * kLnRows + w;
@@ -436,6 +437,10 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
             for (int j = 0; j < 8; ++j) o.v[j] += rv[i].v[j];
           }
           hdet_st8(dx + base + 8 * ch, o);
+          if (part_out && !dropped) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ao[i].v[j] += sizeof(T) == 2 ? __uint_as_float(hdet_bf16_bits(o.v[j]) << 16) : o.v[j];
+          }
           if (dropped) {      // the gradient through the dropout of the branch below, from dx as it is stored
             const int64_t e = (int64_t)row * d + 8 * ch;
 #pragma unroll
@@ -451,6 +456,10 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
               }
             }
             hdet_st8(dropped + base + 8 * ch, o);
+            if (part_out) {
+#pragma unroll
+              for (int j = 0; j < 8; ++j) ao[i].v[j] += sizeof(T) == 2 ? __uint_as_float(hdet_bf16_bits(o.v[j]) << 16) : o.v[j];
+            }
           }
         }
       }
@@ -466,6 +475,15 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
   for (int c = threadIdx.x; c < d; c += 256) {
     part[pbase + c] = ((l1[0][c] + l1[1][c]) + l1[2][c]) + l1[3][c];
     part[second + pbase + c] = ((l2[0][c] + l2[1][c]) + l2[2][c]) + l2[3][c];
+  }
+  if (part_out) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) l1[w][(lane + 64 * i) * 8 + j] = ao[i].v[j];
+    __syncthreads();
+    for (int c = threadIdx.x; c < d; c += 256) part_out[pbase + c] = ((l1[0][c] + l1[1][c]) + l1[2][c]) + l1[3][c];
   }
 }
 
@@ -843,7 +861,7 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   // per block: biases of the four Linear layers (3d + d + ff + d columns) and two LayerNorms (2 x 2d); then final LayerNorm, head bias
   // (the LayerNorm pairs in chunks of kLnRows rows when their backward kernel produces them itself)
   const size_t ln_chunks = (M + kLnRows - 1) / kLnRows;
-  p->part = (float*)take(N * (p->nrc * ((size_t)L * (5 * d + ff) + V) + ln_chunks * 2 * d * (2 * (size_t)L + 1)) * 4);
+  p->part = (float*)take(N * (p->nrc * ((size_t)L * (3 * d + ff) + V) + ln_chunks * (2 * d * (2 * (size_t)L + 1) + 2 * d * (size_t)L)) * 4);
   p->jobs_dev = (colsum_job*)take((6 * (size_t)L + 2) * sizeof(colsum_job));
   return off;
 }
@@ -920,9 +938,12 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
   // stage 2 of the column reductions: one job per bias vector and LayerNorm parameter pair
   int64_t part_off = 0;
   int first_block = 0;
-  auto add_job = [&](int cols, int mode, int64_t out_off, int64_t out2_off) {
+  // producer_g: for the bias of an output projection, the gain offset of the LayerNorm whose backward kernel
+  // produces that bias gradient's input (and, when it is of the fused kind, stage 1 of its column sum); -1 otherwise
+  auto add_job = [&](int cols, int mode, int64_t out_off, int64_t out2_off, int64_t producer_g = -1) {
     if (cols % 8 != 0) return;                       // such widths take the single-stage kernel
-    const int nchunks = mode == 1 && hdet_tf_ln_fused(p, out_off) ? (p->M + kLnRows - 1) / kLnRows : p->nrc;
+    const bool by_ln = (mode == 1 && hdet_tf_ln_fused(p, out_off)) || (producer_g >= 0 && hdet_tf_ln_fused(p, producer_g));
+    const int nchunks = by_ln ? (p->M + kLnRows - 1) / kLnRows : p->nrc;
     colsum_job j = {part_off, out_off, out2_off, cols, mode, first_block, nchunks};
     p->jobs.push_back(j);
     part_off += (int64_t)(mode == 1 ? 2 : 1) * p->N * nchunks * cols;
@@ -932,10 +953,10 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
   add_job((int)d, 1, p->lnf_g, p->lnf_b);
   for (int l = 0; l < p->L; ++l) {
     const tf_block_off& b = p->blk[l];
-    add_job((int)d, 0, b.b_2, 0);
+    add_job((int)d, 0, b.b_2, 0, l + 1 < p->L ? p->blk[l + 1].ln1_g : p->lnf_g);
     add_job((int)ff, 0, b.b_1, 0);
     add_job((int)d, 1, b.ln2_g, b.ln2_b);
-    add_job((int)d, 0, b.b_o, 0);
+    add_job((int)d, 0, b.b_o, 0, b.ln2_g);
     add_job(3 * (int)d, 0, b.b_qkv, 0);
     add_job((int)d, 1, b.ln1_g, b.ln1_b);
   }
@@ -979,7 +1000,7 @@ void launch_ln_fwd(const hdet_tf_plan* p, const void* x, int64_t g_off, int64_t 
 template <typename T>
 bool launch_ln_bwd_dx(const hdet_tf_plan* p, const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off,
                       const void* resid, void* dx, hipStream_t s, void* dropped = nullptr, const drop_args* da = nullptr,
-                      bool* dropped_done = nullptr) {
+                      bool* dropped_done = nullptr, int64_t next_bias_off = -1, bool* bias_done = nullptr) {
   const int M = p->M, d = p->d;
   const int64_t ps = p->buf.plane_stride;
   const float* theta = p->buf.params_dev;
@@ -993,7 +1014,13 @@ bool launch_ln_bwd_dx(const hdet_tf_plan* p, const void* dy, const void* x, cons
       const dim3 grid(job->nchunks, p->N);
       const drop_args none = {nullptr, -1, 0, 0, 0, 0};
       const bool with_drop = dropped && da;
-#define CALL(K) hipLaunchKernelGGL((ln_bwd_fused_kernel<T, K>), grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx, p->part + job->part_off, with_drop ? (T*)dropped : (T*)nullptr, with_drop ? *da : none)
+      // stage 1 of the bias gradient of the output projection that receives this kernel's output
+      float* part_out = nullptr;
+      if (next_bias_off >= 0)
+        for (const colsum_job& j : p->jobs)
+          if (j.out_off == next_bias_off && j.mode == 0 && j.cols == d && j.nchunks == job->nchunks) { part_out = p->part + j.part_off; break; }
+      if (bias_done) *bias_done = part_out != nullptr;
+#define CALL(K) hipLaunchKernelGGL((ln_bwd_fused_kernel<T, K>), grid, dim3(256), 0, s, (const T*)dy, (const T*)x, mean, rstd, theta, ps, g_off, M, d, (const T*)resid, (T*)dx, p->part + job->part_off, with_drop ? (T*)dropped : (T*)nullptr, with_drop ? *da : none, part_out)
       if (nch == 1) CALL(1); else CALL(2);
 #undef CALL
       if (dropped_done) *dropped_done = with_drop;
@@ -1049,8 +1076,8 @@ hipError_t launch_colsum(const hdet_tf_plan* p, const void* src, int cols, const
     for (const colsum_job& j : p->jobs)
       if (j.out_off == out_off && j.cols == cols && j.mode == MODE) { job = &j; break; }
     if (!job) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((colsum_part_kernel<T, MODE>), dim3((cols + 511) / 512, p->nrc, N), dim3(256), 0, s, (const T*)src, (int64_t)cols,
-                       (int64_t)M * cols, M, cols, kColsumRows, (const T*)x, mean, rstd, p->part + job->part_off);
+    hipLaunchKernelGGL((colsum_part_kernel<T, MODE>), dim3((cols + 511) / 512, job->nchunks, N), dim3(256), 0, s, (const T*)src, (int64_t)cols,
+                       (int64_t)M * cols, M, cols, (M + job->nchunks - 1) / job->nchunks, (const T*)x, mean, rstd, p->part + job->part_off);
   } else {
     hipLaunchKernelGGL((colsum_kernel<T, MODE>), dim3((cols + 63) / 64, N), dim3(1024), 0, s, (const T*)src, (int64_t)cols, (int64_t)M * cols, M, cols,
                        (const T*)x, mean, rstd, grads + out_off, grads + out2_off, ps);
@@ -1237,9 +1264,10 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   // With a dropout channel, the gradient that enters a residual branch is the stream's gradient passed
   // through that branch's dropout; the LayerNorm backward kernel that produces the stream's gradient
   // writes it as a second output where it can (dropped_done), else a separate pass does.
-  bool dropped_done = false;
+  bool dropped_done = false, b2_done = false, bo_done = false;    // *_done: stage 1 of that bias gradient came with the LayerNorm kernel
   da.site = 2 * (L - 1) + 1;
-  if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, nullptr, p->dxa, s, drop ? p->dtmp2 : nullptr, &da, &dropped_done))
+  if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, nullptr, p->dxa, s, drop ? p->dtmp2 : nullptr, &da, &dropped_done,
+                           p->blk[L - 1].b_2, &b2_done))
     TF_CHECK(ln_params(p->dtmp, p->x_in[L], p->stf_mean, p->stf_rstd, p->lnf_g, p->lnf_b));
   for (int l = L - 1; l >= 0; --l) {
     const tf_block_off& o = p->blk[l];
@@ -1252,7 +1280,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       dy = p->dtmp2;
     }
     TF_CHECK(wgrad(dy, d, p->f[l], ff, o.w_2));
-    TF_CHECK(colsum(dy, d, o.b_2));
+    if (!b2_done) TF_CHECK(colsum(dy, d, o.b_2));
     {
       bool fused = false;
       const gelu_fusion gf = {nullptr, p->z[l], &fused, nullptr, nullptr, nullptr};
@@ -1265,7 +1293,9 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
     dropped_done = false;
     da.site = 2 * l;
-    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, p->dxa, p->dxb, s, drop ? p->dtmp2 : nullptr, &da, &dropped_done))
+    bo_done = false;
+    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, p->dxa, p->dxb, s, drop ? p->dtmp2 : nullptr, &da, &dropped_done,
+                             o.b_o, &bo_done))
       TF_CHECK(ln_params(p->dtmp, p->x_mid[l], p->st2_mean[l], p->st2_rstd[l], o.ln2_g, o.ln2_b));
     // attention branch: x_mid = x_in + drop(o)
     const void* dob = p->dxb;
@@ -1275,7 +1305,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       dob = p->dtmp2;
     }
     TF_CHECK(wgrad(dob, d, p->a[l], d, o.w_o));
-    TF_CHECK(colsum(dob, d, o.b_o));
+    if (!bo_done) TF_CHECK(colsum(dob, d, o.b_o));
     TF_CHECK(gemm<T>(p, NN, act(dob, d), wt(o.w_o, d), p->dtmp, d, act_d, true, M, d, d, 1, 1, nullptr, 0, s));   // da
     if (p->fused_attn) {
       hdet_attn_desc ad = attn_desc(l);
@@ -1297,7 +1327,9 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     TF_CHECK(gemm<T>(p, NN, act(p->dqkv, 3 * d), wt(o.w_qkv, d), p->dtmp, d, act_d, true, M, d, 3 * d, 1, 1, nullptr, 0, s));
     dropped_done = false;
     da.site = 2 * (l - 1) + 1;                     // the MLP branch of the block below
-    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s, drop && l > 0 ? p->dtmp2 : nullptr, &da, &dropped_done))
+    b2_done = false;
+    if (!launch_ln_bwd_dx<T>(p, p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, p->dxb, p->dxa, s, drop && l > 0 ? p->dtmp2 : nullptr, &da, &dropped_done,
+                             l > 0 ? p->blk[l - 1].b_2 : -1, &b2_done))
       TF_CHECK(ln_params(p->dtmp, p->x_in[l], p->st1_mean[l], p->st1_rstd[l], o.ln1_g, o.ln1_b));
   }
   hipLaunchKernelGGL(zero_kernel, dim3(grid_for((int64_t)V * d), N), dim3(256), 0, s, grads, ps, p->tok, (int64_t)V * d);
