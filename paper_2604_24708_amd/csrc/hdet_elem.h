@@ -87,12 +87,30 @@ __device__ __forceinline__ void hdet_st4_stream(uint16_t* p, const hdet_f4& x) {
   __builtin_nontemporal_store(u, reinterpret_cast<hdet_u2v*>(p));
 }
 
+// x of another lane of the same row of 16 lanes, by a data-parallel primitive: CTRL 0xB1 / 0x4E = quad
+// permutations [1,0,3,2] / [2,3,0,1], 0x141 / 0x140 = mirror within 8 / 16 lanes
+template <int CTRL>
+__device__ __forceinline__ float hdet_dpp(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+// Reductions over the wavefront, the same value in every lane: four steps inside each row of 16 lanes
+// (pairs, quads, 8, 16), then two exchanges between rows.  The order is fixed.
 __device__ __forceinline__ float hdet_wave_sum(float x) {
-  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  x += hdet_dpp<0xB1>(x);
+  x += hdet_dpp<0x4E>(x);
+  x += hdet_dpp<0x141>(x);
+  x += hdet_dpp<0x140>(x);
+  x += __shfl_xor(x, 16);
+  x += __shfl_xor(x, 32);
   return x;
 }
 __device__ __forceinline__ float hdet_wave_max(float x) {
-  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  x = fmaxf(x, hdet_dpp<0xB1>(x));
+  x = fmaxf(x, hdet_dpp<0x4E>(x));
+  x = fmaxf(x, hdet_dpp<0x141>(x));
+  x = fmaxf(x, hdet_dpp<0x140>(x));
+  x = fmaxf(x, __shfl_xor(x, 16));
+  x = fmaxf(x, __shfl_xor(x, 32));
   return x;
 }
 
