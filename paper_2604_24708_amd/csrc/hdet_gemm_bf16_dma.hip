@@ -293,6 +293,11 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
     drop_thresh = (uint32_t)floor((double)p * 4294967296.0);
     drop_scale = 1.f / (1.f - p);
   }
+  // column sums of the stored result over the wavefront's rows, for the columns this lane stores (per strip column group)
+  constexpr bool kColsum = EPI == HDET_EPI_GELUGRAD_BF16;
+  f4 csum[WNT / JG];
+#pragma unroll
+  for (int jg = 0; jg < WNT / JG; ++jg) csum[jg] = f4{0.f, 0.f, 0.f, 0.f};
   if (kGate) fetch_gate(0, gate[0]);
 #pragma unroll
   for (int jg = 0; jg < WNT / JG; ++jg) {
@@ -362,9 +367,50 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
           } else {
             const us4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
             *reinterpret_cast<us4*>(reinterpret_cast<uint16_t*>(g.c) + off) = o;
+            if (kColsum) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q) csum[jg][q] += bf2f(o[q]);
+            }
           }
         }
       }
+    }
+  }
+  // Stage 1 of the column sums: a lane has added its rows in ascending order; the RPI lanes that hold the same
+  // columns are added by exchanges (a fixed tree), then the wavefronts that share a 128-row block in the order of
+  // their rows.  Every (128-row block, column) of C is written by exactly one block of the grid.
+  if (kColsum && g.colsum) {
+    constexpr int RW = TM / WGM;                      // rows per wavefront
+    static_assert(TM % 128 == 0 && RW <= 128 && 128 % RW == 0, "wavefronts must tile 128-row blocks");
+    float* cbuf = reinterpret_cast<float*>(S);        // [WGM * WGN wavefronts][TN / WGN columns]
+#pragma unroll
+    for (int jg = 0; jg < WNT / JG; ++jg)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float x = csum[jg][q];
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) x += __shfl_xor(x, o);
+        csum[jg][q] = x;
+      }
+    __syncthreads();                                   // the strips are no longer in use
+    if (lane < LPR) {
+#pragma unroll
+      for (int jg = 0; jg < WNT / JG; ++jg)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cbuf[wave * (TN / WGN) + jg * CW + lc + q] = csum[jg][q];
+    }
+    __syncthreads();
+    constexpr int WPC = RW >= 128 ? 1 : 128 / RW;      // wavefronts (along m) per 128-row block
+    constexpr int CHUNKS = TM >= 128 ? TM / 128 : 1;
+    const int nchunks = (g.m + 127) / 128;
+    for (int t = tid; t < CHUNKS * TN; t += THREADS) {
+      const int ch = t / TN, cn = t % TN;              // chunk of the tile, column of the tile
+      const int wcol = cn / (TN / WGN), ccol = cn % (TN / WGN);
+      float a = 0.f;
+#pragma unroll
+      for (int u = 0; u < WPC; ++u) a += cbuf[((ch * WPC + u) * WGN + wcol) * (TN / WGN) + ccol];
+      const int chunk = m0 / 128 + ch, col = n0 + cn;
+      if (chunk < nchunks && col < g.n) g.colsum[((int64_t)z * nchunks + chunk) * g.n + col] = a;
     }
   }
 }

@@ -158,6 +158,10 @@ struct hdet_bgemm_args {
   // replica * 65536 + drop_site, drop_stream) and key drop_seed; element = row * ldc + column
   const hdet_ctrl* drop_ctrl; int drop_channel;
   uint32_t drop_step, drop_site, drop_stream, drop_seed_lo, drop_seed_hi;
+  // HDET_EPI_GELUGRAD_BF16, optional (n1 = n2 = 1): colsum[(replica * ceil(m / 128) + m / 128) * n + column] receives the
+  // sum of C as stored over that 128-row block of the column (stage 1 of the bias gradient of the layer whose
+  // pre-activation gradient C is); colsum_bs is unused padding for alignment
+  float* colsum;
 };
 
 // a_kmajor: A(m,k) at a[m*lda + k], else at a[k*lda + m]; b_kmajor: B(k,n) at b[n*ldb + k], else

@@ -1105,8 +1105,9 @@ struct mat { const void* p; int64_t ld; int64_t s[3]; };
 // them (it does on the LDS-direct path); otherwise the caller runs the element-wise kernel.
 // What a GEMM may fold into its epilogue when the fast bf16 kernel takes the product: the GELU after
 // it (second output), the GELU gradient at the pre-activation, or the residual stream it is added to
-// (the sum then goes to resid_out instead of c; with `drop`, the layer's output is dropped out first).  *fused tells the caller whether it happened.
-struct gelu_fusion { void* gelu_out; const void* gelu_pre; bool* fused; const void* resid; void* resid_out; const drop_args* drop; };
+// (the sum then goes to resid_out instead of c; with `drop`, the layer's output is dropped out first); with the GELU
+// gradient, colsum_out receives stage 1 of the column sums of the result.  *fused tells the caller whether it happened.
+struct gelu_fusion { void* gelu_out; const void* gelu_pre; bool* fused; const void* resid; void* resid_out; const drop_args* drop; float* colsum_out; };
 
 template <typename T>
 hipError_t gemm(const hdet_tf_plan* pl, int form, mat A, mat B, void* c, int64_t ldc, const int64_t* c_s, bool act_out,
@@ -1136,7 +1137,7 @@ hipError_t gemm(const hdet_tf_plan* pl, int form, mat A, mat B, void* c, int64_t
           f.drop_seed_lo = gf->drop->seed_lo; f.drop_seed_hi = gf->drop->seed_hi;
         }
       }
-      else { f.mask = (const uint16_t*)gf->gelu_pre; f.mask_ld = ldc; f.mask_bs = c_s[0]; fepi = HDET_EPI_GELUGRAD_BF16; }
+      else { f.mask = (const uint16_t*)gf->gelu_pre; f.mask_ld = ldc; f.mask_bs = c_s[0]; f.colsum = gf->colsum_out; fepi = HDET_EPI_GELUGRAD_BF16; }
       if ((fepi == HDET_EPI_GELUGRAD_BF16 || bias) && hdet_bgemm_dma_eligible(f, form != TN, form == NT, fepi)) {
         *gf->fused = true;
         return hdet_launch_bgemm(f, form != TN, form == NT, fepi, batch, s);
@@ -1220,7 +1221,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     {   // x_mid = x_in + drop(a W_o^T + b_o), the sum (and the dropout) in the GEMM's epilogue where the fast kernel applies
       bool fused = false;
       da.site = 2 * l;
-      const gelu_fusion rf = {nullptr, nullptr, &fused, p->x_in[l], p->x_mid[l], drop ? &da : nullptr};
+      const gelu_fusion rf = {nullptr, nullptr, &fused, p->x_in[l], p->x_mid[l], drop ? &da : nullptr, nullptr};
       TF_CHECK(gemm<T>(p, NT, act(p->a[l], d), wt(o.w_o, d), p->tmp_d, d, act_d, true, M, d, d, 1, 1, theta + o.b_o, ps, s, &rf));
       if (!fused)
         hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_in[l], (const T*)p->tmp_d, (T*)p->x_mid[l], nd, da);
@@ -1228,7 +1229,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     launch_ln_fwd<T>(p, p->x_mid[l], o.ln2_g, o.ln2_b, p->h2[l], p->st2_mean[l], p->st2_rstd[l], s);
     {
       bool fused = false;
-      const gelu_fusion gf = {p->f[l], nullptr, &fused, nullptr, nullptr, nullptr};
+      const gelu_fusion gf = {p->f[l], nullptr, &fused, nullptr, nullptr, nullptr, nullptr};
       TF_CHECK(gemm<T>(p, NT, act(p->h2[l], d), wt(o.w_1, d), p->z[l], ff, act_ff, true, M, ff, d, 1, 1, theta + o.b_1, ps, s, &gf));
       if (!fused)
         hipLaunchKernelGGL(gelu_fwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->z[l], (T*)p->f[l], (int64_t)N * nff);
@@ -1236,7 +1237,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     {
       bool fused = false;
       da.site = 2 * l + 1;
-      const gelu_fusion rf = {nullptr, nullptr, &fused, p->x_mid[l], p->x_in[l + 1], drop ? &da : nullptr};
+      const gelu_fusion rf = {nullptr, nullptr, &fused, p->x_mid[l], p->x_in[l + 1], drop ? &da : nullptr, nullptr};
       TF_CHECK(gemm<T>(p, NT, act(p->f[l], ff), wt(o.w_2, ff), p->tmp_d, d, act_d, true, M, d, ff, 1, 1, theta + o.b_2, ps, s, &rf));
       if (!fused)
         hipLaunchKernelGGL((dropout_kernel<T, true>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)p->x_mid[l], (const T*)p->tmp_d, (T*)p->x_in[l + 1], nd, da);
@@ -1281,15 +1282,21 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     }
     TF_CHECK(wgrad(dy, d, p->f[l], ff, o.w_2));
     if (!b2_done) TF_CHECK(colsum(dy, d, o.b_2));
+    bool b1_done = false;
     {
       bool fused = false;
-      const gelu_fusion gf = {nullptr, p->z[l], &fused, nullptr, nullptr, nullptr};
+      // stage 1 of the first MLP layer's bias gradient comes with the product when its epilogue forms the GELU gradient
+      float* b1_part = nullptr;
+      for (const colsum_job& j : p->jobs)
+        if (j.out_off == o.b_1 && j.mode == 0 && j.cols == ff && j.nchunks == (M + 127) / 128) { b1_part = p->part + j.part_off; break; }
+      const gelu_fusion gf = {nullptr, p->z[l], &fused, nullptr, nullptr, nullptr, b1_part};
       TF_CHECK(gemm<T>(p, NN, act(dy, d), wt(o.w_2, ff), p->dff, ff, act_ff, true, M, ff, d, 1, 1, nullptr, 0, s, &gf));
       if (!fused)
         hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->dff, (const T*)p->z[l], (T*)p->dff, (int64_t)N * nff);
+      b1_done = fused && b1_part;
     }
     TF_CHECK(wgrad(p->dff, ff, p->h2[l], d, o.w_1));
-    TF_CHECK(colsum(p->dff, ff, o.b_1));
+    if (!b1_done) TF_CHECK(colsum(p->dff, ff, o.b_1));
     TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
     dropped_done = false;
     da.site = 2 * l;
