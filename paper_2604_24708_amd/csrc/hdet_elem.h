@@ -7,12 +7,7 @@
 __device__ __forceinline__ float hdet_ld(const float* p) { return *p; }
 __device__ __forceinline__ float hdet_ld(const uint16_t* p) { return __uint_as_float((unsigned)(*p) << 16); }
 __device__ __forceinline__ void hdet_st(float* p, float x) { *p = x; }
-__device__ __forceinline__ void hdet_st(uint16_t* p, float x) {
-  unsigned u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) { *p = (uint16_t)((u >> 16) | 0x0040u); return; }
-  u += 0x7fffu + ((u >> 16) & 1u);
-  *p = (uint16_t)(u >> 16);
-}
+__device__ __forceinline__ void hdet_st(uint16_t* p, float x) { *p = __builtin_bit_cast(unsigned short, (__bf16)x); }
 
 // Eight consecutive elements (16-byte aligned for bf16, 32-byte for fp32) in one or two
 // 128-bit accesses.
@@ -34,11 +29,14 @@ __device__ __forceinline__ hdet_f8 hdet_ld8(const uint16_t* p) {
   }
   return r;
 }
-__device__ __forceinline__ unsigned hdet_bf16_bits(float x) {
-  unsigned u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
+__device__ __forceinline__ unsigned hdet_bf16_bits(float x) {      // round to nearest even (the hardware conversion)
+  return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)x);
+}
+// two values rounded and packed, lo in the low half: one conversion instruction
+typedef float hdet_f2v __attribute__((ext_vector_type(2)));
+typedef __bf16 hdet_bf2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned hdet_bf16_pack(float lo, float hi) {
+  return __builtin_bit_cast(unsigned, __builtin_convertvector((hdet_f2v){lo, hi}, hdet_bf2v));
 }
 __device__ __forceinline__ void hdet_st8(float* p, const hdet_f8& x) {
   *reinterpret_cast<hdet_f4v*>(p) = (hdet_f4v){x.v[0], x.v[1], x.v[2], x.v[3]};
@@ -47,7 +45,7 @@ __device__ __forceinline__ void hdet_st8(float* p, const hdet_f8& x) {
 __device__ __forceinline__ void hdet_st8(uint16_t* p, const hdet_f8& x) {
   hdet_u4v u;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) u[i] = hdet_bf16_bits(x.v[2 * i]) | (hdet_bf16_bits(x.v[2 * i + 1]) << 16);
+  for (int i = 0; i < 4; ++i) u[i] = hdet_bf16_pack(x.v[2 * i], x.v[2 * i + 1]);
   *reinterpret_cast<hdet_u4v*>(p) = u;
 }
 
@@ -69,7 +67,7 @@ __device__ __forceinline__ void hdet_st4(float* p, const hdet_f4& x) {
   *reinterpret_cast<hdet_f4v*>(p) = (hdet_f4v){x.v[0], x.v[1], x.v[2], x.v[3]};
 }
 __device__ __forceinline__ void hdet_st4(uint16_t* p, const hdet_f4& x) {
-  hdet_u2v u = {hdet_bf16_bits(x.v[0]) | (hdet_bf16_bits(x.v[1]) << 16), hdet_bf16_bits(x.v[2]) | (hdet_bf16_bits(x.v[3]) << 16)};
+  hdet_u2v u = {hdet_bf16_pack(x.v[0], x.v[1]), hdet_bf16_pack(x.v[2], x.v[3])};
   *reinterpret_cast<hdet_u2v*>(p) = u;
 }
 
@@ -83,7 +81,7 @@ __device__ __forceinline__ void hdet_st4_stream(float* p, const hdet_f4& x) {
   __builtin_nontemporal_store((hdet_f4v){x.v[0], x.v[1], x.v[2], x.v[3]}, reinterpret_cast<hdet_f4v*>(p));
 }
 __device__ __forceinline__ void hdet_st4_stream(uint16_t* p, const hdet_f4& x) {
-  const hdet_u2v u = {hdet_bf16_bits(x.v[0]) | (hdet_bf16_bits(x.v[1]) << 16), hdet_bf16_bits(x.v[2]) | (hdet_bf16_bits(x.v[3]) << 16)};
+  const hdet_u2v u = {hdet_bf16_pack(x.v[0], x.v[1]), hdet_bf16_pack(x.v[2], x.v[3])};
   __builtin_nontemporal_store(u, reinterpret_cast<hdet_u2v*>(p));
 }
 

@@ -99,65 +99,123 @@ __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const in
 
 // Wide rows (2048 <= classes <= 32768, classes % 4 == 0): one block of BS threads per row, the row
 // held in registers (thread t owns the 4-element chunks t, t + BS, ...), so the logits are
-// read once; logits and their gradient are streamed past the caches.  Same formulas as
-// xent_kernel, with the exponential on the hardware's exp2 (relative error about 1e-7).
-template <typename T, int BS, int NV>
-__global__ __launch_bounds__(BS) void xent_row_kernel(const float* logits, const int32_t* labels, int rows, int classes,
-                                                      T* dlogits, float* row_loss, const hdet_ctrl* ctrl, int ls_channel) {
+// read once; logits and their gradient are streamed past the caches.  Same quantities as
+// xent_kernel, arranged for few instructions per element: e = exp2(z * log2(e) - max * log2(e)) on the
+// hardware's exp2 (relative error about 1e-7), gradient e * (1 / (sum * rows)) - miss / rows with the
+// label's entry corrected by its owner, sum of (z - max) as sum of z minus classes * max.
+//
+// With colsum != nullptr a block takes `rows_per_block` consecutive rows, one after the other with the
+// next row's loads in flight, and a thread also adds up, per column it owns, the gradients it stores:
+// colsum[(replica * gridDim.x + blockIdx.x) * classes + c] = sum over the block's rows of dlogits as
+// stored, rows in ascending order -- stage 1 of the output layer's bias gradient.
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int BS>
+__device__ __forceinline__ void xent_block_reduce(float& a, float& b, float* red, float* red2, bool is_max) {
+  constexpr int NW = BS / 64;
+  const int tid = threadIdx.x;
+  if (is_max) a = wave_max(a);
+  else { a = wave_sum(a); b = wave_sum(b); }
+  if ((tid & 63) == 0) { red[tid >> 6] = a; red2[tid >> 6] = b; }
+  __syncthreads();
+  a = red[0];
+  b = red2[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) {
+    if (is_max) a = fmaxf(a, red[w]);
+    else { a += red[w]; b += red2[w]; }
+  }
+  __syncthreads();
+}
+
+template <typename T, int BS, int NV, bool SUMS>
+__global__ __launch_bounds__(BS, SUMS ? 2 : 4) void xent_row_kernel(const float* logits, const int32_t* labels, int rows, int classes,
+                                                      int rows_per_block, T* dlogits, float* row_loss, const hdet_ctrl* ctrl,
+                                                      int ls_channel, float* colsum) {
   constexpr int NW = BS / 64;
   __shared__ float red[NW], red2[NW];
-  const float eps = smoothing_of(ctrl, ls_channel, blockIdx.y);
-  const int64_t gr = (int64_t)blockIdx.y * rows + blockIdx.x;
-  const float* z = logits + gr * classes;
-  const int c4 = classes >> 2, tid = threadIdx.x;
-  hdet_f4 v[NV];
-  float mx = -INFINITY;
+  const int r = blockIdx.y, tid = threadIdx.x, c4 = classes >> 2;
+  const float eps = smoothing_of(ctrl, ls_channel, r);
+  const float invb = 1.f / (float)rows, hit = 1.f - eps, miss = eps / (float)classes;
+  const float hitb = hit * invb, missb = miss * invb;
+  const int row0 = blockIdx.x * rows_per_block;
+  const int row1 = row0 + rows_per_block < rows ? row0 + rows_per_block : rows;
+  hdet_f4 cur[NV], nxt[SUMS ? NV : 1], acc[SUMS ? NV : 1];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int ch = tid + BS * i;
-    if (ch < c4) {
-      v[i] = hdet_ld4_stream(z + 4 * ch);
+    if (SUMS) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) mx = fmaxf(mx, v[i].v[j]);
+      for (int j = 0; j < 4; ++j) acc[i].v[j] = 0.f;
+    }
+    if (tid + BS * i < c4 && row0 < row1) cur[i] = hdet_ld4_stream(logits + ((int64_t)r * rows + row0) * classes + 4 * (tid + BS * i));
+  }
+  for (int row = row0; row < row1; ++row) {
+    const int64_t gr = (int64_t)r * rows + row;
+    if (SUMS && row + 1 < row1) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+        if (tid + BS * i < c4) nxt[i] = hdet_ld4_stream(logits + (gr + 1) * classes + 4 * (tid + BS * i));
+    }
+    float mx = -INFINITY, sz = 0.f, unused = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (tid + BS * i < c4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { mx = fmaxf(mx, cur[i].v[j]); sz += cur[i].v[j]; }
+      }
+    xent_block_reduce<BS>(mx, unused, red, red2, true);
+    const float mxl = mx * kLog2e;
+    float se = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (tid + BS * i < c4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { cur[i].v[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[i].v[j], kLog2e, -mxl)); se += cur[i].v[j]; }
+      }
+    xent_block_reduce<BS>(se, sz, red, red2, false);
+    const int y = __builtin_amdgcn_readfirstlane(labels[gr]);      // the same for the whole block
+    const int ych = y >> 2;
+    const float a = invb / se;
+    T* dl = dlogits + gr * classes;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int ch = tid + BS * i;
+      if (ch < c4) {
+        hdet_f4 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o.v[j] = __builtin_fmaf(cur[i].v[j], a, -missb);
+        if (ych >= BS * i && ych < BS * (i + 1)) {                  // uniform: the label's chunk is among these
+          asm volatile("" ::: "memory");                            // keeps this a branch, taken once per row
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o.v[j] -= 4 * ch + j == y ? hitb : 0.f;
+        }
+        hdet_st4_stream(dl + 4 * ch, o);
+        if (SUMS) {
+          if (sizeof(T) == 2) {
+            const unsigned u0 = hdet_bf16_pack(o.v[0], o.v[1]), u1 = hdet_bf16_pack(o.v[2], o.v[3]);
+            acc[i].v[0] += __uint_as_float(u0 << 16);
+            acc[i].v[1] += __uint_as_float(u0 & 0xffff0000u);
+            acc[i].v[2] += __uint_as_float(u1 << 16);
+            acc[i].v[3] += __uint_as_float(u1 & 0xffff0000u);
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i].v[j] += o.v[j];
+          }
+        }
+      }
+    }
+    if (tid == 0) row_loss[gr] = logf(se) - hit * (logits[gr * classes + y] - mx) - eps * (sz / (float)classes - mx);
+    if (SUMS) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) cur[i] = nxt[i];
     }
   }
-  mx = wave_max(mx);
-  if ((tid & 63) == 0) red[tid >> 6] = mx;
-  __syncthreads();
-  mx = red[0];
+  if (SUMS) {
+    float* cs = colsum + ((int64_t)r * gridDim.x + blockIdx.x) * classes;
 #pragma unroll
-  for (int w = 1; w < NW; ++w) mx = fmaxf(mx, red[w]);
-  __syncthreads();
-  float se = 0.f, sz = 0.f;
-#pragma unroll
-  for (int i = 0; i < NV; ++i)
-    if (tid + BS * i < c4) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) { sz += v[i].v[j] - mx; v[i].v[j] = __expf(v[i].v[j] - mx); se += v[i].v[j]; }
-    }
-  se = wave_sum(se);
-  sz = wave_sum(sz);
-  if ((tid & 63) == 0) { red[tid >> 6] = se; red2[tid >> 6] = sz; }
-  __syncthreads();
-  se = red[0];
-  sz = red2[0];
-#pragma unroll
-  for (int w = 1; w < NW; ++w) { se += red[w]; sz += red2[w]; }
-  const int y = labels[gr];
-  const float inv = 1.f / se, invb = 1.f / (float)rows;
-  const float hit = 1.f - eps, miss = eps / (float)classes;
-  T* d = dlogits + gr * classes;
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int ch = tid + BS * i;
-    if (ch < c4) {
-      hdet_f4 o;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) o.v[j] = (v[i].v[j] * inv - (4 * ch + j == y ? hit : 0.f) - miss) * invb;
-      hdet_st4_stream(d + 4 * ch, o);
-    }
+    for (int i = 0; i < NV; ++i)
+      if (tid + BS * i < c4) *reinterpret_cast<hdet_f4*>(cs + 4 * (tid + BS * i)) = acc[i];
   }
-  if (tid == 0) row_loss[gr] = logf(se) - hit * (z[y] - mx) - eps * (sz / (float)classes);
 }
 
 // Per-replica mean of the row losses in a fixed tree order (one block per replica), the
@@ -193,19 +251,30 @@ struct hdet_mlp_plan {
   int ls_channel;                        // label-smoothing channel or -1
 };
 
+bool hdet_xent_wide(int classes) { return classes >= 2048 && classes <= 32768 && classes % 4 == 0; }
+
 hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* labels, int rows, int classes, void* dlogits,
-                            float* row_loss, int n_replicas, const hdet_ctrl* ctrl, int ls_channel, hipStream_t s) {
-  if (classes >= 2048 && classes <= 32768 && classes % 4 == 0) {
-    const dim3 grid(rows, n_replicas);
-#define HDET_XENT_ROW(T, BS, NV) \
-  hipLaunchKernelGGL((xent_row_kernel<T, BS, NV>), grid, dim3(BS), 0, s, logits, labels, rows, classes, (T*)dlogits, row_loss, ctrl, ls_channel)
+                            float* row_loss, int n_replicas, const hdet_ctrl* ctrl, int ls_channel, hipStream_t s,
+                            float* colsum, int rows_per_block) {
+  if (hdet_xent_wide(classes)) {
+    const bool sums = colsum != nullptr && rows_per_block > 0;
+    if (!sums) rows_per_block = 1;
+    const dim3 grid((rows + rows_per_block - 1) / rows_per_block, n_replicas);
+#define HDET_XENT_ROW(T, BS, NV, SUMS) \
+  hipLaunchKernelGGL((xent_row_kernel<T, BS, NV, SUMS>), grid, dim3(BS), 0, s, logits, labels, rows, classes, rows_per_block, (T*)dlogits, row_loss, ctrl, ls_channel, colsum)
+#define HDET_XENT_ROW_T(BS, NV, SUMS)        \
+  do {                                       \
+    if (bf16) HDET_XENT_ROW(uint16_t, BS, NV, SUMS); \
+    else HDET_XENT_ROW(float, BS, NV, SUMS); \
+  } while (0)
     if (classes <= 8192) {
-      if (bf16) HDET_XENT_ROW(uint16_t, 256, 8);
-      else HDET_XENT_ROW(float, 256, 8);
+      if (sums) HDET_XENT_ROW_T(256, 8, true);
+      else HDET_XENT_ROW_T(256, 8, false);
     } else {
-      if (bf16) HDET_XENT_ROW(uint16_t, 512, 16);
-      else HDET_XENT_ROW(float, 512, 16);
+      if (sums) HDET_XENT_ROW_T(512, 16, true);
+      else HDET_XENT_ROW_T(512, 16, false);
     }
+#undef HDET_XENT_ROW_T
 #undef HDET_XENT_ROW
     return hipGetLastError();
   }

@@ -792,8 +792,18 @@ int grid_for(int64_t n) { int64_t b = (n + 255) / 256; return (int)(b > 8192 ? 8
 
 // xent and loss reduction live with the MLP path
 hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* labels, int rows, int classes, void* dlogits,
-                            float* row_loss, int n_replicas, const hdet_ctrl* ctrl, int ls_channel, hipStream_t s);
+                            float* row_loss, int n_replicas, const hdet_ctrl* ctrl, int ls_channel, hipStream_t s,
+                            float* colsum = nullptr, int rows_per_block = 0);
+bool hdet_xent_wide(int classes);
 hipError_t hdet_launch_loss_reduce(const float* row_loss, int rows, hdet_ctrl* ctrl, int n_replicas, hipStream_t s);
+
+// Rows per block of the wide-row loss kernel when it also forms stage 1 of the head bias gradient: enough rows
+// to make the partial sums few, as long as about four blocks per compute unit remain; 0 = a separate pass does it.
+static int xent_rows_per_block(int64_t M, int64_t N, int64_t V) {
+  if (!hdet_xent_wide((int)V) || V % 8 != 0) return 0;
+  const int64_t r = M * N / 1024;
+  return r < 8 ? 0 : (int)(r > 64 ? 64 : r);
+}
 
 struct tf_block_off { int64_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_1, b_1, w_2, b_2; };
 
@@ -861,7 +871,9 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   // per block: biases of the four Linear layers (3d + d + ff + d columns) and two LayerNorms (2 x 2d); then final LayerNorm, head bias
   // (the LayerNorm pairs in chunks of kLnRows rows when their backward kernel produces them itself)
   const size_t ln_chunks = (M + kLnRows - 1) / kLnRows;
-  p->part = (float*)take(N * (p->nrc * ((size_t)L * (3 * d + ff) + V) + ln_chunks * (2 * d * (2 * (size_t)L + 1) + 2 * d * (size_t)L)) * 4);
+  const int xr = xent_rows_per_block(M, N, V);
+  const size_t head_chunks = xr ? (M + xr - 1) / xr : p->nrc;
+  p->part = (float*)take(N * (p->nrc * ((size_t)L * (3 * d + ff)) + head_chunks * V + ln_chunks * (2 * d * (2 * (size_t)L + 1) + 2 * d * (size_t)L)) * 4);
   p->jobs_dev = (colsum_job*)take((6 * (size_t)L + 2) * sizeof(colsum_job));
   return off;
 }
@@ -940,16 +952,17 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
   int first_block = 0;
   // producer_g: for the bias of an output projection, the gain offset of the LayerNorm whose backward kernel
   // produces that bias gradient's input (and, when it is of the fused kind, stage 1 of its column sum); -1 otherwise
-  auto add_job = [&](int cols, int mode, int64_t out_off, int64_t out2_off, int64_t producer_g = -1) {
+  auto add_job = [&](int cols, int mode, int64_t out_off, int64_t out2_off, int64_t producer_g = -1, int chunks = 0) {
     if (cols % 8 != 0) return;                       // such widths take the single-stage kernel
     const bool by_ln = (mode == 1 && hdet_tf_ln_fused(p, out_off)) || (producer_g >= 0 && hdet_tf_ln_fused(p, producer_g));
-    const int nchunks = by_ln ? (p->M + kLnRows - 1) / kLnRows : p->nrc;
+    const int nchunks = chunks ? chunks : by_ln ? (p->M + kLnRows - 1) / kLnRows : p->nrc;
     colsum_job j = {part_off, out_off, out2_off, cols, mode, first_block, nchunks};
     p->jobs.push_back(j);
     part_off += (int64_t)(mode == 1 ? 2 : 1) * p->N * nchunks * cols;
     first_block += (cols + 255) / 256;
   };
-  add_job((int)V, 0, p->b_head, 0);
+  const int xr = xent_rows_per_block(p->M, p->N, V);
+  add_job((int)V, 0, p->b_head, 0, -1, xr ? (p->M + xr - 1) / xr : 0);
   add_job((int)d, 1, p->lnf_g, p->lnf_b);
   for (int l = 0; l < p->L; ++l) {
     const tf_block_off& b = p->blk[l];
@@ -1245,7 +1258,13 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   }
   launch_ln_fwd<T>(p, p->x_in[L], p->lnf_g, p->lnf_b, p->hf, p->stf_mean, p->stf_rstd, s);
   TF_CHECK(gemm<T>(p, NT, act(p->hf, d), wt(p->w_head, d), p->logits, V, act_v, false, M, V, d, 1, 1, theta + p->b_head, ps, s));
-  TF_CHECK(hdet_launch_xent(sizeof(T) == 2, p->logits, targets, M, V, p->dlogits, p->row_loss, N, ctrl, p->ls_channel, s));
+  // the loss kernel for wide rows also forms stage 1 of the head bias gradient, xr rows per chunk
+  float* head_part = nullptr;
+  const int xr = xent_rows_per_block(M, N, V);
+  if (xr)
+    for (const colsum_job& j : p->jobs)
+      if (j.out_off == p->b_head && j.mode == 0 && j.cols == V && j.nchunks == (M + xr - 1) / xr) { head_part = p->part + j.part_off; break; }
+  TF_CHECK(hdet_launch_xent(sizeof(T) == 2, p->logits, targets, M, V, p->dlogits, p->row_loss, N, ctrl, p->ls_channel, s, head_part, xr));
   TF_CHECK(hdet_launch_loss_reduce(p->row_loss, M, ctrl, N, s));
 
   // ---- backward -----------------------------------------------------------------------
@@ -1260,7 +1279,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   };
 
   TF_CHECK(wgrad(p->dlogits, V, p->hf, d, p->w_head));
-  TF_CHECK(colsum(p->dlogits, V, p->b_head));
+  if (!head_part) TF_CHECK(colsum(p->dlogits, V, p->b_head));
   TF_CHECK(gemm<T>(p, NN, act(p->dlogits, V), wt(p->w_head, d), p->dtmp, d, act_d, true, M, d, V, 1, 1, nullptr, 0, s));
   // With a dropout channel, the gradient that enters a residual branch is the stream's gradient passed
   // through that branch's dropout; the LayerNorm backward kernel that produces the stream's gradient

@@ -240,6 +240,35 @@ def test_fp32_label_smoothing_and_attention_temperature_channels(cfg, batch):
         x.close()
 
 
+# wide vocabularies with enough rows that the loss kernel takes several rows per block and forms the
+# first stage of the head bias gradient itself: 3 x 42 x 70 rows = 8 per block with a ragged last block;
+# 2104 classes = 526 four-element chunks over 256 threads, 8200 = 2050 over 512 threads
+LOSS_A = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=70, vocab=2104)
+LOSS_B = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=70, vocab=8200)
+
+
+@pytest.mark.parametrize("cfg,bf16", [(LOSS_A, False), (LOSS_A, True), (LOSS_B, False), (LOSS_B, True)])
+def test_wide_row_loss_with_head_bias_partial_sums(cfg, bf16):
+    """Loss, head bias gradient and every other tensor when the cross-entropy kernel walks several rows
+    per block, with a label-smoothing channel (eps_r differs per replica)."""
+    n, batch = 3, 42
+    extra = [(O.CH_LABEL_SMOOTH, 0.1, 0.5, 0.5, 0.0, 0.5)]
+    run = TfRun(base(n_replicas=n, extra=extra), cfg, batch, bf16=bf16)
+    assert (n * batch * cfg["seq_len"]) // 1024 == 8 and (batch * cfg["seq_len"]) % 8 != 0
+    ids, tgt, gl = run.forward_backward(1)
+    eps = run.orc.label_smoothing_table()
+    assert len(set(eps.tolist())) == n and eps.min() > 0.02
+    losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, 1)
+    assert np.max(np.abs(gl - losses) / np.maximum(1.0, np.abs(losses))) <= (1e-2 if bf16 else 1e-5)
+    g_dev = run.g.cpu().numpy()[:, :run.P]
+    for r in range(n):
+        errs = per_tensor_errors(cfg, g_dev[r], grads[r])
+        bad = {k: v for k, v in errs.items() if v > (4e-2 if bf16 else 2e-5)}
+        assert not bad, (r, bad)
+    assert torch.all(run.g[:, run.P:] == 7.0) if run.stride > run.P else True
+    run.close()
+
+
 @pytest.mark.parametrize("cfg,batch,n", [(FUSE1, 2, 2), (FUSE3, 2, 3), (FUSE4, 3, 2), (FUSE5, 2, 2), (FUSE8, 2, 2), (FUSE16, 1, 2)])
 def test_bf16_fused_attention_against_oracle_and_unfused_path(cfg, batch, n):
     """The fused attention kernels (scores kept on chip) against the oracle, at the mixed-precision
