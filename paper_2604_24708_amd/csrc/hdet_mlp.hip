@@ -365,7 +365,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
   }
   // loss and dlogits
   float* dz = (float*)p->dz_a; float* dz_next = (float*)p->dz_b;
-  hipLaunchKernelGGL(xent_kernel<float>, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss, ctrl, p->ls_channel);
+  if (hipError_t e = hdet_launch_xent(false, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0)) return e;
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   // backward
   for (int i = L - 1; i >= 0; --i) {
@@ -419,7 +419,7 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
     if (e != hipSuccess) return e;
   }
   uint16_t* dz = (uint16_t*)p->dz_a; uint16_t* dz_next = (uint16_t*)p->dz_b;
-  hipLaunchKernelGGL(xent_kernel<uint16_t>, dim3((B + 3) / 4, N), dim3(256), 0, s, p->logits, y, B, w[L], dz, p->row_loss, ctrl, p->ls_channel);
+  if (hipError_t e = hdet_launch_xent(true, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0)) return e;
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   for (int i = L - 1; i >= 0; --i) {
     hdet_bgemm_args g = {};                          // dW = dZ^T X
