@@ -70,6 +70,57 @@ def test_validation_needs_no_gpu():
     assert H.hdet_destroy(None) is None
 
 
+def test_model_configs_validate_and_size_without_a_gpu():
+    """Host logic of the model handles: dimension and channel rules give HDET_EINVAL, and the
+    workspace of the transformer workloads covers at least the tensors that must exist
+    (fp32 logits, their bf16 gradient, the stage-1 partial sums of the head bias)."""
+    base = dict(n_replicas=8, sync_interval=32, total_steps=2000, warm_steps=600, lr_max=6e-4, alpha=0.15,
+                optimizer=H.HDET_ADAMW, precision=H.HDET_BF16_GEMM_FP32_MASTER)
+    tf = dict(model_kind=H.HDET_TRANSFORMER, n_blocks=6, d_model=512, n_heads=8, d_ff=2048, seq_len=256, vocab=32000, batch=16)
+
+    def size(**kw):
+        d = dict(base)
+        d.update(tf)
+        d.update(kw)
+        cfg = H.make_config(**d)
+        blocks, dm, ff, V, S = d["n_blocks"], d["d_model"], d["d_ff"], d["vocab"], d["seq_len"]
+        P = V * dm + S * dm + blocks * (4 * dm * dm + 2 * dm * ff + ff + 9 * dm) + 2 * dm + V * dm + V
+        stride = (P + 3) // 4 * 4
+        return H.hdet_workspace_bytes(cfg, stride)[2]
+
+    ws = size()
+    n, M, V = 8, 16 * 256, 32000
+    floor = n * M * V * (4 + 2) + n * (M // 32) * V * 4
+    assert floor < ws < 4 * floor
+    assert size(batch=32) > ws > size(batch=8)
+    assert size(n_blocks=12, d_model=1024, n_heads=16, d_ff=4096, seq_len=512) > 2 * ws
+    for bad in [dict(n_blocks=0), dict(n_blocks=65), dict(d_model=510), dict(n_heads=7), dict(seq_len=0), dict(vocab=1),
+                dict(batch=0), dict(d_ff=0)]:
+        with pytest.raises(H.HdetError) as e:
+            size(**bad)
+        assert e.value.code == H.HDET_EINVAL, bad
+    mlp = dict(model_kind=H.HDET_MLP, widths=[64, 128, 10], batch=32)
+    for bad in [dict(widths=[64, 0, 10]), dict(batch=0)]:
+        d = dict(base)
+        d.update(mlp)
+        d.update(bad)
+        with pytest.raises(H.HdetError):
+            H.hdet_workspace_bytes(H.make_config(**d), 10000)
+    # channel rules: label smoothing needs a model, attention temperature a transformer, one channel per kind
+    ls = (H.HDET_CH_LABEL_SMOOTH, 0.1, 0.5, 0.5, 0.0, 0.5)
+    at = (H.HDET_CH_ATTN_TEMP, 1.2, 0.4, 0.5, 0.25, 4.0)
+    flat = dict(n_replicas=4, sync_interval=4, total_steps=40, warm_steps=12, lr_max=0.05, alpha=0.2, n_params=100)
+    with pytest.raises(H.HdetError):
+        H.hdet_workspace_bytes(H.make_config(extra=[ls], **flat), 100)
+    d = dict(base)
+    d.update(mlp)
+    with pytest.raises(H.HdetError):
+        H.hdet_workspace_bytes(H.make_config(extra=[at], **d), 10000)
+    with pytest.raises(H.HdetError):
+        size(extra=[ls, ls])
+    assert size(extra=[ls, at]) == ws
+
+
 def test_product_path_does_not_touch_the_oracle():
     """Nothing under the package may import or name the oracle."""
     pkg = os.path.join(ROOT, "paper_2604_24708_amd")
