@@ -373,7 +373,8 @@ def main():
     dt = time.perf_counter() - t0
 
     ms_per_step = dt / args.steps * 1e3
-    upd_ms = sum(a.elapsed_time(b) for a, b in upd_ev) / len(upd_ev)
+    upd_all = sorted(a.elapsed_time(b) for a, b in upd_ev)
+    upd_ms = sum(upd_all) / len(upd_all)
     bytes_per_launch = (12 * n + 16) * P if args.shared_state else ADAMW_BYTES * n * P
     achieved = bytes_per_launch / (upd_ms * 1e-3) / 1e9
     st = H.hdet_get_state(h)
@@ -396,6 +397,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(n, P),
                      "kernel": "hdet_update_kernel", "kernel_ms": upd_ms,
+                     "kernel_ms_median": upd_all[len(upd_all) // 2], "kernel_ms_min": upd_all[0],
                      "algorithmic_bytes_per_launch": bytes_per_launch},
     }
     if conv_ev:
