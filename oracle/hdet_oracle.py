@@ -120,16 +120,32 @@ def philox4x32_10(counter: Sequence[int], key: Sequence[int]) -> List[int]:
 PERM_STREAM = 0x48444554  # ASCII "HDET": separates permutation draws from other uses
 
 
+def permutation_from_words(next_word, n: int) -> np.ndarray:
+    """Fisher-Yates from the top index down on the identity: for i = n-1 .. 1 draw j uniform on
+    [0, i] and swap entries i and j.  A draw takes successive 32-bit words from `next_word()` and
+    rejects those at or above the largest multiple of i+1 below 2^32 (no modulo bias), then reduces
+    the accepted word modulo i+1."""
+    pi = list(range(n))
+    for i in range(n - 1, 0, -1):
+        bound = i + 1
+        limit = (1 << 32) - ((1 << 32) % bound)
+        while True:
+            x = next_word()
+            if x < limit:
+                break
+        j = x % bound
+        pi[i], pi[j] = pi[j], pi[i]
+    return np.array(pi, dtype=np.int32)
+
+
 def permutation(seed: int, k: int, channel: int, n: int) -> np.ndarray:
     """Fresh permutation pi of Eq. 9 for controller update number k and hyperparameter
     channel `channel`; a pure function of (seed, k, channel) so that every rank (here:
     both implementations) agrees without an exchange.
 
-    The paper does not name a generator.  Reading taken: Fisher-Yates from the top index
-    down on the identity; the draw for position i is uniform on [0, i] by rejection from
-    32-bit Philox words (no modulo bias).  Words are consumed in order from blocks
-    philox(counter=(block, k, channel, PERM_STREAM), key=(seed_lo, seed_hi)),
-    block = 0, 1, ...
+    The paper does not name a generator.  Reading taken: permutation_from_words on the words
+    of the blocks philox(counter=(block, k, channel, PERM_STREAM), key=(seed_lo, seed_hi)),
+    block = 0, 1, ..., each block's four words in order.
     """
     key = (seed & _MASK32, (seed >> 32) & _MASK32)
     words: List[int] = []
@@ -142,17 +158,7 @@ def permutation(seed: int, k: int, channel: int, n: int) -> np.ndarray:
             block += 1
         return words.pop(0)
 
-    pi = list(range(n))
-    for i in range(n - 1, 0, -1):
-        bound = i + 1
-        limit = (1 << 32) - ((1 << 32) % bound)
-        while True:
-            x = next_word()
-            if x < limit:
-                break
-        j = x % bound
-        pi[i], pi[j] = pi[j], pi[i]
-    return np.array(pi, dtype=np.int32)
+    return permutation_from_words(next_word, n)
 
 
 # --------------------------------------------------------------------------------------
@@ -255,9 +261,36 @@ def converge(theta: np.ndarray, store=np.float32) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 # Sec. 3.4, Eq. 4-7: controller
 # --------------------------------------------------------------------------------------
+_LOG2E = 1.4426950408889634
+_LN2_HI = 6.93147180369123816490e-01      # the leading 32 bits of ln 2: k * _LN2_HI is exact for |k| < 2^20
+_LN2_LO = 1.90821492927058770002e-10
+_INV_FACT = [1.0 / math.factorial(i) for i in range(14)]
+
+
+def exp_spec(x: float) -> float:
+    """exp(x) for x <= 0, the exponential of Eq. 4's softmax after the maximum score is subtracted.
+
+    The schedule state must be reproducible bit for bit, and math libraries differ in the last place
+    of exp.  The exponential is therefore a fixed sequence of IEEE double operations (no fused
+    multiply-add): 0 below -708; otherwise k = x log2(e) rounded to the nearest integer (ties to
+    even), r = (x - k LN2_HI) - k LN2_LO, the Taylor polynomial of degree 13 at r by Horner's rule
+    with coefficients 1/i! (each the correctly rounded quotient), scaled by 2^k.  Within two units
+    in the last place of the true exponential (pinned against a 50-digit evaluation)."""
+    if x > 0.0:
+        raise ValueError("exp_spec is specified for x <= 0")
+    if not (x >= -708.0):
+        return 0.0
+    k = float(round(x * _LOG2E))
+    r = (x - k * _LN2_HI) - k * _LN2_LO
+    p = _INV_FACT[13]
+    for i in range(12, -1, -1):
+        p = p * r + _INV_FACT[i]
+    return p * math.ldexp(1.0, int(k))
+
+
 def controller_weights(losses: Sequence[float], sigma: float) -> np.ndarray:
     """s_r = (Lbar - L_r)/sigma, w = softmax(s)  (Eq. 4); the maximum score is subtracted
-    before exponentiation, which leaves w unchanged."""
+    before exponentiation, which leaves w unchanged.  The exponential is exp_spec."""
     n = len(losses)
     lbar = 0.0
     for r in range(n):
@@ -265,7 +298,7 @@ def controller_weights(losses: Sequence[float], sigma: float) -> np.ndarray:
     lbar /= n
     s = [(lbar - float(losses[r])) / sigma for r in range(n)]
     smax = max(s)
-    e = [math.exp(x - smax) for x in s]
+    e = [exp_spec(x - smax) for x in s]
     z = 0.0
     for r in range(n):
         z += e[r]

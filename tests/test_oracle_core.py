@@ -127,6 +127,57 @@ def test_permutation_properties():
     assert not np.array_equal(O.permutation(7, 3, 0, 8), O.permutation(8, 3, 0, 8))
 
 
+def test_permutation_by_hand_from_the_known_answer_words():
+    """Fisher-Yates worked by hand on the first known-answer block of the generator,
+    philox((0,0,0,0), key (0,0)) = 6627e8d5 e169c58d bc57ac4c 9b00dbd8 (tests/golden/philox4x32_10_kat.txt).
+    N = 4, start [0, 1, 2, 3]:
+      i = 3: bound 4, every word is accepted (2^32 is a multiple of 4); 0x6627e8d5 mod 4 = 1 -> swap 3, 1: [0, 3, 2, 1]
+      i = 2: bound 3, words below 0xffffffff are accepted; 0xe169c58d = 3781805453 = 3 * 1260601817 + 2 -> j = 2: no move
+      i = 1: bound 2; 0xbc57ac4c is even -> j = 0 -> swap 1, 0: [3, 0, 2, 1]
+    A walk from the bottom index up, a word taken out of order or a reduction without the top-down
+    bound would give another ordering."""
+    kat = [0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8]
+    assert O.philox4x32_10((0, 0, 0, 0), (0, 0)) == kat
+    it = iter(kat)
+    assert O.permutation_from_words(lambda: next(it), 4).tolist() == [3, 0, 2, 1]
+    # rejection: for bound 3 the word 0xffffffff (the one value at or above the largest multiple of 3) is
+    # skipped and the next word is used; a plain modulo would have taken 0xffffffff mod 3 = 0
+    it = iter([0x6627e8d5, 0xffffffff, 0xe169c58d, 0xbc57ac4c])
+    assert O.permutation_from_words(lambda: next(it), 4).tolist() == [3, 0, 2, 1]
+    it = iter([0x00000000, 0xffffffff, 0x00000001, 0x00000001])
+    # i = 3: j = 0 -> [3, 1, 2, 0]; i = 2: 0xffffffff rejected, 1 mod 3 = 1 -> swap 2, 1 -> [3, 2, 1, 0]; i = 1: j = 1: no move
+    assert O.permutation_from_words(lambda: next(it), 4).tolist() == [3, 2, 1, 0]
+    # the keyed form consumes block 0, 1, ... of counter (block, k, channel, "HDET"), four words each in order
+    words = []
+    for block in range(3):
+        words += O.philox4x32_10((block, 5, 2, O.PERM_STREAM), (7, 0))
+    it = iter(words)
+    assert O.permutation(7, 5, 2, 8).tolist() == O.permutation_from_words(lambda: next(it), 8).tolist()
+
+
+def test_exp_spec_is_the_exponential_to_two_units_in_the_last_place():
+    """The softmax of Eq. 4 uses a written-out exponential so that the schedule state is reproducible bit
+    for bit; it must still be the exponential: checked against a 50-digit evaluation, and for the
+    properties the controller relies on."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 50
+    rng = np.random.default_rng(11)
+    xs = np.concatenate([-rng.random(4000) * 708.0, -rng.random(4000) * 5.0, -rng.random(2000) * 1e-3,
+                         -np.arange(0, 40) * math.log(2.0), [-708.0, -1e-300, -0.0, 0.0]])
+    worst = 0.0
+    for x in xs.tolist():
+        e = O.exp_spec(x)
+        worst = max(worst, float(abs(Decimal(e) - Decimal(x).exp()) / Decimal(math.ulp(e))))
+    assert worst <= 2.0
+    assert O.exp_spec(0.0) == 1.0 and O.exp_spec(-0.0) == 1.0
+    assert O.exp_spec(-708.1) == 0.0 and O.exp_spec(-1e9) == 0.0 and O.exp_spec(float("-inf")) == 0.0
+    grid = np.linspace(-50.0, 0.0, 20001)
+    vals = np.array([O.exp_spec(x) for x in grid.tolist()])
+    assert np.all(np.diff(vals) >= 0.0)
+    with pytest.raises(ValueError):
+        O.exp_spec(1e-3)
+
+
 def test_permutation_uniform_chi2():
     """Eq. 9 asks for a uniformly random permutation: over many syncs all 24 orderings of
     N = 4 must appear equally often (chi-square, 23 dof; 99.9% quantile = 49.7)."""
@@ -418,7 +469,7 @@ def test_loop_n2_by_hand():
 
 
 def test_multichannel_independent_permutations_and_clamp():
-    extra = [O.Channel(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), O.Channel(O.CH_WD, 0.05, 0.5, 0.5, 0.0)]
+    extra = [O.Channel(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.45), O.Channel(O.CH_WD, 0.05, 0.5, 0.5, 0.0)]
     cfg = _cfg(n_replicas=8, optimizer=O.ADAMW, extra=extra, lr_max=3e-4, alpha=0.15)
     orc, _ = _run(cfg)
     assert np.allclose(np.sort(orc.dropout_table()) / orc.base[1], O.spread_multipliers(8, 1.0),
