@@ -63,13 +63,19 @@ def softmax_xent(logits: np.ndarray, labels: np.ndarray, smoothing: float = 0.0)
 
 
 def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Sequence[int],
-                      bf16: bool = False, info: dict = None, label_smoothing: float = 0.0) -> Tuple[float, np.ndarray]:
+                      bf16: bool = False, info: dict = None, label_smoothing: float = 0.0,
+                      relu_tie: Tuple[float, bool] = None) -> Tuple[float, np.ndarray]:
     """Loss and flat fp32 gradient for one replica.  x: [B, d_in], y: [B] int.
 
     If `info` is given, info["relu_margin"] receives the smallest |pre-activation| over all
     hidden units: the gradient is discontinuous where a pre-activation is zero, so a
     comparison against an implementation in another precision is only meaningful when this
-    margin exceeds that implementation's rounding error."""
+    margin exceeds that implementation's rounding error.
+
+    relu_tie = (tau, open): hidden units whose |pre-activation| is below tau -- ties at the kink of
+    the ReLU as far as an fp32 implementation can tell -- are all taken as open (the unit passes its
+    value and its gradient) or all as closed.  Both are valid subgradients; without the argument
+    the sign of the fp64 pre-activation decides, as everywhere else."""
     def q(a):
         return round_bf16(a.astype(np.float32)).astype(np.float64) if bf16 else a.astype(np.float64)
 
@@ -77,11 +83,16 @@ def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Se
     n_layers = len(layers)
     acts = [q(x)]                                   # input of each layer (as the GEMM sees it)
     pre = []
+    gates = []                                      # which hidden units pass
     for i, (w, b) in enumerate(layers):
         zi = acts[-1] @ q(w).T + b.astype(np.float64)
         pre.append(zi)
         if i + 1 < n_layers:
-            acts.append(q(np.maximum(zi, 0.0)))
+            gate = zi > 0.0
+            if relu_tie is not None:
+                gate = np.where(np.abs(zi) < relu_tie[0], bool(relu_tie[1]), gate)
+            gates.append(gate)
+            acts.append(q(np.where(gate, zi, 0.0)))
     if info is not None:
         info["relu_margin"] = min([float(np.min(np.abs(p))) for p in pre[:-1]] + [float("inf")])
     loss, dz = softmax_xent(pre[-1], y.astype(np.int64), label_smoothing)
@@ -93,7 +104,7 @@ def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Se
         grads[2 * i + 1] = dzq.sum(axis=0).astype(np.float32)
         if i > 0:
             da = dzq @ q(w)
-            dz = da * (pre[i - 1] > 0.0)
+            dz = da * gates[i - 1]
     return loss, np.concatenate(grads)
 
 

@@ -61,39 +61,45 @@ class MlpRun:
         gpu_losses = np.array([out[r] for r in range(n)])
         losses = np.zeros(n)
         grads = np.zeros((n, P), np.float32)
-        margin = float("inf")
         th_dev = self.theta.cpu().numpy()[:, :P]
+        g_dev = self.g.cpu().numpy()[:, :P]
         eps = self.orc.label_smoothing_table()          # per-replica label smoothing (0 without a channel)
         self.theta_before, self.eps_used = th_dev.copy(), eps.copy()
-        for r in range(n):
+
+        def oracle_grad(theta_r, r):
+            """Loss and gradient of replica r at theta_r.  A ReLU whose pre-activation lies within the
+            device's rounding error of zero may open on one side and stay shut on the other; both are
+            valid (sub)gradients.  On such a step the oracle is evaluated with the tied units open and
+            with them closed, and the choice that the device made (the nearer gradient) is the one that
+            is compared and that the oracle's own trajectory continues with."""
             info = {}
-            losses[r], grads[r] = M.mlp_loss_and_grad(self.orc.theta[r], x[r], y[r], self.widths,
-                                                      bf16=self.bf16, info=info, label_smoothing=float(eps[r]))
-            margin = min(margin, info["relu_margin"])
+            out = M.mlp_loss_and_grad(theta_r, x[r], y[r], self.widths, bf16=self.bf16, info=info,
+                                      label_smoothing=float(eps[r]))
+            if info["relu_margin"] >= self.relu_tau:
+                return out, False
+            cands = [M.mlp_loss_and_grad(theta_r, x[r], y[r], self.widths, bf16=self.bf16, label_smoothing=float(eps[r]),
+                                         relu_tie=(self.relu_tau, op)) for op in (True, False)]
+            errs = [rel_err(g_dev[r], c[1]) for c in cands]
+            return cands[int(np.argmin(errs))], True
+
+        tied = False
+        for r in range(n):
+            (losses[r], grads[r]), tie = oracle_grad(self.orc.theta[r], r)
+            tied = tied or tie
         self.loss_err = float(np.max(np.abs(gpu_losses - losses)))
         if check_grads:
             # gradient parity proper: the oracle's gradient at the device's own parameters
             # (the trajectories of the two sides differ by up to the parameter tolerance)
             at_dev = []
             for r in range(n):
-                info = {}
-                at_dev.append(M.mlp_loss_and_grad(th_dev[r], x[r], y[r], self.widths, bf16=self.bf16, info=info,
-                                                  label_smoothing=float(eps[r]))[1])
-                margin = min(margin, info["relu_margin"])
-            self.grad_err = rel_err(self.g.cpu().numpy()[:, :P], np.stack(at_dev))
-        # A ReLU whose pre-activation is within the device's rounding error of zero may open on
-        # one side and stay shut on the other; both gradients are valid (sub)gradients.  Such a
-        # step is not compared, and the oracle continues from the device's state.
-        self.borderline = margin < self.relu_tau
+                (_, gr), tie = oracle_grad(th_dev[r], r)
+                at_dev.append(gr)
+                tied = tied or tie
+            self.grad_err = rel_err(g_dev, np.stack(at_dev))
+        self.borderline = tied
+        self.resyncs += int(tied)                       # steps on which a tie had to be resolved
         H.hdet_fanout_step(self.h, None, H.HDET_FUSE_CONVERGE if fuse else 0)
         self.orc.fanout_step(grads, losses)
-        if self.borderline:
-            self.resyncs += 1
-            assert not fuse, "borderline step on a fused sync step: rerun with another seed"
-            self.orc.theta = self.theta.cpu().numpy()[:, :P].copy()
-            self.orc.m = self.m.cpu().numpy()[:, :P].copy()
-            self.orc.v = self.v.cpu().numpy()[:, :P].copy()
-            self.grad_err = self.loss_err = 0.0
         if t % self.d["sync_interval"] == 0:
             H.hdet_converge(self.h)
             self.orc.converge()
