@@ -163,7 +163,7 @@ def transformer_workload(args):
         T = 64
         cfg = dict(n_blocks=12, d_model=1024, n_heads=16, d_ff=4096, seq_len=512, vocab=32000)
         lr_max = 3e-4
-        extra = [(H.HDET_CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (H.HDET_CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
+        extra = [(H.HDET_CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.45), (H.HDET_CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
     P = I.transformer_param_count(cfg)
     stride = (P + 63) // 64 * 64          # planes start on 256-byte boundaries
     total = max(2000, args.warmup + args.steps)

@@ -39,7 +39,8 @@ extern "C" {
 #define HDET_MAX_GROUPS   4    /* parameter groups with a learning-rate channel each        */
 #define HDET_MAX_LAYERS   16
 
-enum { HDET_OK = 0, HDET_EINVAL = -1, HDET_ESTATE = -2, HDET_EHIP = -3 };
+enum { HDET_OK = 0, HDET_EINVAL = -1, HDET_ESTATE = -2, HDET_EHIP = -3,
+       HDET_ENONFINITE = -4 };   /* an interval loss handed to hdet_autolr_update is not finite */
 
 enum { HDET_SGDM = 0, HDET_ADAMW = 1 };                       /* optimizer                   */
 enum { HDET_GRAD_SHARED = 0, HDET_GRAD_PER_REPLICA = 1 };     /* gradient exchange           */
@@ -61,7 +62,11 @@ typedef struct {
   double  base;        /* initial centre value h_bar                                         */
   double  alpha;       /* spread ratio                                                       */
   double  lambda;      /* step of Eq. 7 for this channel                                     */
-  double  lo, hi;      /* the centre value is clamped to [lo, hi] after each controller step */
+  double  lo, hi;      /* the centre value is clamped to [lo, hi] after each controller step.
+                          Replica values range over centre * [1 - alpha, 1 + alpha] (Eq. 1), so
+                          the whole range must stay meaningful: hi * (1 + alpha) < 1 for a
+                          dropout rate, <= 1 for label smoothing, lo * (1 - alpha) > 0 for an
+                          attention temperature; lo <= base <= hi.  HDET_EINVAL otherwise.    */
 } hdet_channel;
 
 typedef struct {
@@ -155,6 +160,10 @@ typedef struct {
   int32_t controller_active;  /* the controller has taken the base rate over                 */
   int32_t nonfinite;          /* controller calls skipped because a loss was not finite      */
   int32_t n_replicas, n_channels;
+  int32_t autolr_done;        /* t is a sync step and hdet_autolr_update has already run on it:
+                                 a state saved between hdet_fanout_step and hdet_autolr_update
+                                 has 0 here, and the resumed handle still accepts that call     */
+  int32_t reserved;
   double  gamma;              /* decay in use for the learning-rate channel                  */
   double  base[HDET_MAX_CH];  /* centre value per channel (rate channels of the groups first,
                                  then the extra channels); rates are meaningful once active  */
@@ -223,8 +232,12 @@ int hdet_converge(hdet_handle* h);
  * host values given in interval_losses_host -- then L_acc <- 0; if the controller is
  * enabled and t >= S_warm: weights (Eq. 4), hypergradient per channel (Eq. 5-6), velocity
  * and base (Eq. 7-8), fresh permutations (Eq. 9).  Runs on the device in one wavefront.
- * A non-finite loss leaves the controller state untouched and increments
- * hdet_state.nonfinite.  HDET_ESTATE off a sync step or twice on the same one.              */
+ * A non-finite loss leaves the controller state untouched (L_acc is still reset, the sync
+ * step still counts as processed) and increments hdet_state.nonfinite.  When the losses come
+ * from the host (interval_losses_host != NULL, N doubles) and the controller was due, the
+ * call then returns HDET_ENONFINITE; with device-accumulated losses the call does not wait
+ * for the stream, so it returns HDET_OK and the caller sees the event in the counter of the
+ * next hdet_get_state.  HDET_ESTATE off a sync step or twice on the same one.               */
 int hdet_autolr_update(hdet_handle* h, const double* interval_losses_host);
 
 /* Waits for the stream and copies the state out / overwrites it (resume).                   */

@@ -16,7 +16,7 @@ HDET_MAX_CH = 8
 HDET_MAX_GROUPS = 4
 HDET_MAX_LAYERS = 16
 
-HDET_OK, HDET_EINVAL, HDET_ESTATE, HDET_EHIP = 0, -1, -2, -3
+HDET_OK, HDET_EINVAL, HDET_ESTATE, HDET_EHIP, HDET_ENONFINITE = 0, -1, -2, -3, -4
 HDET_SGDM, HDET_ADAMW = 0, 1
 HDET_GRAD_SHARED, HDET_GRAD_PER_REPLICA = 0, 1
 HDET_FP32, HDET_BF16_GEMM_FP32_MASTER = 0, 1
@@ -77,6 +77,7 @@ class hdet_state(C.Structure):
     _fields_ = [
         ("t", C.c_int64), ("k", C.c_int64), ("controller_active", C.c_int32),
         ("nonfinite", C.c_int32), ("n_replicas", C.c_int32), ("n_channels", C.c_int32),
+        ("autolr_done", C.c_int32), ("reserved", C.c_int32),
         ("gamma", C.c_double),
         ("base", C.c_double * HDET_MAX_CH), ("vel", C.c_double * HDET_MAX_CH),
         ("delta", C.c_double * HDET_MAX_CH),
@@ -230,10 +231,16 @@ def hdet_converge(h):
     _check(load_library().hdet_converge(h), h)
 
 
-def hdet_autolr_update(h, interval_losses: Optional[Sequence[float]] = None):
+def hdet_autolr_update(h, interval_losses: Optional[Sequence[float]] = None, n_replicas: Optional[int] = None):
+    """`interval_losses`: None (the device-accumulated losses) or exactly N values; the C call reads
+    N doubles, so the length is checked here against `n_replicas` or, if that is not given, against
+    the handle's own count (one state query)."""
     arr = None
     if interval_losses is not None:
-        arr = (C.c_double * len(interval_losses))(*[float(x) for x in interval_losses])
+        n = n_replicas if n_replicas is not None else hdet_get_state(h).n_replicas
+        if len(interval_losses) != n:
+            raise ValueError(f"interval_losses has {len(interval_losses)} values, the handle has {n} replicas")
+        arr = (C.c_double * n)(*[float(x) for x in interval_losses])
     _check(load_library().hdet_autolr_update(h, arr), h)
 
 

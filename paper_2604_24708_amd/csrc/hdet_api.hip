@@ -6,6 +6,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <cmath>
+
 #include <new>
 
 #include "hdet_internal.h"
@@ -118,11 +120,16 @@ int validate(const hdet_config* c, std::string* why) {
     if (ch.kind != HDET_CH_WD && ch.kind != HDET_CH_DROPOUT && ch.kind != HDET_CH_LABEL_SMOOTH && ch.kind != HDET_CH_ATTN_TEMP)
       return bad("extra channel kind must be HDET_CH_DROPOUT, HDET_CH_WD, HDET_CH_LABEL_SMOOTH or HDET_CH_ATTN_TEMP");
     if (++seen[ch.kind] > 1) return bad("at most one channel per kind");
-    if (!(ch.alpha >= 0.0 && ch.alpha <= 1.0) || !(ch.base >= 0.0) || !(ch.lo <= ch.hi)) return bad("bad extra channel parameters");
-    if (ch.kind == HDET_CH_LABEL_SMOOTH && (c->model_kind == HDET_FLAT || !(ch.hi <= 1.0) || !(ch.base * (1.0 + ch.alpha) <= 1.0)))
-      return bad("label smoothing needs a model and values in [0, 1]");
-    if (ch.kind == HDET_CH_ATTN_TEMP && (c->model_kind != HDET_TRANSFORMER || !(ch.lo > 0.0) || !(ch.base * (1.0 - ch.alpha) > 0.0)))
-      return bad("attention temperature needs a transformer and values > 0");
+    if (!(ch.alpha >= 0.0 && ch.alpha <= 1.0) || !(ch.lo >= 0.0) || !(ch.lo <= ch.base && ch.base <= ch.hi))
+      return bad("extra channel needs alpha in [0, 1] and 0 <= lo <= base <= hi");
+    // the controller clamps the centre value to [lo, hi] (Eq. 7); replica r then uses centre * rho_pi(r) with rho in
+    // [1 - alpha, 1 + alpha] (Eq. 1, Eq. 9), so the bounds below hold for every value a kernel can read
+    if (ch.kind == HDET_CH_DROPOUT && !(ch.hi * (1.0 + ch.alpha) < 1.0))
+      return bad("dropout needs hi * (1 + alpha) < 1");
+    if (ch.kind == HDET_CH_LABEL_SMOOTH && (c->model_kind == HDET_FLAT || !(ch.hi * (1.0 + ch.alpha) <= 1.0)))
+      return bad("label smoothing needs a model and hi * (1 + alpha) <= 1");
+    if (ch.kind == HDET_CH_ATTN_TEMP && (c->model_kind != HDET_TRANSFORMER || !(ch.lo * (1.0 - ch.alpha) > 0.0)))
+      return bad("attention temperature needs a transformer and lo * (1 - alpha) > 0");
   }
   if (c->shared_opt_state != 0 && c->shared_opt_state != 1) return bad("shared_opt_state must be 0 or 1");
   if (c->shared_opt_state && (c->optimizer != HDET_ADAMW || c->grad_mode != HDET_GRAD_SHARED))
@@ -387,8 +394,12 @@ int hdet_autolr_update(hdet_handle* h, const double* interval_losses_host) {
   memset(&a, 0, sizeof(a));
   a.ctrl = h->ctrl_dev;
   a.use_injected = interval_losses_host != nullptr;
+  bool nonfinite = false;
   if (interval_losses_host)
-    for (int r = 0; r < c.n_replicas; ++r) a.injected[r] = interval_losses_host[r];
+    for (int r = 0; r < c.n_replicas; ++r) {
+      a.injected[r] = interval_losses_host[r];
+      nonfinite = nonfinite || !std::isfinite(interval_losses_host[r]);
+    }
   a.run_controller = c.autolr_enabled && h->t >= c.warm_steps;
   a.n_replicas = c.n_replicas;
   a.n_channels = h->n_channels;
@@ -410,6 +421,8 @@ int hdet_autolr_update(hdet_handle* h, const double* interval_losses_host) {
   hipError_t e = hdet_launch_controller(a, h->stream);
   if (e != hipSuccess) return hip_fail(h, e, "controller kernel");
   h->last_autolr_t = h->t;
+  // the kernel has left the controller state untouched and counted the event
+  if (nonfinite && a.run_controller) return fail(h, HDET_ENONFINITE, "an interval loss is not finite: controller state left untouched");
   return HDET_OK;
 }
 
@@ -427,6 +440,7 @@ int hdet_get_state(hdet_handle* h, hdet_state* out) {
   out->nonfinite = c.nonfinite;
   out->n_replicas = h->cfg.n_replicas;
   out->n_channels = h->n_channels;
+  out->autolr_done = h->t > 0 && h->last_autolr_t == h->t;
   out->gamma = h->gamma;
   memcpy(out->base, c.base, sizeof(c.base));
   memcpy(out->vel, c.vel, sizeof(c.vel));
@@ -471,7 +485,7 @@ int hdet_set_state(hdet_handle* h, const hdet_state* in) {
   int rc = upload_ctrl(h, c);
   if (rc != HDET_OK) return rc;
   h->t = in->t;
-  h->last_autolr_t = (in->t % h->cfg.sync_interval == 0) ? in->t : 0;
+  h->last_autolr_t = (in->autolr_done && in->t % h->cfg.sync_interval == 0) ? in->t : 0;
   h->converged_at_t = -1;
   return write_shadow(h);
 }

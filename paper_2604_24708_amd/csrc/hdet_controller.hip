@@ -7,30 +7,12 @@
 // operands through shuffles in that order), contraction into fused multiply-adds disabled,
 // so that the result follows the written formulas operation by operation.
 
+#include "hdet_elem.h"        // Philox-4x32-10, the one device copy
 #include "hdet_internal.h"
 
 #pragma clang fp contract(off)
 
 namespace {
-
-// Philox-4x32 with 10 rounds (Salmon et al., SC'11).
-struct philox_out { uint32_t x[4]; };
-
-__device__ philox_out philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
-                                    uint32_t k1) {
-  for (int rnd = 0; rnd < 10; ++rnd) {
-    if (rnd > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
-    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
-    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n1 = (uint32_t)p1;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-    const uint32_t n3 = (uint32_t)p0;
-    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
-  }
-  philox_out o = {{c0, c1, c2, c3}};
-  return o;
-}
 
 constexpr uint32_t kPermStream = 0x48444554u;   // "HDET"
 
@@ -43,14 +25,14 @@ __device__ void draw_permutation(int32_t* pi, int n, uint32_t k, uint32_t j, uin
   for (int i = 0; i < n; ++i) pi[i] = i;
   uint32_t block = 0;
   int have = 0;
-  philox_out words = {{0, 0, 0, 0}};
+  hdet_philox4 words = {{0, 0, 0, 0}};
   for (int i = n - 1; i > 0; --i) {
     const uint32_t bound = (uint32_t)i + 1u;
     const uint64_t limit = 0x100000000ull - (0x100000000ull % bound);
     uint32_t x;
     do {
       if (have == 0) {
-        words = philox4x32_10(block++, k, j, kPermStream, seed_lo, seed_hi);
+        words = hdet_philox4x32_10(block++, k, j, kPermStream, seed_lo, seed_hi);
         have = 4;
       }
       x = words.x[4 - have];
@@ -59,6 +41,26 @@ __device__ void draw_permutation(int32_t* pi, int n, uint32_t k, uint32_t j, uin
     const int t = (int)(x % bound);
     const int32_t tmp = pi[i]; pi[i] = pi[t]; pi[t] = tmp;
   }
+}
+
+// exp(x) for the softmax of Eq. 4 (x <= 0 there), specified operation by operation so that every
+// implementation in IEEE double arithmetic without fused multiply-adds returns the same bits as this
+// one, whatever its math library does:
+//   x < -708             -> 0                                   (below 2^-1021: treated as no weight)
+//   k = rint(x * log2 e),  r = (x - k * LN2_HI) - k * LN2_LO    (LN2_HI has 32 significant bits: k * LN2_HI is exact)
+//   p = sum_{i <= 13} r^i / i!  by Horner's rule from i = 13 down, each coefficient the rounded quotient 1 / i!
+//   result = p * 2^k                                             (exact scaling, k >= -1021)
+// |r| <= 0.347, so the series is cut below 2^-57 and the result is within two units in the last place of exp(x).
+__device__ double exp_spec(double x) {
+  if (!(x >= -708.0)) return 0.0;
+  const double k = __builtin_rint(x * 1.4426950408889634);
+  const double r = (x - k * 6.93147180369123816490e-01) - k * 1.90821492927058770002e-10;
+  const double c[14] = {1.0, 1.0, 1.0 / 2.0, 1.0 / 6.0, 1.0 / 24.0, 1.0 / 120.0, 1.0 / 720.0, 1.0 / 5040.0, 1.0 / 40320.0,
+                        1.0 / 362880.0, 1.0 / 3628800.0, 1.0 / 39916800.0, 1.0 / 479001600.0, 1.0 / 6227020800.0};
+  double p = c[13];
+#pragma unroll
+  for (int i = 12; i >= 0; --i) p = p * r + c[i];
+  return p * __builtin_ldexp(1.0, (int)k);
 }
 
 // sum over lanes 0..n-1 in ascending order; every lane gets the result
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(64) void hdet_controller_kernel(const hdet_controll
   const double s = mine ? (lbar - L) / a.sigma : 0.0;
   double smax = __shfl(s, 0);
   for (int r = 1; r < n; ++r) { const double o = __shfl(s, r); smax = o > smax ? o : smax; }
-  const double e = mine ? exp(s - smax) : 0.0;
+  const double e = mine ? exp_spec(s - smax) : 0.0;
   const double z = ordered_sum(e, n);
   const double w = e / z;
   const double inv_n = 1.0 / (double)n;

@@ -422,10 +422,22 @@ bool chunk_regular(const void* base, int64_t ld, const int64_t* bs, int chunk_ex
          (reinterpret_cast<uintptr_t>(base) & 15) == 0;
 }
 
+// compute units of the current device (queried once per device; 256 on MI355X)
+int compute_units() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+  }
+  return cached[dev];
+}
+
 template <bool AK, bool BK, int EPI>
 hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
   auto blocks = [&](int tm, int tn) { return (int64_t)((g.m + tm - 1) / tm) * ((g.n + tn - 1) / tn) * batch; };
-  constexpr int kCus = 256;
+  const int kCus = compute_units();
   // a gating epilogue is long enough to want a second block on the CU up to K = 1024
   constexpr bool gating = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16;
   const bool long_k = g.k >= (gating ? 2048 : 1024);

@@ -361,7 +361,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
     g.c = i + 1 < L ? (float*)p->act[i + 1] : p->logits; g.c_rs = w[i + 1]; g.c_s[0] = (int64_t)B * w[i + 1];
     g.m = B; g.n = w[i + 1]; g.k = w[i];
     g.bias = theta + p->b_off[i]; g.bias_bs = ps;
-    (void)hdet_launch_sgemm(g, i + 1 < L ? HDET_SEPI_BIAS_RELU : HDET_SEPI_BIAS, N, s);
+    if (hipError_t e = hdet_launch_sgemm(g, i + 1 < L ? HDET_SEPI_BIAS_RELU : HDET_SEPI_BIAS, N, s)) return e;
   }
   // loss and dlogits
   float* dz = (float*)p->dz_a; float* dz_next = (float*)p->dz_b;
@@ -375,7 +375,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
     g.b = (const float*)p->act[i]; g.b_rs = w[i]; g.b_cs = 1; g.b_s[0] = (int64_t)B * w[i];   // B(b,k) = X[b][k]
     g.c = grads + p->w_off[i]; g.c_rs = w[i]; g.c_s[0] = ps;
     g.m = w[i + 1]; g.n = w[i]; g.k = B;
-    (void)hdet_launch_sgemm(g, HDET_SEPI_NONE, N, s);
+    if (hipError_t e = hdet_launch_sgemm(g, HDET_SEPI_NONE, N, s)) return e;
     hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 63) / 64, N), dim3(256), 0, s, dz, B, w[i + 1],
                        (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
     if (i > 0) {
@@ -386,7 +386,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
       d.c = dz_next; d.c_rs = w[i]; d.c_s[0] = (int64_t)B * w[i];
       d.m = B; d.n = w[i]; d.k = w[i + 1];
       d.mask = (const float*)p->act[i]; d.mask_rs = w[i]; d.mask_bs = (int64_t)B * w[i];
-      (void)hdet_launch_sgemm(d, HDET_SEPI_MASK, N, s);
+      if (hipError_t e = hdet_launch_sgemm(d, HDET_SEPI_MASK, N, s)) return e;
       float* t = dz; dz = dz_next; dz_next = t;
     }
   }

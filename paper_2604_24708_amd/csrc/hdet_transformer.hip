@@ -974,8 +974,10 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
     add_job((int)d, 1, b.ln1_g, b.ln1_b);
   }
   p->final_blocks = first_block;
+  // on the handle's stream, like all other work; the host copy lives as long as the plan
   if (!p->jobs.empty() &&
-      hipMemcpy(p->jobs_dev, p->jobs.data(), p->jobs.size() * sizeof(colsum_job), hipMemcpyHostToDevice) != hipSuccess) {
+      hipMemcpyAsync(p->jobs_dev, p->jobs.data(), p->jobs.size() * sizeof(colsum_job), hipMemcpyHostToDevice,
+                     (hipStream_t)cfg.stream) != hipSuccess) {
     *err = "could not upload the column-reduction table"; delete p; return nullptr;
   }
   return p;

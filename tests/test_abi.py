@@ -33,9 +33,9 @@ def test_struct_layouts_match_the_c_compiler():
 int main(void) {
   printf("%zu %zu %zu %zu %zu ", sizeof(hdet_config), sizeof(hdet_buffers), sizeof(hdet_state),
          sizeof(hdet_channel), sizeof(hdet_model_dims));
-  printf("%zu %zu %zu %zu %zu %zu\n", offsetof(hdet_config, dims), offsetof(hdet_config, extra),
+  printf("%zu %zu %zu %zu %zu %zu %zu %zu\n", offsetof(hdet_config, dims), offsetof(hdet_config, extra),
          offsetof(hdet_config, stream), offsetof(hdet_state, rho), offsetof(hdet_state, perm),
-         offsetof(hdet_buffers, plane_stride));
+         offsetof(hdet_buffers, plane_stride), offsetof(hdet_state, autolr_done), offsetof(hdet_state, gamma));
   return 0;
 }'''
     with tempfile.TemporaryDirectory() as d:
@@ -47,7 +47,8 @@ int main(void) {
     want = [C.sizeof(B.hdet_config), C.sizeof(B.hdet_buffers), C.sizeof(B.hdet_state),
             C.sizeof(B.hdet_channel), C.sizeof(B.hdet_model_dims),
             B.hdet_config.dims.offset, B.hdet_config.extra.offset, B.hdet_config.stream.offset,
-            B.hdet_state.rho.offset, B.hdet_state.perm.offset, B.hdet_buffers.plane_stride.offset]
+            B.hdet_state.rho.offset, B.hdet_state.perm.offset, B.hdet_buffers.plane_stride.offset,
+            B.hdet_state.autolr_done.offset, B.hdet_state.gamma.offset]
     assert got == want
 
 
@@ -119,6 +120,36 @@ def test_model_configs_validate_and_size_without_a_gpu():
     with pytest.raises(H.HdetError):
         size(extra=[ls, ls])
     assert size(extra=[ls, at]) == ws
+
+
+def test_channel_ranges_cover_every_replica_value():
+    """The controller clamps a channel's centre to [lo, hi]; replica values spread over
+    centre * [1 - alpha, 1 + alpha] (Eq. 1).  A configuration whose spread could leave the meaningful
+    range of its kind (dropout rate < 1, label smoothing <= 1, temperature > 0) is refused."""
+    base = dict(n_replicas=8, sync_interval=32, total_steps=2000, warm_steps=600, lr_max=6e-4, alpha=0.15,
+                optimizer=H.HDET_ADAMW, precision=H.HDET_BF16_GEMM_FP32_MASTER,
+                model_kind=H.HDET_TRANSFORMER, n_blocks=2, d_model=64, n_heads=4, d_ff=256, seq_len=32, vocab=512, batch=4)
+    P = 512 * 64 + 32 * 64 + 2 * (4 * 64 * 64 + 2 * 64 * 256 + 256 + 9 * 64) + 2 * 64 + 512 * 64 + 512
+
+    def ok(extra):
+        return H.hdet_workspace_bytes(H.make_config(extra=extra, **base), P)
+
+    def refused(extra):
+        with pytest.raises(H.HdetError) as e:
+            ok(extra)
+        assert e.value.code == H.HDET_EINVAL
+
+    ok([(H.HDET_CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.45)])          # up to 0.9
+    refused([(H.HDET_CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.5)])      # could reach 1.0
+    refused([(H.HDET_CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9)])      # could reach 1.8
+    refused([(H.HDET_CH_DROPOUT, 0.5, 0.1, 0.5, 0.0, 0.45)])     # base above hi
+    ok([(H.HDET_CH_LABEL_SMOOTH, 0.1, 0.5, 0.5, 0.0, 2.0 / 3.0)])
+    refused([(H.HDET_CH_LABEL_SMOOTH, 0.1, 0.5, 0.5, 0.0, 0.7)])
+    ok([(H.HDET_CH_ATTN_TEMP, 1.2, 0.4, 0.5, 0.25, 4.0)])
+    refused([(H.HDET_CH_ATTN_TEMP, 1.2, 1.0, 0.5, 0.25, 4.0)])   # the lowest replica value would be 0
+    refused([(H.HDET_CH_ATTN_TEMP, 1.2, 0.4, 0.5, 0.0, 4.0)])
+    refused([(H.HDET_CH_WD, 0.05, 0.5, 0.5, -0.1, 1.0)])
+    ok([(H.HDET_CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))])
 
 
 def test_product_path_does_not_touch_the_oracle():

@@ -148,7 +148,7 @@ def test_hundred_steps_within_1e4():
 
 
 def test_weight_decay_channel_and_three_permutations():
-    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
+    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.45), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
     d = base_cfg(n_replicas=8, extra=extra, lr_max=3e-3, alpha=0.15)
     run = FlatRun(d, 4099)
     for t in range(1, 21):
@@ -227,11 +227,88 @@ def test_nonfinite_loss_skips_the_controller():
     for t in range(1, 5):
         H.hdet_fanout_step(run.h, run.g, 0)
         run.orc.fanout_step(np.zeros((4, 64), np.float32), [0.0] * 4)
-    H.hdet_autolr_update(run.h, [1.0, float("nan"), 1.0, 1.0])
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_autolr_update(run.h, [1.0, float("nan"), 1.0, 1.0])
+    assert e.value.code == H.HDET_ENONFINITE                     # reported; the sync step still counts as processed
     run.orc.autolr_update([1.0, float("nan"), 1.0, 1.0])
     st = H.hdet_get_state(run.h)
-    assert st.nonfinite == 1 and st.k == 0 and st.controller_active == 0
+    assert st.nonfinite == 1 and st.k == 0 and st.controller_active == 0 and st.autolr_done == 1
     check_state(st, run.orc)
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_autolr_update(run.h, [1.0] * 4)
+    assert e.value.code == H.HDET_ESTATE
+    # the next interval is finite again: the controller takes over as if nothing had happened
+    for t in range(5, 9):
+        H.hdet_fanout_step(run.h, run.g, 0)
+        run.orc.fanout_step(np.zeros((4, 64), np.float32), [0.0] * 4)
+    H.hdet_autolr_update(run.h, [1.0, 1.1, 0.9, 1.0])
+    run.orc.autolr_update([1.0, 1.1, 0.9, 1.0])
+    check_state(H.hdet_get_state(run.h), run.orc)
+    # before warm_steps a non-finite loss is only recorded as L_r: the controller was not due, no error
+    d2 = base_cfg(warm_steps=8)
+    run2 = FlatRun(d2, 64)
+    for t in range(1, 5):
+        H.hdet_fanout_step(run2.h, run2.g, 0)
+    H.hdet_autolr_update(run2.h, [1.0, float("inf"), 1.0, 1.0])
+    assert H.hdet_get_state(run2.h).nonfinite == 0
+    with pytest.raises(ValueError):
+        H.hdet_autolr_update(run2.h, [1.0] * 3)                  # the binding refuses a list that is not N long
+    run.close(); run2.close()
+
+
+def test_state_saved_between_update_and_controller_call_resumes():
+    """A snapshot taken on a sync step after hdet_fanout_step but before hdet_autolr_update carries
+    autolr_done = 0, and the handle it is loaded into still runs the controller for that sync step."""
+    d = base_cfg(n_replicas=4, warm_steps=0)
+    a = FlatRun(d, 257)
+    for t in range(1, 4):
+        a.step(t, fuse=False)
+    g = I.flat_grads(4, 257, 99, 4, std=0.1)
+    a.g[:, :257] = torch.from_numpy(g).to(a.g.device)
+    H.hdet_fanout_step(a.h, a.g, 0)
+    H.hdet_converge(a.h)
+    st = H.hdet_get_state(a.h)
+    assert st.t == 4 and st.autolr_done == 0
+    b = FlatRun(d, 257)
+    b.theta.copy_(a.theta); b.m.copy_(a.m); b.v.copy_(a.v)
+    H.hdet_set_state(b.h, st)
+    losses = [1.0, 1.2, 0.8, 1.1]
+    H.hdet_autolr_update(a.h, losses)
+    H.hdet_autolr_update(b.h, losses)                            # would be HDET_ESTATE if the flag were guessed from t
+    sa, sb = H.hdet_get_state(a.h), H.hdet_get_state(b.h)
+    assert sa.k == sb.k == 1 and sa.base[0] == sb.base[0] and sb.autolr_done == 1
+    assert [sa.perm[0][r] for r in range(4)] == [sb.perm[0][r] for r in range(4)]
+    H.hdet_set_state(b.h, sb)
+    with pytest.raises(H.HdetError) as e:
+        H.hdet_autolr_update(b.h, losses)                        # a snapshot taken after the call keeps refusing a second one
+    assert e.value.code == H.HDET_ESTATE
+    a.close(); b.close()
+
+
+def test_channel_base_driven_to_its_upper_bound_stays_in_range():
+    """A dropout channel whose centre value the controller pushes up (large lambda, losses falling with
+    the value) is clamped at hi; every replica's value stays below hi * (1 + alpha) < 1, and the state
+    still matches the oracle bit for bit."""
+    extra = [(O.CH_DROPOUT, 0.3, 1.0, 50.0, 0.0, 0.45)]
+    d = base_cfg(n_replicas=4, warm_steps=0, extra=extra, total_steps=40)
+    run = FlatRun(d, 64)
+    hit = False
+    for t in range(1, 25):
+        H.hdet_fanout_step(run.h, run.g, 0)
+        run.orc.fanout_step(np.zeros((4, 64), np.float32), [0.0] * 4)
+        if t % 4 == 0:
+            st = H.hdet_get_state(run.h)
+            # the replica with the largest dropout value reports the lowest loss
+            vals = [st.base[1] * st.rho[1][st.perm[1][r]] for r in range(4)]
+            losses = [2.0 - v for v in vals]
+            H.hdet_autolr_update(run.h, losses)
+            run.orc.autolr_update(losses)
+            st = H.hdet_get_state(run.h)
+            check_state(st, run.orc)
+            assert 0.0 <= st.base[1] <= 0.45
+            assert all(st.base[1] * st.rho[1][st.perm[1][r]] < 1.0 for r in range(4))
+            hit = hit or st.base[1] == 0.45
+    assert hit
     run.close()
 
 

@@ -144,7 +144,7 @@ def test_fp32_full_loop_trajectory(cfg, batch, n):
 def test_fp32_dropout_and_weight_decay_channels():
     """Three explored scalars (rate, dropout, weight decay) with independent permutations
     (Remark 1); dropout masks regenerated on both sides from (seed, step, replica, site)."""
-    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
+    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.45), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
     d = base(n_replicas=4, optimizer=O.ADAMW, lr_max=2e-3, alpha=0.15, extra=extra, total_steps=10, sync_interval=2,
              warm_steps=2)
     run = TfRun(d, TINY, 3)
@@ -189,7 +189,7 @@ def test_bf16_loss_curve_within_1e2(cfg, batch, n, steps):
 
 
 def test_bf16_dropout_loss_matches():
-    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9)]
+    extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.45)]
     d = base(n_replicas=4, optimizer=O.ADAMW, lr_max=2e-3, extra=extra)
     run = TfRun(d, SMALL, 2, bf16=True)
     for t in range(1, 4):
@@ -207,7 +207,7 @@ def test_fp32_label_smoothing_and_attention_temperature_channels(cfg, batch):
     ones, each with its own permutation."""
     n = 4
     extra = [(O.CH_LABEL_SMOOTH, 0.1, 0.5, 0.5, 0.0, 0.5), (O.CH_ATTN_TEMP, 1.2, 0.4, 0.5, 0.25, 4.0),
-             (O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.9), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
+             (O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.45), (O.CH_WD, 0.05, 0.5, 0.5, 0.0, float("inf"))]
     d = base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, extra=extra)
     run = TfRun(d, cfg, batch)
     for t in range(1, 13):
