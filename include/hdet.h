@@ -198,6 +198,25 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* buffers, hdet_handle
  * HDET_ESTATE once t > 0.                                                                   */
 int hdet_warm_init(hdet_handle* h, const float* theta0_dev, double nu, uint64_t seed);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: the initialisation of hdet_warm_init without a handle
+ * (hdet_create allocates the control block that holds hdet_warm_init's partial sums).  Writes
+ * params_dev[r][0..n_params) = theta0 + eps_r for r < n_replicas exactly as hdet_warm_init does
+ * for the same (theta0, nu, seed), and, if params_bf16_dev is not NULL, the bfloat16 copy in the
+ * same layout.  All pointers are device memory owned by the caller, 16-byte aligned, planes
+ * plane_stride elements apart (>= n_params, a multiple of 4); theta0_dev [n_params] must not
+ * overlap params_dev; stream: hipStream_t or NULL.  The partial sums of ||theta0||^2 live in a
+ * fixed array of 8200 bytes inside the library, one copy per GPU for the life of the process;
+ * the call allocates and frees nothing and does not wait for the stream.  Every entry of that
+ * array that a call reads it has written before, so nothing carries over from one call to the
+ * next; but all calls on one GPU share the array: calls that overlap in time on the same GPU
+ * (different streams or threads) race and must be serialised by the caller.
+ * Limits: 1 <= n_params <= 2^34, 1 <= n_replicas <= HDET_MAX_REPLICAS; beyond them HDET_EINVAL.
+ * Errors: HDET_EINVAL, HDET_EHIP; the message is that of hdet_last_error(NULL).              */
+int hdet_warm_init_noalloc(const float* theta0_dev, float* params_dev, uint16_t* params_bf16_dev,
+                           int64_t n_params, int64_t plane_stride, int32_t n_replicas, double nu,
+                           uint64_t seed, void* stream);
+
 /* Forward, mean cross-entropy and backward of all N replicas on x_dev [N][B][d_in]
  * (fp32; rounded to bf16 on load in bf16 precision) and labels y_dev [N][B] int32 -- for
  * HDET_TRANSFORMER x_dev is token ids [N][B][S] int32 and y_dev the next-token targets

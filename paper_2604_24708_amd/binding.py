@@ -25,7 +25,7 @@ HDET_CH_LR, HDET_CH_DROPOUT, HDET_CH_WD, HDET_CH_LABEL_SMOOTH, HDET_CH_ATTN_TEMP
 HDET_FUSE_CONVERGE = 1
 
 EXPORTS = [
-    "hdet_workspace_bytes", "hdet_create", "hdet_warm_init", "hdet_forward_backward", "hdet_fanout_step",
+    "hdet_workspace_bytes", "hdet_create", "hdet_warm_init", "hdet_warm_init_noalloc", "hdet_forward_backward", "hdet_fanout_step",
     "hdet_converge", "hdet_autolr_update", "hdet_get_state", "hdet_set_state",
     "hdet_set_launch_shape", "hdet_last_error", "hdet_destroy",
 ]
@@ -118,6 +118,7 @@ def load_library(path: Optional[str] = None):
                                          C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     lib.hdet_create.argtypes = [C.POINTER(hdet_config), C.POINTER(hdet_buffers), C.POINTER(vp)]
     lib.hdet_warm_init.argtypes = [vp, vp, C.c_double, C.c_uint64]
+    lib.hdet_warm_init_noalloc.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, C.c_double, C.c_uint64, vp]
     lib.hdet_forward_backward.argtypes = [vp, vp, vp, C.POINTER(C.c_float)]
     lib.hdet_fanout_step.argtypes = [vp, vp, C.c_uint32]
     lib.hdet_converge.argtypes = [vp]
@@ -214,6 +215,12 @@ def hdet_create(cfg: hdet_config, params, opt_m, opt_v=None, grads=None, params_
 
 def hdet_warm_init(h, theta0, nu: float, seed: int):
     _check(load_library().hdet_warm_init(h, _ptr(theta0), nu, seed), h)
+
+
+def hdet_warm_init_noalloc(theta0, params, params_bf16, n_params: int, plane_stride: int, n_replicas: int,
+                           nu: float, seed: int, stream: Optional[int] = None):
+    _check(load_library().hdet_warm_init_noalloc(_ptr(theta0), _ptr(params), _ptr(params_bf16), n_params, plane_stride,
+                                                 n_replicas, nu, seed, stream))
 
 
 def hdet_forward_backward(h, x, y, want_losses: bool = False):

@@ -172,6 +172,8 @@ int write_shadow(hdet_handle* h) {
 
 }  // namespace
 
+void hdet_set_global_error(const std::string& msg) { g_create_error = msg; }
+
 extern "C" {
 
 int hdet_workspace_bytes(const hdet_config* cfg, int64_t plane_stride, size_t* plane_set_bytes,
@@ -305,8 +307,9 @@ int hdet_warm_init(hdet_handle* h, const float* theta0_dev, double nu, uint64_t 
   const float* lo = h->buf.params_dev;
   const float* hi = lo + (int64_t)h->cfg.n_replicas * h->buf.plane_stride;
   if (theta0_dev + p > lo && theta0_dev < hi) return fail(h, HDET_EINVAL, "theta0_dev must not overlap params_dev");
+  if (p > HDET_WARM_MAX_PARAMS) return fail(h, HDET_EINVAL, "hdet_warm_init takes at most 2^34 parameters per replica");
   hipError_t e = hdet_launch_warm_init(theta0_dev, h->buf.params_dev, p, h->buf.plane_stride, h->cfg.n_replicas,
-                                       h->ctrl_dev, nu, seed, h->stream);
+                                       h->ctrl_dev->warm_partial, &h->ctrl_dev->warm_sumsq, nu, seed, h->stream);
   if (e != hipSuccess) return hip_fail(h, e, "warm initialisation kernels");
   return write_shadow(h);
 }

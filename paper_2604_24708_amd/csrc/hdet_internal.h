@@ -99,7 +99,11 @@ hipError_t hdet_launch_shadow(const float* theta, uint16_t* shadow, int64_t n_pa
                               int n_replicas, int blocks, hipStream_t stream);
 hipError_t hdet_launch_controller(const hdet_controller_args& a, hipStream_t stream);
 hipError_t hdet_launch_warm_init(const float* theta0, float* theta, int64_t n_params, int64_t stride, int n_replicas,
-                                 hdet_ctrl* ctrl, double nu, uint64_t seed, hipStream_t stream);
+                                 double* partial, double* sumsq, double nu, uint64_t seed, hipStream_t stream);
+// the noise generator numbers blocks of four parameters with a 32-bit counter word
+#define HDET_WARM_MAX_PARAMS ((int64_t)1 << 34)
+// message that hdet_last_error(NULL) returns (entry points without a handle)
+void hdet_set_global_error(const std::string& msg);
 
 // ---------------------------------------------------------------------------------------
 // Replica-batched GEMMs.  The batch index z of a launch is split into up to three levels,

@@ -7,6 +7,9 @@
 // elements 4b..4b+3 come from philox(counter = (b, replica, 0, "WARM"), key = seed) through
 // two Box-Muller pairs, evaluated in fp64 (a one-off kernel; fp32 logs would lose the tail).
 
+#include <mutex>
+#include <string>
+
 #include "hdet_elem.h"
 #include "hdet_internal.h"
 
@@ -61,17 +64,83 @@ __global__ __launch_bounds__(256) void warm_noise_kernel(const float* theta0, fl
 
 }  // namespace
 
+// partial: HDET_WARM_PARTIALS doubles, sumsq: one double, both device memory that the three kernels own
+// for the duration of the call (every entry that is read is written first: nothing has to start at zero)
 hipError_t hdet_launch_warm_init(const float* theta0, float* theta, int64_t n_params, int64_t stride, int n_replicas,
-                                 hdet_ctrl* ctrl, double nu, uint64_t seed, hipStream_t s) {
+                                 double* partial, double* sumsq, double nu, uint64_t seed, hipStream_t s) {
   int64_t nb = (n_params + 256 * 64 - 1) / (256 * 64);
   if (nb > HDET_WARM_PARTIALS) nb = HDET_WARM_PARTIALS;
   if (nb < 1) nb = 1;
-  hipLaunchKernelGGL(sumsq_partial_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta0, n_params, ctrl->warm_partial);
-  hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(1), 0, s, ctrl->warm_partial, (int)nb, &ctrl->warm_sumsq);
+  hipLaunchKernelGGL(sumsq_partial_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta0, n_params, partial);
+  hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(1), 0, s, partial, (int)nb, sumsq);
   int64_t gb = ((n_params + 3) / 4 + 255) / 256;
   if (gb > 65536) gb = 65536;
   if (gb < 1) gb = 1;
   hipLaunchKernelGGL(warm_noise_kernel, dim3((unsigned)gb, n_replicas), dim3(256), 0, s, theta0, theta, n_params, stride,
-                     &ctrl->warm_sumsq, nu, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32));
+                     sumsq, nu, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32));
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// The same initialisation for callers that cannot allocate device memory: no handle (hdet_create
+// allocates the control block that holds the partial sums above), the partial sums live in a
+// file-scope device array instead.  Every GPU holds its own copy of the array for the life of
+// the process; its address on a device is looked up once, with that device current.
+// ---------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kScratchDoubles = HDET_WARM_PARTIALS + 1;                   // partial sums, then their total
+static __device__ __align__(256) double scratch[kScratchDoubles];        // 8200 bytes per GPU
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// device address of `scratch` on the current device (host code must never pass the array's name itself)
+int scratch_on_current_device(double** out, std::string* why) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { *why = std::string("hipGetDevice: ") + hipGetErrorString(e); return HDET_EHIP; }
+  if (dev < 0 || dev >= kMaxDevices) { *why = "device ordinal out of range"; return HDET_EHIP; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    double* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) { *why = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e); return HDET_EHIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return HDET_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" int hdet_warm_init_noalloc(const float* theta0_dev, float* params_dev, uint16_t* params_bf16_dev,
+                                      int64_t n_params, int64_t plane_stride, int32_t n_replicas, double nu,
+                                      uint64_t seed, void* stream) {
+  auto bad = [](int code, const std::string& msg) { hdet_set_global_error(msg); return code; };
+  if (!theta0_dev || !params_dev) return bad(HDET_EINVAL, "theta0_dev and params_dev are required");
+  if (!aligned16(theta0_dev) || !aligned16(params_dev) || !aligned16(params_bf16_dev))
+    return bad(HDET_EINVAL, "device pointers must be 16-byte aligned");
+  if (n_replicas < 1 || n_replicas > HDET_MAX_REPLICAS) return bad(HDET_EINVAL, "n_replicas out of range");
+  if (n_params < 1 || n_params > HDET_WARM_MAX_PARAMS)
+    return bad(HDET_EINVAL, "n_params must be in 1 .. 2^34 (the noise generator numbers blocks of four parameters with 32 bits)");
+  if (plane_stride < n_params || (plane_stride & 3)) return bad(HDET_EINVAL, "plane_stride must be >= n_params and a multiple of 4");
+  if (!(nu >= 0.0)) return bad(HDET_EINVAL, "nu must be >= 0");
+  const float* lo = params_dev;
+  const float* hi = lo + (int64_t)n_replicas * plane_stride;
+  if (theta0_dev + n_params > lo && theta0_dev < hi) return bad(HDET_EINVAL, "theta0_dev must not overlap params_dev");
+  double* ptr = nullptr;
+  std::string why;
+  const int rc = scratch_on_current_device(&ptr, &why);
+  if (rc != HDET_OK) return bad(rc, why);
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = hdet_launch_warm_init(theta0_dev, params_dev, n_params, plane_stride, n_replicas, ptr, ptr + HDET_WARM_PARTIALS,
+                                       nu, seed, s);
+  if (e == hipSuccess && params_bf16_dev)
+    e = hdet_launch_shadow(params_dev, params_bf16_dev, n_params, plane_stride, n_replicas, 4096, s);
+  if (e != hipSuccess) return bad(HDET_EHIP, std::string("warm initialisation kernels: ") + hipGetErrorString(e));
+  return HDET_OK;
 }
