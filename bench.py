@@ -33,6 +33,7 @@ CONVERGE_BYTES = 8        # standalone converge: 4 read + 4 written
 # default workload; valid only for the kernel source it was taken with.
 TRAFFIC_KERNEL_SHA = "27c4de97d1e28446"
 TRAFFIC_BYTES_PER_REPLICA_ELEMENT = 224.000e9 / 8e9
+TRAFFIC_SOURCE = "profiles/update_kernels_flat_N8_P1e9_hbm_counters.txt"
 
 
 def measured_traffic(n, p):
@@ -48,15 +49,11 @@ def measured_traffic(n, p):
 
 
 def oracle_baseline(n, t_sync, p_sample, steps):
-    """The CPU oracle as it stands on a bounded sample: same N, T, optimizer; P = p_sample."""
+    """The CPU oracle as it stands on a bounded sample: same N, T, optimizer; P = p_sample.  Its flat path is
+    element-wise numpy, which runs on one thread whatever the size of the BLAS pool.  Returns seconds."""
     import numpy as np
     import hdet_inputs as I
     from oracle import hdet_oracle as O
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = 1
     cfg = O.Config(n_replicas=n, total_steps=steps, sync_interval=t_sync, warm_steps=0, lr_max=1e-3,
                    alpha=0.1, autolr_enabled=True, optimizer=O.ADAMW, weight_decay=0.01,
                    grad_mode=O.GRAD_PER_REPLICA, seed=7)
@@ -65,8 +62,29 @@ def oracle_baseline(n, t_sync, p_sample, steps):
     t0 = time.perf_counter()
     for t in range(1, steps + 1):
         orc.step(g, 1.0 + 0.01 * np.arange(n))
-    dt = time.perf_counter() - t0
-    return dt, cores
+    return time.perf_counter() - t0
+
+
+def _oracle_chunk(job):
+    n, t_sync, p_chunk, steps = job
+    if p_chunk == 0:
+        return 0.0          # start-up call: the process has imported what it needs
+    return oracle_baseline(n, t_sync, p_chunk, steps)
+
+
+def oracle_baseline_all_cores(n, t_sync, p_sample, steps):
+    """The same oracle run on every host core at once: the update and the converge are element-wise in P, so
+    each process takes a slice of the parameter axis (the controller's N scalars are recomputed by each).
+    Returns (wall seconds, processes)."""
+    import concurrent.futures
+    import multiprocessing
+    procs = max(1, min(os.cpu_count() or 1, 16))
+    chunk = p_sample // procs
+    with concurrent.futures.ProcessPoolExecutor(procs, mp_context=multiprocessing.get_context("spawn")) as ex:
+        list(ex.map(_oracle_chunk, [(n, t_sync, 0, steps)] * procs))          # spin the processes up
+        t0 = time.perf_counter()
+        list(ex.map(_oracle_chunk, [(n, t_sync, chunk, steps)] * procs))
+        return time.perf_counter() - t0, procs
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
@@ -225,6 +243,104 @@ def transformer_workload(args):
             "loss_first_replica": float(st.l_step[0])}
 
 
+def cfg0_leg():
+    """The small parity configuration as a latency figure: N = 4 replicas of the MLP 64-128-10 in fp32, batch 32,
+    SGD momentum 0.9, one-cycle peak 0.05 over 40 steps, alpha 0.2, T = 4, auto-LR on; the full 40-step run on the
+    device (second run timed, kernels warm) and in the oracle."""
+    import numpy as np
+    import torch
+    import hdet_inputs as I
+    import paper_2604_24708_amd as H
+    from oracle import hdet_oracle as O
+    from oracle import mlp_oracle as M
+    dev = torch.device("cuda:0")
+    n, B, T, S = 4, 32, 4, 40
+    widths = [64, 128, 10]
+    P = I.mlp_param_count(widths)
+    stride = (P + 3) // 4 * 4
+    th0 = I.mlp_init(n, widths, I.SEED_INIT)
+    batches = [I.mlp_batch(n, B, widths[0], I.SEED_DATA, t, widths, I.SEED_TEACHER) for t in range(1, S + 1)]
+    dev_batches = [(torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)) for x, y in batches]
+    stream = torch.cuda.current_stream()
+
+    def run_device():
+        theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
+        theta[:, :P] = torch.from_numpy(th0).to(dev)
+        m, g = torch.zeros_like(theta), torch.zeros_like(theta)
+        cfg = H.make_config(n_replicas=n, sync_interval=T, total_steps=S, warm_steps=12, lr_max=0.05, alpha=0.2,
+                            autolr_enabled=1, optimizer=H.HDET_SGDM, momentum=0.9, weight_decay=0.0,
+                            grad_mode=H.HDET_GRAD_PER_REPLICA, precision=H.HDET_FP32, model_kind=H.HDET_MLP,
+                            widths=widths, batch=B, seed=I.SEED_PERM, stream=stream.cuda_stream)
+        _, _, ws_bytes = H.hdet_workspace_bytes(cfg, stride)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+        h = H.hdet_create(cfg, theta, m, None, grads=g, workspace=ws, plane_stride=stride)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(1, S + 1):
+            H.hdet_forward_backward(h, *dev_batches[t - 1])
+            H.hdet_fanout_step(h, None, H.HDET_FUSE_CONVERGE)
+            if t % T == 0:
+                H.hdet_converge(h)
+                H.hdet_autolr_update(h, None)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        H.hdet_destroy(h)
+        return dt
+
+    run_device()
+    gpu_s = run_device()
+    ocfg = O.Config(n_replicas=n, total_steps=S, sync_interval=T, warm_steps=12, lr_max=0.05, alpha=0.2,
+                    autolr_enabled=True, optimizer=O.SGDM, momentum=0.9, weight_decay=0.0,
+                    grad_mode=O.GRAD_PER_REPLICA, seed=I.SEED_PERM)
+    orc = O.HDETOracle(ocfg, th0)
+    t0 = time.perf_counter()
+    for t in range(1, S + 1):
+        x, y = batches[t - 1]
+        out = [M.mlp_loss_and_grad(orc.theta[r], x[r], y[r], widths) for r in range(n)]
+        orc.step(np.stack([o[1] for o in out]), [o[0] for o in out])
+    cpu_s = time.perf_counter() - t0
+    return {"workload": "N=4 x MLP 64-128-10 fp32, batch 32/replica, SGD momentum 0.9, 40 steps, T=4, auto-LR on",
+            "gpu_run_ms": gpu_s * 1e3, "gpu_ms_per_step": gpu_s * 1e3 / S, "gpu_replica_steps_per_s": n * S / gpu_s,
+            "oracle_run_ms": cpu_s * 1e3, "oracle_replica_steps_per_s": n * S / cpu_s, "oracle_cores": 1,
+            "note": "launch-latency bound (9 610 parameters per replica); the oracle runs it on one thread"}
+
+
+def warm_init_leg(H, theta, theta0, n, P, stride, stream):
+    """Eq. 10 at the headline size: theta0 [P] read, N perturbed planes written (4 (N + 1) P algorithmic bytes)."""
+    import torch
+    ms = []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        H.hdet_warm_init_noalloc(theta0, theta, None, P, stride, n, 0.01, 4242, stream.cuda_stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    best = min(ms)
+    nbytes = 4.0 * (n + 1) * P
+    return {"ms": best, "algorithmic_bytes": nbytes, "achieved": nbytes / (best * 1e-3) / 1e9, "unit": "GB/s",
+            "frac_of_hbm_peak": nbytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
+def stream_reference(a, b):
+    """What the memory system gives plain streams of the headline size on this machine, same buffers: a device copy
+    (1 read + 1 write per element) and a three-stream add (2 reads + 1 write), by the tensor library's kernels."""
+    import torch
+    out = {}
+    for name, fn, streams in (("copy_1r1w", lambda: b.copy_(a), 2), ("add_2r1w", lambda: torch.add(a, b, out=b), 3)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        out[name] = {"ms": ms, "GBps": streams * a.numel() * 4 / (ms * 1e-3) / 1e9}
+    return out
+
+
 def shared_state_leg(H, I, theta, g, m, v, n, P, T, stride, stream, args):
     """2 T steps of shared-gradient AdamW with one plane of each moment, timed like the main leg."""
     import torch
@@ -291,6 +407,22 @@ def main():
         print("bench.py: this build runs on one GPU only (the replicas are an axis in one GPU's memory); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    # The CPU oracle first, before this process touches the GPU: its all-cores figure starts worker processes.
+    cpu_baseline = None
+    if args.workload in ("both", "flat") and not args.no_cpu_baseline:
+        n, P, T = args.replicas, int(args.params), args.sync_interval
+        p_sample, o_steps = 4_000_000, T + 1
+        odt = oracle_baseline(n, T, p_sample, o_steps)
+        cpu_baseline = {"value": n * o_steps / odt * (p_sample / P), "unit": "replica-steps/s",
+                        "cores": 1, "kind": "oracle",
+                        "sample": f"oracle (numpy, fp64 arithmetic, element-wise: one thread) on N={n} x P={p_sample} for "
+                                  f"{o_steps} steps incl. one converge+controller, {odt:.1f} s; scaled linearly in P to P={P:.3g}"}
+        p_all = 16_000_000
+        adt, procs = oracle_baseline_all_cores(n, T, p_all, o_steps)
+        cpu_baseline["all_cores"] = {"value": n * o_steps / adt * (p_all / P), "unit": "replica-steps/s", "cores": procs,
+                                     "sample": f"the same oracle in {procs} processes, each on a slice of P={p_all} "
+                                               f"(element-wise in P), {adt:.1f} s wall; scaled linearly in P to P={P:.3g}"}
 
     import torch
     import hdet_inputs as I
@@ -396,6 +528,9 @@ def main():
                    "controller_updates": int(st.k)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(n, P),
+                     # not a reading of this run: the stored counter figure of the summary named here, null once the
+                     # kernel source or the workload differs from what the counters were taken on
+                     "traffic_source": TRAFFIC_SOURCE if measured_traffic(n, P) is not None else None,
                      "kernel": "hdet_update_kernel", "kernel_ms": upd_ms,
                      "kernel_ms_median": upd_all[len(upd_all) // 2], "kernel_ms_min": upd_all[0],
                      "algorithmic_bytes_per_launch": bytes_per_launch},
@@ -405,6 +540,9 @@ def main():
         out["converge_standalone"] = {"kernel_ms": cms, "achieved": CONVERGE_BYTES * n * P / (cms * 1e-3) / 1e9,
                                       "unit": "GB/s"}
     if args.workload == "both" and not args.shared_state:
+        out["stream_reference"] = stream_reference(g.view(-1)[:n * P], m.view(-1)[:n * P])
+        m.zero_()
+        out["warm_init"] = warm_init_leg(H, theta, g[0, :P], n, P, stride, stream)
         # the paper's own mode on the same buffers: every replica applies the mean gradient, and
         # AdamW's moments, which then do not depend on the replica, are kept once
         out["shared_gradient_one_set_of_moments"] = shared_state_leg(H, I, theta, g, m, v, n, P, T, stride, stream, args)
@@ -417,13 +555,12 @@ def main():
         targs.steps, targs.warmup = min(args.steps, 16), min(args.warmup, 4)
         out["transformer_bf16"] = transformer_workload(targs)
         torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
-        p_sample, o_steps = 10_000_000, T + 1
-        odt, cores = oracle_baseline(n, T, p_sample, o_steps)
-        out["cpu_baseline"] = {"value": n * o_steps / odt * (p_sample / P), "unit": "replica-steps/s",
-                               "cores": cores, "kind": "oracle",
-                               "sample": f"oracle (numpy, fp64 arithmetic) on N={n} x P={p_sample} for {o_steps} steps "
-                                         f"incl. one converge+controller, {odt:.1f} s; scaled linearly in P to P={P:.3g}"}
+        targs.tf_config, targs.steps, targs.warmup = "12L", min(args.steps, 8), min(args.warmup, 2)
+        out["transformer_12L_bf16"] = transformer_workload(targs)
+        torch.cuda.empty_cache()
+        out["mlp_fp32_small"] = cfg0_leg()
+    if cpu_baseline is not None:
+        out["cpu_baseline"] = cpu_baseline
     print(json.dumps(out))
 
 

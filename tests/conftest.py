@@ -29,3 +29,14 @@ def load_golden(name):
 @pytest.fixture
 def golden():
     return load_golden
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Largest element-wise error ratio seen per mixed-precision check (tests/harness.py: check_bf16_tensor)."""
+    try:
+        import harness
+    except Exception:
+        return
+    if harness.observed_elem_err:
+        worst = sorted(harness.observed_elem_err.items(), key=lambda kv: -kv[1])[:12]
+        terminalreporter.write_line("largest element-wise bf16 error ratios: " + ", ".join(f"{k}={v:.3f}" for k, v in worst))

@@ -25,6 +25,77 @@ def rel_err(a: np.ndarray, b: np.ndarray) -> float:
     return float(np.max(np.abs(a - b) / np.maximum(np.abs(b), floor)))
 
 
+def rel_err_detail(a: np.ndarray, b: np.ndarray, tol: float):
+    """rel_err together with the indices of the entries that pass only thanks to the floor: those whose
+    plain relative error |a_i - b_i| / |b_i| exceeds `tol` while the floored one does not."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    if a.size == 0:
+        return 0.0, np.zeros((0, a.ndim), dtype=np.int64)
+    rms = float(np.sqrt(np.mean(b * b)))
+    floor = max(rms / 32.0, 1e-30)
+    diff = np.abs(a - b)
+    floored = diff / np.maximum(np.abs(b), floor)
+    needs = (diff > tol * np.abs(b)) & (floored <= tol)
+    return float(np.max(floored)), np.argwhere(needs)
+
+
+def norm_err(a, b) -> float:
+    """||a - b|| / ||b|| over one tensor."""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def elem_err(a, b) -> float:
+    """max_i |a_i - b_i| / (|b_i| + rms(b)) over one tensor: the element-wise companion of norm_err for
+    mixed-precision results.  Both sides round to bfloat16 at the same points, but a value that sits next
+    to a rounding boundary may round the other way (one part in 256 of that value), and an entry of a
+    gradient sums many such values, so single entries differ by a few percent of their own size or of the
+    tensor's scale, whichever is larger -- far more than the tensor norm does.  A wrong entry is another
+    matter: a missing row, a value taken from a neighbour or a stale buffer is off by about the tensor's
+    scale and gives a ratio of 0.5 or more."""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    if a.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(b * b)))
+    return float(np.max(np.abs(a - b) / (np.abs(b) + max(rms, 1e-30))))
+
+
+# Bound on elem_err for mixed-precision gradients: see check_bf16_tensor.
+ELEM_TOL_BF16 = 0.25
+observed_elem_err = {}          # largest ratio seen per tag, for the record printed at the end of a run
+
+
+def check_bf16_tensor(a, b, norm_tol: float, tag, elem_tol: float = ELEM_TOL_BF16):
+    """One mixed-precision tensor against the oracle: its norm-wise error (what bf16 rounding noise adds
+    up to over the tensor) and every single entry (elem_err), so that neither a wrong block nor a single
+    wrong entry of the size of the tensor's scale passes."""
+    ne, ee = norm_err(a, b), elem_err(a, b)
+    key = str(tag)
+    observed_elem_err[key] = max(observed_elem_err.get(key, 0.0), ee)
+    assert ne <= norm_tol, (tag, "norm", ne)
+    assert ee <= elem_tol, (tag, "element", ee)
+
+
+def mlp_tied_rows_equalised(g_dev, g_ref, widths, ties):
+    """Copies of two flat MLP gradients in which the entries that a ReLU tie decides are taken out of an
+    element-wise comparison (set to the oracle's value on both sides): a hidden unit whose pre-activation is
+    zero to within the rounding error of a mixed-precision product may pass its gradient on one side and not
+    on the other -- both are valid subgradients -- and that switches one batch row's contribution to row `unit`
+    of that layer's weight gradient and to its bias gradient on and off.  (Layers below see the difference as one
+    term in 4096 of one batch row's gradient, far below the element-wise bound.)"""
+    a, b = np.array(g_dev, copy=True), np.asarray(g_ref)
+    off = 0
+    for i in range(len(widths) - 1):
+        d_in, d_out = widths[i], widths[i + 1]
+        if i < len(ties):
+            for unit in sorted({int(u) for _, u in ties[i]}):
+                a[off + unit * d_in: off + (unit + 1) * d_in] = b[off + unit * d_in: off + (unit + 1) * d_in]
+                a[off + d_out * d_in + unit] = b[off + d_out * d_in + unit]
+        off += d_out * d_in + d_out
+    return a, b
+
+
 def ulp_diff_f32(a, b) -> int:
     a = np.asarray(a, dtype=np.float32).view(np.int32).astype(np.int64)
     b = np.asarray(b, dtype=np.float32).view(np.int32).astype(np.int64)

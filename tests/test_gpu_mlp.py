@@ -6,7 +6,7 @@ import torch
 
 import hdet_inputs as I
 import paper_2604_24708_amd as H
-from harness import check_state, library_config, oracle_config, rel_err
+from harness import check_bf16_tensor, check_state, library_config, mlp_tied_rows_equalised, oracle_config, rel_err
 from oracle import hdet_oracle as O
 from oracle import mlp_oracle as M
 
@@ -284,12 +284,16 @@ def test_bf16_gradients_at_device_parameters(widths, batch, n, check):
                                   want_losses=True)
     g_dev = run.g.cpu().numpy()[:, :run.P]
     for r in (check or range(n)):
-        loss, g = M.mlp_loss_and_grad(run.orc.theta[r], x[r], y[r], widths, bf16=True)
+        info = {"tie_tau": 1e-5}
+        loss, g = M.mlp_loss_and_grad(run.orc.theta[r], x[r], y[r], widths, bf16=True, info=info)
         assert abs(out[r] - loss) <= 2e-3
+        assert sum(len(t) for t in info["relu_ties"]) <= 1e-4 * batch * sum(widths[1:-1])      # ties are rare
+        g_cmp, ref_cmp = mlp_tied_rows_equalised(g_dev[r], g, widths, info["relu_ties"])
         off = 0
         for i in range(len(widths) - 1):          # per tensor: a transposed or shifted block would show
             for size in (widths[i + 1] * widths[i], widths[i + 1]):
                 assert norm_err(g_dev[r, off:off + size], g[off:off + size]) <= 2e-2, (r, i, size)
+                check_bf16_tensor(g_cmp[off:off + size], ref_cmp[off:off + size], 2e-2, ("mlp", tuple(widths), r, i, size))
                 off += size
     run.close()
 
