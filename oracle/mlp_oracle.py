@@ -70,8 +70,7 @@ def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Se
     If `info` is given, info["relu_margin"] receives the smallest |pre-activation| over all
     hidden units: the gradient is discontinuous where a pre-activation is zero, so a
     comparison against an implementation in another precision is only meaningful when this
-    margin exceeds that implementation's rounding error.  With info["tie_tau"] set on entry,
-    info["relu_ties"] lists, per hidden layer, the (batch row, unit) pairs closer to zero than that.
+    margin exceeds that implementation's rounding error.
 
     relu_tie = (tau, open): hidden units whose |pre-activation| is below tau -- ties at the kink of
     the ReLU as far as an fp32 implementation can tell -- are all taken as open (the unit passes its
@@ -96,9 +95,6 @@ def mlp_loss_and_grad(flat: np.ndarray, x: np.ndarray, y: np.ndarray, widths: Se
             acts.append(q(np.where(gate, zi, 0.0)))
     if info is not None:
         info["relu_margin"] = min([float(np.min(np.abs(p))) for p in pre[:-1]] + [float("inf")])
-        if "tie_tau" in info:
-            # hidden units (row of the batch, unit) per hidden layer whose pre-activation is within tie_tau of the kink
-            info["relu_ties"] = [np.argwhere(np.abs(p) < info["tie_tau"]) for p in pre[:-1]]
     loss, dz = softmax_xent(pre[-1], y.astype(np.int64), label_smoothing)
     grads: List[np.ndarray] = [None] * (2 * n_layers)
     for i in range(n_layers - 1, -1, -1):

@@ -335,6 +335,9 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   a.ctrl_out = h->ctrl_dev;
   a.n_params = param_count(c);
   a.stride = h->buf.plane_stride;
+  // a model handle in shared-gradient mode has formed the replica mean itself, in plane 0 of its gradient buffer
+  const bool one_plane = !grads_dev && c.model_kind != HDET_FLAT && c.grad_mode == HDET_GRAD_SHARED;
+  a.grad_stride = one_plane ? 0 : a.stride;
   a.n_replicas = c.n_replicas;
   a.wd_channel = h->wd_channel;
   a.first_step = t == 1;

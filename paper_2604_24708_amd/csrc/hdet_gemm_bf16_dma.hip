@@ -294,7 +294,7 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
     drop_scale = 1.f / (1.f - p);
   }
   // column sums of the stored result over the wavefront's rows, for the columns this lane stores (per strip column group)
-  constexpr bool kColsum = EPI == HDET_EPI_GELUGRAD_BF16;
+  constexpr bool kColsum = EPI == HDET_EPI_GELUGRAD_BF16 || EPI == HDET_EPI_MASK_BF16;
   f4 csum[WNT / JG];
 #pragma unroll
   for (int jg = 0; jg < WNT / JG; ++jg) csum[jg] = f4{0.f, 0.f, 0.f, 0.f};

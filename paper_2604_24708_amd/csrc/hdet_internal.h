@@ -54,6 +54,8 @@ struct hdet_update_args {
   hdet_ctrl* ctrl_out;     // same block, for lr_used
   int64_t n_params;        // P
   int64_t stride;          // plane stride in elements
+  int64_t grad_stride;     // plane stride of `grad`: `stride`, or 0 when every replica applies the one plane at `grad`
+                           // (the model paths in shared-gradient mode form the replica mean themselves)
   int32_t n_replicas;
   int32_t lr_channel;      // learning-rate channel of the parameter group being updated
   int32_t wd_channel;      // channel index of a weight-decay channel or -1
@@ -162,7 +164,7 @@ struct hdet_bgemm_args {
   // replica * 65536 + drop_site, drop_stream) and key drop_seed; element = row * ldc + column
   const hdet_ctrl* drop_ctrl; int drop_channel;
   uint32_t drop_step, drop_site, drop_stream, drop_seed_lo, drop_seed_hi;
-  // HDET_EPI_GELUGRAD_BF16, optional (n1 = n2 = 1): colsum[(replica * ceil(m / 128) + m / 128) * n + column] receives the
+  // HDET_EPI_GELUGRAD_BF16 and HDET_EPI_MASK_BF16 on the LDS-direct kernel, optional (n1 = n2 = 1): colsum[(replica * ceil(m / 128) + m / 128) * n + column] receives the
   // sum of C as stored over that 128-row block of the column (stage 1 of the bias gradient of the layer whose
   // pre-activation gradient C is); colsum_bs is unused padding for alignment
   float* colsum;

@@ -72,10 +72,12 @@ __device__ __forceinline__ float smoothing_of(const hdet_ctrl* ctrl, int ls_chan
 //   loss_b = log(sum exp(z - max)) - (1 - eps) (z_y - max) - eps mean_c (z_c - max),
 //   dlogits = (softmax - q) / B.
 // 4 rows per 256-thread block.
+// grad_rows: the row count the gradient is divided by -- `rows`, or N * rows when the replica mean of the
+// gradients is formed downstream as one sum over all replicas' rows (shared-gradient mode).
 template <typename T>
 __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const int32_t* labels, int rows,
                                                    int classes, T* dlogits, float* row_loss, const hdet_ctrl* ctrl,
-                                                   int ls_channel) {
+                                                   int ls_channel, int grad_rows) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(256) void xent_kernel(const float* logits, const in
   se = wave_sum(se);
   sz = wave_sum(sz);
   const int y = labels[gr];
-  const float inv = 1.f / se, invb = 1.f / (float)rows;
+  const float inv = 1.f / se, invb = 1.f / (float)grad_rows;
   const float hit = 1.f - eps, miss = eps / (float)classes;
   T* d = dlogits + gr * classes;
   for (int c = lane; c < classes; c += 64) put(d + c, (expf(z[c] - mx) * inv - (c == y ? hit : 0.f) - miss) * invb);
@@ -131,12 +133,12 @@ __device__ __forceinline__ void xent_block_reduce(float& a, float& b, float* red
 template <typename T, int BS, int NV, bool SUMS>
 __global__ __launch_bounds__(BS, SUMS ? 2 : 4) void xent_row_kernel(const float* logits, const int32_t* labels, int rows, int classes,
                                                       int rows_per_block, T* dlogits, float* row_loss, const hdet_ctrl* ctrl,
-                                                      int ls_channel, float* colsum) {
+                                                      int ls_channel, float* colsum, int grad_rows) {
   constexpr int NW = BS / 64;
   __shared__ float red[NW], red2[NW];
   const int r = blockIdx.y, tid = threadIdx.x, c4 = classes >> 2;
   const float eps = smoothing_of(ctrl, ls_channel, r);
-  const float invb = 1.f / (float)rows, hit = 1.f - eps, miss = eps / (float)classes;
+  const float invb = 1.f / (float)grad_rows, hit = 1.f - eps, miss = eps / (float)classes;
   const float hitb = hit * invb, missb = miss * invb;
   const int row0 = blockIdx.x * rows_per_block;
   const int row1 = row0 + rows_per_block < rows ? row0 + rows_per_block : rows;
@@ -247,6 +249,7 @@ struct hdet_mlp_plan {
   float* logits;
   void* dz_a; void* dz_b;                // ping-pong activation gradients, fp32 or bf16
   float* row_loss;
+  float* colsum_part;                    // bf16: [N][ceil(B / 128)][widest layer] partial column sums of an activation gradient
   bool bf16;
   int ls_channel;                        // label-smoothing channel or -1
 };
@@ -255,13 +258,14 @@ bool hdet_xent_wide(int classes) { return classes >= 2048 && classes <= 32768 &&
 
 hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* labels, int rows, int classes, void* dlogits,
                             float* row_loss, int n_replicas, const hdet_ctrl* ctrl, int ls_channel, hipStream_t s,
-                            float* colsum, int rows_per_block) {
+                            float* colsum, int rows_per_block, int grad_rows) {
+  if (grad_rows <= 0) grad_rows = rows;
   if (hdet_xent_wide(classes)) {
     const bool sums = colsum != nullptr && rows_per_block > 0;
     if (!sums) rows_per_block = 1;
     const dim3 grid((rows + rows_per_block - 1) / rows_per_block, n_replicas);
 #define HDET_XENT_ROW(T, BS, NV, SUMS) \
-  hipLaunchKernelGGL((xent_row_kernel<T, BS, NV, SUMS>), grid, dim3(BS), 0, s, logits, labels, rows, classes, rows_per_block, (T*)dlogits, row_loss, ctrl, ls_channel, colsum)
+  hipLaunchKernelGGL((xent_row_kernel<T, BS, NV, SUMS>), grid, dim3(BS), 0, s, logits, labels, rows, classes, rows_per_block, (T*)dlogits, row_loss, ctrl, ls_channel, colsum, grad_rows)
 #define HDET_XENT_ROW_T(BS, NV, SUMS)        \
   do {                                       \
     if (bf16) HDET_XENT_ROW(uint16_t, BS, NV, SUMS); \
@@ -279,8 +283,8 @@ hipError_t hdet_launch_xent(bool bf16, const float* logits, const int32_t* label
     return hipGetLastError();
   }
   const dim3 grid((rows + 3) / 4, n_replicas);
-  if (bf16) hipLaunchKernelGGL(xent_kernel<uint16_t>, grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss, ctrl, ls_channel);
-  else hipLaunchKernelGGL(xent_kernel<float>, grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss, ctrl, ls_channel);
+  if (bf16) hipLaunchKernelGGL(xent_kernel<uint16_t>, grid, dim3(256), 0, s, logits, labels, rows, classes, (uint16_t*)dlogits, row_loss, ctrl, ls_channel, grad_rows);
+  else hipLaunchKernelGGL(xent_kernel<float>, grid, dim3(256), 0, s, logits, labels, rows, classes, (float*)dlogits, row_loss, ctrl, ls_channel, grad_rows);
   return hipGetLastError();
 }
 
@@ -306,6 +310,7 @@ int hdet_mlp_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string*
   for (int i = 0; i < L; ++i) if ((size_t)cfg.dims.widths[i] > maxw) maxw = cfg.dims.widths[i];
   total += 2 * align_up(n * b * maxw * esz);                                  // dz ping-pong
   total += align_up(n * b * sizeof(float));                                   // row losses
+  if (bf16) total += align_up(n * ((b + 127) / 128) * maxw * sizeof(float));  // column sums per 128-row chunk
   *bytes = total;
   return HDET_OK;
 }
@@ -337,7 +342,8 @@ hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, 
   }
   p->dz_a = ws; ws += align_up(n * b * maxw * esz);
   p->dz_b = ws; ws += align_up(n * b * maxw * esz);
-  p->row_loss = (float*)ws;
+  p->row_loss = (float*)ws; ws += align_up(n * b * sizeof(float));
+  p->colsum_part = p->bf16 ? (float*)ws : nullptr;
   return p;
 }
 
@@ -352,6 +358,10 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
   const float* theta = p->buf.params_dev;
   float* grads = p->buf.grads_dev;
   p->act[0] = const_cast<void*>(x);
+  // Shared-gradient mode (Algorithm 1, "AllReduce gradients"): every replica applies the replica mean, so only the
+  // mean is formed -- the N batches are rows of one matrix, the weight gradient is one product over K = N B rows and
+  // the loss gradient carries the 1 / (N B); the result goes to plane 0 of the gradient buffer.
+  const bool shared = c.grad_mode == HDET_GRAD_SHARED;
 
   // forward: Y = act(X W^T + b)
   for (int i = 0; i < L; ++i) {
@@ -365,7 +375,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
   }
   // loss and dlogits
   float* dz = (float*)p->dz_a; float* dz_next = (float*)p->dz_b;
-  if (hipError_t e = hdet_launch_xent(false, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0)) return e;
+  if (hipError_t e = hdet_launch_xent(false, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0, shared ? N * B : B)) return e;
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   // backward
   for (int i = L - 1; i >= 0; --i) {
@@ -374,9 +384,9 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
     g.a = dz; g.a_rs = 1; g.a_cs = w[i + 1]; g.a_s[0] = (int64_t)B * w[i + 1];     // A(o,b) = dZ[b][o]
     g.b = (const float*)p->act[i]; g.b_rs = w[i]; g.b_cs = 1; g.b_s[0] = (int64_t)B * w[i];   // B(b,k) = X[b][k]
     g.c = grads + p->w_off[i]; g.c_rs = w[i]; g.c_s[0] = ps;
-    g.m = w[i + 1]; g.n = w[i]; g.k = B;
-    if (hipError_t e = hdet_launch_sgemm(g, HDET_SEPI_NONE, N, s)) return e;
-    hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 63) / 64, N), dim3(256), 0, s, dz, B, w[i + 1],
+    g.m = w[i + 1]; g.n = w[i]; g.k = shared ? N * B : B;
+    if (hipError_t e = hdet_launch_sgemm(g, HDET_SEPI_NONE, shared ? 1 : N, s)) return e;
+    hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 63) / 64, shared ? 1 : N), dim3(256), 0, s, dz, shared ? N * B : B, w[i + 1],
                        (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
     if (i > 0) {
       // dX = dZ W, masked by the ReLU of the layer below
@@ -403,6 +413,7 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
   const uint16_t* wbf = p->buf.params_bf16_dev;     // weights as the GEMMs see them
   float* grads = p->buf.grads_dev;
   hipError_t e;
+  const bool shared = c.grad_mode == HDET_GRAD_SHARED;      // one gradient plane: see forward_backward_f32
 
   const int64_t nx = (int64_t)N * B * w[0];
   int cb = (int)((nx + 255) / 256); if (cb > 4096) cb = 4096;
@@ -419,18 +430,26 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
     if (e != hipSuccess) return e;
   }
   uint16_t* dz = (uint16_t*)p->dz_a; uint16_t* dz_next = (uint16_t*)p->dz_b;
-  if (hipError_t e = hdet_launch_xent(true, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0)) return e;
+  const int nchunks = (B + 127) / 128;
+  bool have_part = false;
+  if (hipError_t e = hdet_launch_xent(true, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0, shared ? N * B : B)) return e;
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   for (int i = L - 1; i >= 0; --i) {
     hdet_bgemm_args g = {};                          // dW = dZ^T X
     g.a = dz; g.lda = w[i + 1]; g.a_s[0] = (int64_t)B * w[i + 1];               // A(o,b) = dZ[b][o]
     g.b = (const uint16_t*)p->act[i]; g.ldb = w[i]; g.b_s[0] = (int64_t)B * w[i];   // B(b,k) = X[b][k]
     g.c = grads + p->w_off[i]; g.ldc = w[i]; g.c_s[0] = ps;
-    g.m = w[i + 1]; g.n = w[i]; g.k = B;
-    e = hdet_launch_bgemm(g, false, false, HDET_EPI_F32, N, s);
+    g.m = w[i + 1]; g.n = w[i]; g.k = shared ? N * B : B;
+    e = hdet_launch_bgemm(g, false, false, HDET_EPI_F32, shared ? 1 : N, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bias_grad_kernel<uint16_t>, dim3((w[i + 1] + 63) / 64, N), dim3(256), 0, s, dz, B, w[i + 1],
-                       (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
+    // db = column sums of dZ: from the 128-row partial sums when the product that formed dZ left them, else from dZ itself
+    if (have_part)
+      hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 63) / 64, shared ? 1 : N), dim3(256), 0, s, p->colsum_part,
+                         shared ? N * nchunks : nchunks, w[i + 1], (int64_t)nchunks * w[i + 1], grads + p->b_off[i], ps);
+    else
+      hipLaunchKernelGGL(bias_grad_kernel<uint16_t>, dim3((w[i + 1] + 63) / 64, shared ? 1 : N), dim3(256), 0, s, dz, shared ? N * B : B, w[i + 1],
+                         (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
+    have_part = false;
     if (i > 0) {                                     // dX = dZ W, through the ReLU below
       hdet_bgemm_args d = {};
       d.a = dz; d.lda = w[i + 1]; d.a_s[0] = (int64_t)B * w[i + 1];
@@ -438,6 +457,11 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
       d.c = dz_next; d.ldc = w[i]; d.c_s[0] = (int64_t)B * w[i];
       d.m = B; d.n = w[i]; d.k = w[i + 1];
       d.mask = (const uint16_t*)p->act[i]; d.mask_ld = w[i]; d.mask_bs = (int64_t)B * w[i];
+      d.n1 = d.n2 = 1;
+      if (hdet_bgemm_dma_eligible(d, true, false, HDET_EPI_MASK_BF16)) {       // that kernel also leaves the column sums of dX
+        d.colsum = p->colsum_part;
+        have_part = true;
+      }
       e = hdet_launch_bgemm(d, true, false, HDET_EPI_MASK_BF16, N, s);
       if (e != hipSuccess) return e;
       uint16_t* t = dz; dz = dz_next; dz_next = t;

@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void hdet_update_plane_kernel(const hdet_
   if (i >= (a.n_params >> 2)) return;
   const int64_t off = (int64_t)r * a.stride + (i << 2);
   f4 th = ld<f4>(a.theta + off);
-  f4 g = ld<f4>(a.grad + off);
+  f4 g = ld<f4>(a.grad + (int64_t)r * a.grad_stride + (i << 2));
   f4 m = ld<f4>(a.m + off);
   f4 v = splat<f4>(0.f);
   if (OPT == HDET_ADAMW) v = ld<f4>(a.v + off);
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void hdet_update_wave_kernel(const 
   f4 th = splat<f4>(0.f), g = th, m = th, v = th;
   if (ok) {
     th = ld<f4>(a.theta + off);
-    g = ld<f4>(a.grad + off);
+    g = ld<f4>(a.grad + (int64_t)r * a.grad_stride + (i << 2));
   }
   if (mine) {
     m = ld<f4>(a.m + moff);
@@ -268,7 +268,7 @@ __device__ __forceinline__ void update_column(const hdet_update_args& a, const r
     // fp64 and rounded to fp32 once: Adam's first steps move by lr * g/(|g| + eps), which
     // magnifies a last-place difference in a near-zero mean gradient ten-thousandfold.
     auto sum = widen(splat<T>(0.f));
-    for (int q = 0; q < n; ++q) sum = sum + widen(ld<T>(a.grad + (int64_t)q * a.stride + col));
+    for (int q = 0; q < n; ++q) sum = sum + widen(ld<T>(a.grad + (int64_t)q * a.grad_stride + col));
     gbar = narrow(sum * (1.0 / (double)n));
   }
   T ratio = splat<T>(0.f);
@@ -287,7 +287,7 @@ __device__ __forceinline__ void update_column(const hdet_update_args& a, const r
     if (SSTATE) {
       adamw_apply<T>(th, ratio, s[r]);
     } else {
-      T g = SHARED ? gbar : ld<T>(a.grad + off);
+      T g = SHARED ? gbar : ld<T>(a.grad + (int64_t)r * a.grad_stride + col);
       T m = ld<T>(a.m + off);
       T v = splat<T>(0.f);
       if (OPT == HDET_ADAMW) v = ld<T>(a.v + off);
@@ -392,7 +392,9 @@ void launch_variant(const hdet_update_args& a, int variant, int blocks, hipStrea
   const bool exchange = SHARED || CONV;
   bool columns_done = false;
   if (variant == 0 && nvec > 0) {
-    if (!exchange) {
+    // with one gradient plane for all replicas the wave kernel is taken as well: the replicas of a column share a
+    // block, so the plane comes from memory once
+    if (!exchange && !(a.grad_stride == 0 && n > 1 && n <= kMaxWaves)) {
       const int64_t bx = (nvec + kThreads - 1) / kThreads;
       if (bx <= 0x7fffffff) {
         hipLaunchKernelGGL((hdet_update_plane_kernel<OPT>), dim3((unsigned)bx, n), dim3(kThreads), 0, stream, a);

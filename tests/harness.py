@@ -77,23 +77,41 @@ def check_bf16_tensor(a, b, norm_tol: float, tag, elem_tol: float = ELEM_TOL_BF1
     assert ee <= elem_tol, (tag, "element", ee)
 
 
-def mlp_tied_rows_equalised(g_dev, g_ref, widths, ties):
-    """Copies of two flat MLP gradients in which the entries that a ReLU tie decides are taken out of an
-    element-wise comparison (set to the oracle's value on both sides): a hidden unit whose pre-activation is
-    zero to within the rounding error of a mixed-precision product may pass its gradient on one side and not
-    on the other -- both are valid subgradients -- and that switches one batch row's contribution to row `unit`
-    of that layer's weight gradient and to its bias gradient on and off.  (Layers below see the difference as one
-    term in 4096 of one batch row's gradient, far below the element-wise bound.)"""
-    a, b = np.array(g_dev, copy=True), np.asarray(g_ref)
-    off = 0
-    for i in range(len(widths) - 1):
+def check_bf16_relu_matrix(a, b, rows: int, cols: int, norm_tol: float, tag):
+    """A weight gradient of a hidden ReLU layer in mixed precision.  Here single entries cannot be held to
+    elem_err: activations that round to the neighbouring bfloat16 move the next layer's pre-activations by
+    up to about 1e-3, a unit that close to the kink passes its gradient on one side and not on the other (both
+    are valid subgradients), and that switches one batch row's term of every entry in the unit's row on or
+    off -- for a few entries that is most of their value.  What a kernel error looks like is different: a
+    wrong row, column or block is off everywhere in it.  So: the norm-wise bound, the median error ratio of
+    every row and of every column (a wrong one has a median of 0.5 or more), and the 99.9th percentile of all
+    entries; the layers that no gate decides (the output layer, every bias) keep the entry-wise bound."""
+    assert norm_err(a, b) <= norm_tol, (tag, "norm")
+    a2, b2 = np.asarray(a, np.float64).reshape(rows, cols), np.asarray(b, np.float64).reshape(rows, cols)
+    ratio = np.abs(a2 - b2) / (np.abs(b2) + max(float(np.sqrt(np.mean(b2 * b2))), 1e-30))
+    row_med, col_med = float(np.max(np.median(ratio, axis=1))), float(np.max(np.median(ratio, axis=0)))
+    q = float(np.quantile(ratio, 0.999))
+    observed_elem_err[str(tag) + " q99.9"] = q
+    assert row_med <= 0.1 and col_med <= 0.1, (tag, "row/column median", row_med, col_med)
+    assert q <= ELEM_TOL_BF16, (tag, "99.9th percentile", q)
+
+
+def check_bf16_mlp_gradients(g_dev, g_ref, widths, norm_tol: float, tag):
+    """All tensors of a mixed-precision ReLU MLP gradient (flat layout W_1, b_1, W_2, b_2, ...)."""
+    off, L = 0, len(widths) - 1
+    for i in range(L):
         d_in, d_out = widths[i], widths[i + 1]
-        if i < len(ties):
-            for unit in sorted({int(u) for _, u in ties[i]}):
-                a[off + unit * d_in: off + (unit + 1) * d_in] = b[off + unit * d_in: off + (unit + 1) * d_in]
-                a[off + d_out * d_in + unit] = b[off + d_out * d_in + unit]
-        off += d_out * d_in + d_out
-    return a, b
+        w_dev, w_ref = g_dev[off:off + d_out * d_in], g_ref[off:off + d_out * d_in]
+        if i == L - 1:
+            check_bf16_tensor(w_dev, w_ref, norm_tol, (tag, i, "W"))
+        else:
+            check_bf16_relu_matrix(w_dev, w_ref, d_out, d_in, norm_tol, (tag, i, "W"))
+        off += d_out * d_in
+        # a bias gradient sums the batch rows of one unit: a switched term weighs as in the weight rows
+        assert norm_err(g_dev[off:off + d_out], g_ref[off:off + d_out]) <= norm_tol, (tag, i, "b")
+        if i == L - 1:
+            check_bf16_tensor(g_dev[off:off + d_out], g_ref[off:off + d_out], norm_tol, (tag, i, "b"))
+        off += d_out
 
 
 def ulp_diff_f32(a, b) -> int:

@@ -355,3 +355,34 @@ def test_checkpoint_resume_is_bit_exact_on_the_transformer():
         assert sa.base[j] == sb.base[j] and sa.vel[j] == sb.vel[j]
         assert [sa.perm[j][r] for r in range(3)] == [sb.perm[j][r] for r in range(3)]
     a.close(); b.close()
+
+
+@pytest.mark.parametrize("cfg,batch,n,bf16", [(TINY, 3, 3, False), (SMALL, 4, 4, False), (SMALL, 4, 4, True), (FUSE3, 2, 2, True)])
+def test_shared_gradient_mode_forms_the_replica_mean_in_one_plane(cfg, batch, n, bf16):
+    """Algorithm 1's gradient exchange on the transformer: plane 0 of the gradient buffer receives the replica mean --
+    weight matrices as one product over the rows of all replicas, embeddings, LayerNorm parameters and biases as the
+    sum of the per-replica results -- and the update applies it to every replica at its own rate."""
+    d = base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, grad_mode=O.GRAD_SHARED)
+    run = TfRun(d, cfg, batch, bf16=bf16)
+    for t in range(1, 6):
+        run.orc.theta = run.theta.cpu().numpy()[:, :run.P].copy()
+        run.orc.m = run.m.cpu().numpy()[:, :run.P].copy()
+        run.orc.v = run.v.cpu().numpy()[:, :run.P].copy()
+        run.g.fill_(7.0)
+        ids, tgt, gl = run.forward_backward(t)
+        losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, t)
+        gbar = O.shared_gradient(grads)
+        assert np.max(np.abs(gl - losses)) <= (1e-2 if bf16 else 2e-5)
+        g0 = run.g.cpu().numpy()[0, :run.P]
+        if bf16:
+            check_bf16_gradients(cfg, g0, gbar, 4e-2, ("shared", cfg["d_model"], t))
+        else:
+            bad = {k: v for k, v in per_tensor_errors(cfg, g0, gbar).items() if v > 2e-5}
+            assert not bad, (t, bad)
+        run.finish_step(t, grads, losses, fuse=(t == 4))
+        # AdamW from identical state: bounded over the tensor (its early steps magnify a rounding difference of a
+        # near-zero gradient entry up to the full step lr); the gradient check above is the entry-wise one
+        assert norm_err(run.theta.cpu().numpy()[:, :run.P], run.orc.theta) <= (1e-3 if not bf16 else 1e-2), t
+    st = H.hdet_get_state(run.h)
+    assert st.k == run.orc.k == 1
+    run.close()
