@@ -90,11 +90,13 @@ def oracle_baseline_all_cores(n, t_sync, p_sample, steps):
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def mlp_workload(args):
+def mlp_workload(args, shared=False):
     """N = 8 replicas of the 4-layer MLP 1024-4096-4096-4096-1000, batch 256 per replica, bf16
     GEMMs with fp32 master weights, AdamW, one-cycle 1000 steps peak 3e-4, alpha 0.1, T = 16,
     auto-LR on.  A step = forward/backward + fan-out update (+ converge + controller on sync
-    steps).  Returns a dict of measurements."""
+    steps).  shared: the paper's own mode -- every replica applies the replica mean of the gradients
+    (formed as one gradient plane by the model path) and AdamW's moments are kept once.
+    Returns a dict of measurements."""
     import numpy as np
     import torch
     import hdet_inputs as I
@@ -108,6 +110,8 @@ def mlp_workload(args):
     theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
     theta[:, :P] = torch.from_numpy(I.mlp_init(1, widths, I.SEED_INIT)).to(dev)
     m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.zeros_like(theta)
+    if shared:
+        m, v = m[:1], v[:1]
     shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
     x = torch.empty((n, B, widths[0]), dtype=torch.float32, device=dev)
     I.device_normal_(x, I.SEED_DATA, 1.0)
@@ -116,7 +120,8 @@ def mlp_workload(args):
     stream = torch.cuda.current_stream()
     cfg = H.make_config(n_replicas=n, sync_interval=T, total_steps=total, warm_steps=int(0.3 * total),
                         lr_max=3e-4, alpha=0.1, autolr_enabled=1, optimizer=H.HDET_ADAMW, weight_decay=0.01,
-                        grad_mode=H.HDET_GRAD_PER_REPLICA, precision=H.HDET_BF16_GEMM_FP32_MASTER,
+                        grad_mode=H.HDET_GRAD_SHARED if shared else H.HDET_GRAD_PER_REPLICA, shared_opt_state=int(shared),
+                        precision=H.HDET_BF16_GEMM_FP32_MASTER,
                         model_kind=H.HDET_MLP, widths=widths, batch=B, seed=I.SEED_PERM,
                         stream=stream.cuda_stream)
     _, _, ws_bytes = H.hdet_workspace_bytes(cfg, stride)
@@ -155,10 +160,14 @@ def mlp_workload(args):
     dgrad_flop = sum(2.0 * B * widths[i] * widths[i + 1] for i in range(1, len(widths) - 1))
     gemm_flop = n * (2 * fwd_flop + dgrad_flop)          # forward + wgrad + dgrad (none for layer 1)
     tflops = gemm_flop / (fb_ms * 1e-3) / 1e12
-    return {"workload": "N=8 x MLP 1024-4096-4096-4096-1000, batch 256/replica, bf16 GEMM + fp32 master, AdamW, T=16",
+    # update bytes per parameter: theta read + written and the bf16 copy written per replica; then either g, m, v per
+    # replica (30 N), or one gradient plane and one set of moments (10 N + 20)
+    upd_bytes = (10.0 * n + 20.0) * P if shared else 30.0 * n * P
+    return {"workload": "N=8 x MLP 1024-4096-4096-4096-1000, batch 256/replica, bf16 GEMM + fp32 master, AdamW, T=16"
+                        + (", shared gradients (one gradient plane, one set of moments)" if shared else ""),
             "replica_steps_per_s": n * args.steps / dt, "ms_per_step": dt / args.steps * 1e3,
-            "forward_backward_ms": fb_ms, "update_ms": up_ms,
-            "update_GBps": 30.0 * n * P / (up_ms * 1e-3) / 1e9,
+            "forward_backward_ms": fb_ms, "update_ms": up_ms, "update_algorithmic_bytes": upd_bytes,
+            "update_GBps": upd_bytes / (up_ms * 1e-3) / 1e9,
             "gemm_flop_per_step": gemm_flop, "forward_backward_TFLOPs": tflops,
             "mfma_frac_of_bf16_peak": tflops / MFMA_BF16_PEAK_TFLOPS,
             "loss_first_replica": float(st.l_step[0])}
@@ -188,13 +197,17 @@ def transformer_workload(args):
     theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
     theta[:, :P] = torch.from_numpy(I.transformer_init(1, cfg, I.SEED_INIT)).to(dev)
     m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.zeros_like(theta)
+    shared = getattr(args, "model_grad_mode", "per_replica") == "shared"
+    if shared:
+        m, v = m[:1], v[:1]
     shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
     ids, tgt = I.zipf_tokens(n, B, cfg["seq_len"], cfg["vocab"], I.SEED_DATA, 0)
     ids, tgt = torch.from_numpy(ids).to(dev), torch.from_numpy(tgt).to(dev)
     stream = torch.cuda.current_stream()
     lc = H.make_config(n_replicas=n, sync_interval=T, total_steps=total, warm_steps=int(0.3 * total),
                        lr_max=lr_max, alpha=alpha, autolr_enabled=1, optimizer=H.HDET_ADAMW, weight_decay=0.01,
-                       grad_mode=H.HDET_GRAD_PER_REPLICA, precision=H.HDET_BF16_GEMM_FP32_MASTER,
+                       grad_mode=H.HDET_GRAD_SHARED if shared else H.HDET_GRAD_PER_REPLICA, shared_opt_state=int(shared),
+                       precision=H.HDET_BF16_GEMM_FP32_MASTER,
                        model_kind=H.HDET_TRANSFORMER, batch=B, seed=I.SEED_PERM, stream=stream.cuda_stream,
                        extra=extra, **cfg)
     _, _, ws_bytes = H.hdet_workspace_bytes(lc, stride)
@@ -235,10 +248,11 @@ def transformer_workload(args):
     gemm_flop = n * 3 * (lin + attn)                          # forward + dgrad + wgrad
     tflops = gemm_flop / (fb_ms * 1e-3) / 1e12
     return {"workload": f"N=8 x decoder-only transformer {L}L d{d} h{nh} ffn{ff} seq{S} vocab{V}, {B} seq/replica, "
-                        f"bf16 GEMM + fp32 master, AdamW, T={T}, {1 + len(extra)} channel(s)",
+                        f"bf16 GEMM + fp32 master, AdamW, T={T}, {1 + len(extra)} channel(s)"
+                        + (", shared gradients (one gradient plane, one set of moments)" if shared else ""),
             "n_params": P, "replica_steps_per_s": n * args.steps / dt, "tokens_per_s": n * M * args.steps / dt,
             "ms_per_step": dt / args.steps * 1e3, "forward_backward_ms": fb_ms, "update_ms": up_ms,
-            "update_GBps": 30.0 * n * P / (up_ms * 1e-3) / 1e9, "gemm_flop_per_step": gemm_flop,
+            "update_GBps": ((10.0 * n + 20.0) if shared else 30.0 * n) * P / (up_ms * 1e-3) / 1e9, "gemm_flop_per_step": gemm_flop,
             "forward_backward_TFLOPs": tflops, "mfma_frac_of_bf16_peak": tflops / MFMA_BF16_PEAK_TFLOPS,
             "loss_first_replica": float(st.l_step[0])}
 
@@ -398,6 +412,8 @@ def main():
                     help="flat: the headline flat-buffer case only; mlp: only the bf16 MLP case (printed as its own "
                          "JSON line); transformer: only the bf16 transformer case; both: the headline line with the "
                          "MLP and transformer figures attached as `mlp_bf16` and `transformer_bf16`")
+    ap.add_argument("--model-grad-mode", choices=["per_replica", "shared"], default="per_replica",
+                    help="--workload mlp / transformer: shared = the replica mean of the gradients as one plane, one set of moments")
     ap.add_argument("--tf-config", choices=["6L", "12L"], default="6L",
                     help="transformer workload: 6 layers d512 seq256 (default) or 12 layers d1024 seq512 with 3 channels")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -412,13 +428,13 @@ def main():
     cpu_baseline = None
     if args.workload in ("both", "flat") and not args.no_cpu_baseline:
         n, P, T = args.replicas, int(args.params), args.sync_interval
-        p_sample, o_steps = 4_000_000, T + 1
+        p_sample, o_steps = 12_000_000, T + 1
         odt = oracle_baseline(n, T, p_sample, o_steps)
         cpu_baseline = {"value": n * o_steps / odt * (p_sample / P), "unit": "replica-steps/s",
                         "cores": 1, "kind": "oracle",
                         "sample": f"oracle (numpy, fp64 arithmetic, element-wise: one thread) on N={n} x P={p_sample} for "
                                   f"{o_steps} steps incl. one converge+controller, {odt:.1f} s; scaled linearly in P to P={P:.3g}"}
-        p_all = 16_000_000
+        p_all = 64_000_000
         adt, procs = oracle_baseline_all_cores(n, T, p_all, o_steps)
         cpu_baseline["all_cores"] = {"value": n * o_steps / adt * (p_all / P), "unit": "replica-steps/s", "cores": procs,
                                      "sample": f"the same oracle in {procs} processes, each on a slice of P={p_all} "
@@ -434,7 +450,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.workload == "mlp":
-        print(json.dumps(mlp_workload(args)))
+        print(json.dumps(mlp_workload(args, shared=args.model_grad_mode == "shared")))
         return
     if args.workload == "transformer":
         print(json.dumps(transformer_workload(args)))
@@ -551,9 +567,15 @@ def main():
     if args.workload == "both":
         out["mlp_bf16"] = mlp_workload(args)
         torch.cuda.empty_cache()
+        out["mlp_bf16_shared_gradient"] = mlp_workload(args, shared=True)
+        torch.cuda.empty_cache()
         targs = argparse.Namespace(**vars(args))
         targs.steps, targs.warmup = min(args.steps, 16), min(args.warmup, 4)
         out["transformer_bf16"] = transformer_workload(targs)
+        torch.cuda.empty_cache()
+        targs.model_grad_mode = "shared"
+        out["transformer_bf16_shared_gradient"] = transformer_workload(targs)
+        targs.model_grad_mode = "per_replica"
         torch.cuda.empty_cache()
         targs.tf_config, targs.steps, targs.warmup = "12L", min(args.steps, 8), min(args.warmup, 2)
         out["transformer_12L_bf16"] = transformer_workload(targs)

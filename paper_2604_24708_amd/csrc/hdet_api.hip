@@ -6,6 +6,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
 #include <cmath>
 
 #include <new>
@@ -335,9 +336,8 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   a.ctrl_out = h->ctrl_dev;
   a.n_params = param_count(c);
   a.stride = h->buf.plane_stride;
-  // a model handle in shared-gradient mode has formed the replica mean itself, in plane 0 of its gradient buffer
-  const bool one_plane = !grads_dev && c.model_kind != HDET_FLAT && c.grad_mode == HDET_GRAD_SHARED;
-  a.grad_stride = one_plane ? 0 : a.stride;
+  a.grad_stride = a.stride;
+  a.grad_scale = 1.f;
   a.n_replicas = c.n_replicas;
   a.wd_channel = h->wd_channel;
   a.first_step = t == 1;
@@ -356,19 +356,39 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   a.momentum = (float)c.momentum;
 
   const bool fuse = (flags & HDET_FUSE_CONVERGE) && (t % c.sync_interval == 0);
-  // one launch per parameter group: the group's slice of every plane with the group's rate channel
+  // A model handle in shared-gradient mode leaves some slices of the plane as one sum over the replicas (plane 0 of its
+  // gradient buffer) and the rest as one gradient per replica; either way the kernel applies the replica mean.
+  std::vector<std::pair<int64_t, int64_t>> summed;
+  const bool shared = c.grad_mode == HDET_GRAD_SHARED;
+  if (!grads_dev && shared && c.model_kind == HDET_MLP) summed.push_back({0, a.n_params});
+  if (!grads_dev && shared && c.model_kind == HDET_TRANSFORMER) hdet_tf_summed_slices(h->tf, &summed);
+  // one launch per parameter group and kind of slice: the slice of every plane with the group's rate channel
   int64_t begin = 0;
+  size_t si = 0;
   for (int grp = 0; grp < h->n_lr; ++grp) {
-    const int64_t end = h->n_lr > 1 ? c.group_end[grp] : a.n_params;
-    hdet_update_args ga = a;
-    ga.theta += begin; ga.grad += begin; ga.m += begin;
-    if (ga.v) ga.v += begin;
-    if (ga.shadow) ga.shadow += begin;
-    ga.n_params = end - begin;
-    ga.lr_channel = grp;
-    hipError_t e = hdet_launch_update(ga, c.optimizer, c.grad_mode == HDET_GRAD_SHARED, fuse, h->tune_variant, default_blocks(h), h->stream);
-    if (e != hipSuccess) return hip_fail(h, e, "update kernel");
-    begin = end;
+    const int64_t gend = h->n_lr > 1 ? c.group_end[grp] : a.n_params;
+    while (begin < gend) {
+      while (si < summed.size() && summed[si].first + summed[si].second <= begin) ++si;
+      const bool in_sum = si < summed.size() && summed[si].first <= begin;
+      int64_t end = gend;
+      if (in_sum) end = std::min(end, summed[si].first + summed[si].second);
+      else if (si < summed.size()) end = std::min(end, summed[si].first);
+      hdet_update_args ga = a;
+      ga.theta += begin; ga.grad += begin; ga.m += begin;
+      if (ga.v) ga.v += begin;
+      if (ga.shadow) ga.shadow += begin;
+      ga.n_params = end - begin;
+      ga.lr_channel = grp;
+      if (in_sum) {
+        ga.grad_stride = 0;
+        ga.grad_scale = (float)(1.0 / (double)c.n_replicas);
+      }
+      // identical gradients need no mean over the replicas, except that one set of moments is built on that kernel
+      const bool mean = shared && (!in_sum || c.shared_opt_state);
+      hipError_t e = hdet_launch_update(ga, c.optimizer, mean, fuse, h->tune_variant, default_blocks(h), h->stream);
+      if (e != hipSuccess) return hip_fail(h, e, "update kernel");
+      begin = end;
+    }
   }
   h->t = t;
   if (fuse) h->converged_at_t = t;

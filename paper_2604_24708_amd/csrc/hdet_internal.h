@@ -5,6 +5,8 @@
 #include <stdint.h>
 
 #include <string>
+#include <utility>
+#include <vector>
 
 #include "hdet.h"
 
@@ -55,7 +57,9 @@ struct hdet_update_args {
   int64_t n_params;        // P
   int64_t stride;          // plane stride in elements
   int64_t grad_stride;     // plane stride of `grad`: `stride`, or 0 when every replica applies the one plane at `grad`
-                           // (the model paths in shared-gradient mode form the replica mean themselves)
+                           // times grad_scale (a model path in shared-gradient mode has summed the replicas' gradients
+                           // there: the replica mean is that sum times 1 / N)
+  float grad_scale;
   int32_t n_replicas;
   int32_t lr_channel;      // learning-rate channel of the parameter group being updated
   int32_t wd_channel;      // channel index of a weight-decay channel or -1
@@ -203,6 +207,9 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
                              int temp_channel, std::string* err);
 void hdet_tf_destroy(hdet_tf_plan* p);
 void hdet_tf_set_fused_attention(hdet_tf_plan* p, bool on);   // on by default where the fused kernels apply
+// Shared-gradient mode: the slices (offset, length) of a parameter plane whose gradient the pass leaves as ONE plane, the
+// sum over the replicas in plane 0 of the gradient buffer; everywhere else it leaves one gradient plane per replica.
+void hdet_tf_summed_slices(const hdet_tf_plan* p, std::vector<std::pair<int64_t, int64_t>>* out);
 // `step`: the update this gradient is for (keys the dropout masks)
 hipError_t hdet_tf_forward_backward(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl,
                                     uint32_t step, hipStream_t stream);

@@ -358,9 +358,9 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
   const float* theta = p->buf.params_dev;
   float* grads = p->buf.grads_dev;
   p->act[0] = const_cast<void*>(x);
-  // Shared-gradient mode (Algorithm 1, "AllReduce gradients"): every replica applies the replica mean, so only the
-  // mean is formed -- the N batches are rows of one matrix, the weight gradient is one product over K = N B rows and
-  // the loss gradient carries the 1 / (N B); the result goes to plane 0 of the gradient buffer.
+  // Shared-gradient mode (Algorithm 1, "AllReduce gradients"): every replica applies the replica mean, so only the sum of
+  // the replicas' gradients is formed -- the N batches are rows of one matrix, a weight gradient is one product over
+  // K = N B rows -- in plane 0 of the gradient buffer; the update kernel multiplies by 1 / N.
   const bool shared = c.grad_mode == HDET_GRAD_SHARED;
 
   // forward: Y = act(X W^T + b)
@@ -375,7 +375,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
   }
   // loss and dlogits
   float* dz = (float*)p->dz_a; float* dz_next = (float*)p->dz_b;
-  if (hipError_t e = hdet_launch_xent(false, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0, shared ? N * B : B)) return e;
+  if (hipError_t e = hdet_launch_xent(false, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0, B)) return e;
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   // backward
   for (int i = L - 1; i >= 0; --i) {
@@ -432,7 +432,7 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
   uint16_t* dz = (uint16_t*)p->dz_a; uint16_t* dz_next = (uint16_t*)p->dz_b;
   const int nchunks = (B + 127) / 128;
   bool have_part = false;
-  if (hipError_t e = hdet_launch_xent(true, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0, shared ? N * B : B)) return e;
+  if (hipError_t e = hdet_launch_xent(true, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0, B)) return e;
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   for (int i = L - 1; i >= 0; --i) {
     hdet_bgemm_args g = {};                          // dW = dZ^T X

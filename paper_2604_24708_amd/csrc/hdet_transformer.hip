@@ -786,17 +786,6 @@ __global__ __launch_bounds__(256) void dropout_kernel(const T* x, const T* branc
   }
 }
 
-// Shared-gradient mode: plane 0 of the slices listed in `ranges` (offset, length pairs) receives the sum over the
-// replicas' planes, r ascending, in fp64 and rounded once (the per-replica values already carry the 1 / N).
-__global__ __launch_bounds__(256) void plane_sum_kernel(float* grads, int64_t ps, int n_replicas, const int64_t* ranges) {
-  const int64_t off = ranges[2 * blockIdx.y], len = ranges[2 * blockIdx.y + 1];
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < len; i += (int64_t)gridDim.x * 256) {
-    double s = 0.0;
-    for (int r = 0; r < n_replicas; ++r) s += (double)grads[(int64_t)r * ps + off + i];
-    grads[off + i] = (float)s;
-  }
-}
-
 int grid_for(int64_t n) { int64_t b = (n + 255) / 256; return (int)(b > 8192 ? 8192 : (b < 1 ? 1 : b)); }
 
 }  // namespace
@@ -843,14 +832,17 @@ struct hdet_tf_plan {
   std::vector<colsum_job> jobs;   // the two-stage reductions of a backward pass, by position in the parameter plane
   colsum_job* jobs_dev;
   int final_blocks;          // x extent of the stage-2 launch
-  // shared-gradient mode: the slices of a parameter plane that are not weight matrices (embeddings, LayerNorm
-  // parameters, biases), as (offset, length) pairs; their per-replica gradients are added up into plane 0
-  std::vector<int64_t> vec_ranges;
-  int64_t* vec_ranges_dev;
-  int64_t vec_range_max;
+  // shared-gradient mode: the weight matrices whose gradient is formed as one product over all replicas' rows
+  // (offset, length), ascending; every other gradient is left per replica
+  std::vector<std::pair<int64_t, int64_t>> summed;
 };
 
 static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Shared-gradient mode: a weight gradient dW [rows][cols] is formed as ONE product over the K = N M rows of all
+// replicas when that product alone has enough 256 x 256 tiles to occupy the chip (the output head); a smaller matrix
+// keeps one product per replica, K = M, whose N results are added up with the vector parameters' gradients.
+static bool tf_wgrad_one_product(int64_t rows, int64_t cols) { return ((rows + 255) / 256) * ((cols + 255) / 256) >= 128; }
 
 // Walks the workspace layout; with base == nullptr only the size is computed.
 static size_t tf_carve(hdet_tf_plan* p, char* base) {
@@ -891,7 +883,6 @@ static size_t tf_carve(hdet_tf_plan* p, char* base) {
   const size_t head_chunks = xr ? (M + xr - 1) / xr : p->nrc;
   p->part = (float*)take(N * (p->nrc * ((size_t)L * (3 * d + ff)) + head_chunks * V + ln_chunks * (2 * d * (2 * (size_t)L + 1) + 2 * d * (size_t)L)) * 4);
   p->jobs_dev = (colsum_job*)take((6 * (size_t)L + 2) * sizeof(colsum_job));
-  p->vec_ranges_dev = (int64_t*)take((4 * (size_t)L + 4) * 2 * sizeof(int64_t));
   return off;
 }
 
@@ -991,27 +982,15 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
     add_job((int)d, 1, b.ln1_g, b.ln1_b);
   }
   p->final_blocks = first_block;
-  {   // slices between the weight matrices, adjacent ones merged
-    std::vector<std::pair<int64_t, int64_t>> mats;          // (offset, length) of every weight matrix, ascending
+  if (cfg.grad_mode == HDET_GRAD_SHARED) {
     for (int l = 0; l < p->L; ++l) {
       const tf_block_off& o = p->blk[l];
-      mats.push_back({o.w_qkv, 3 * d * d}); mats.push_back({o.w_o, d * d});
-      mats.push_back({o.w_1, ff * d}); mats.push_back({o.w_2, d * ff});
+      if (tf_wgrad_one_product(3 * d, d)) p->summed.push_back({o.w_qkv, 3 * d * d});
+      if (tf_wgrad_one_product(d, d)) p->summed.push_back({o.w_o, d * d});
+      if (tf_wgrad_one_product(ff, d)) p->summed.push_back({o.w_1, ff * d});
+      if (tf_wgrad_one_product(d, ff)) p->summed.push_back({o.w_2, d * ff});
     }
-    mats.push_back({p->w_head, V * d});
-    int64_t at = 0;
-    p->vec_range_max = 0;
-    auto add_range = [&](int64_t from, int64_t to) {
-      if (to <= from) return;
-      p->vec_ranges.push_back(from); p->vec_ranges.push_back(to - from);
-      if (to - from > p->vec_range_max) p->vec_range_max = to - from;
-    };
-    for (const auto& mt : mats) { add_range(at, mt.first); at = mt.first + mt.second; }
-    add_range(at, off);
-    if (hipMemcpyAsync(p->vec_ranges_dev, p->vec_ranges.data(), p->vec_ranges.size() * sizeof(int64_t), hipMemcpyHostToDevice,
-                       (hipStream_t)cfg.stream) != hipSuccess) {
-      *err = "could not upload the table of vector-parameter slices"; delete p; return nullptr;
-    }
+    if (tf_wgrad_one_product(V, d)) p->summed.push_back({p->w_head, V * d});
   }
   // on the handle's stream, like all other work; the host copy lives as long as the plan
   if (!p->jobs.empty() &&
@@ -1023,6 +1002,8 @@ hdet_tf_plan* hdet_tf_create(const hdet_config& cfg, const hdet_buffers& buf, in
 }
 
 void hdet_tf_destroy(hdet_tf_plan* p) { delete p; }
+
+void hdet_tf_summed_slices(const hdet_tf_plan* p, std::vector<std::pair<int64_t, int64_t>>* out) { *out = p->summed; }
 
 void hdet_tf_set_fused_attention(hdet_tf_plan* p, bool on) {
   p->fused_attn = on && p->bf16 && hdet_attn_fusable(p->S, p->d, p->nh, p->B);
@@ -1223,9 +1204,9 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   const float scale = 1.f / sqrtf((float)dh);
   const int64_t heads_rows = (int64_t)N * B * nh * S;
   const int64_t nd = (int64_t)M * d, nff = (int64_t)M * ff;
-  // Shared-gradient mode (Algorithm 1, "AllReduce gradients"): only the replica mean is formed, in plane 0 of the
-  // gradient buffer.  The loss gradient carries 1 / (N M); a weight gradient is one product over the K = N M rows of
-  // all replicas; the other parameter gradients are formed per replica as usual and added up at the end of the pass.
+  // Shared-gradient mode (Algorithm 1, "AllReduce gradients"): a large weight gradient (tf_wgrad_one_product) is formed as
+  // one product over the K = N M rows of all replicas -- the sum of the replicas' gradients, in plane 0 of the gradient
+  // buffer --, everything else per replica as usual; the update kernel turns both into the replica mean.
   const bool shared = p->cfg.grad_mode == HDET_GRAD_SHARED;
   drop_args da = {ctrl, p->drop_channel, step, (uint32_t)(p->cfg.seed & 0xffffffffu), (uint32_t)(p->cfg.seed >> 32), 0};
   const bool drop = p->drop_channel >= 0;
@@ -1310,8 +1291,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   if (xr)
     for (const colsum_job& j : p->jobs)
       if (j.out_off == p->b_head && j.mode == 0 && j.cols == V && j.nchunks == (M + xr - 1) / xr) { head_part = p->part + j.part_off; break; }
-  TF_CHECK(hdet_launch_xent(sizeof(T) == 2, p->logits, targets, M, V, p->dlogits, p->row_loss, N, ctrl, p->ls_channel, s, head_part, xr,
-                            shared ? N * M : M));
+  TF_CHECK(hdet_launch_xent(sizeof(T) == 2, p->logits, targets, M, V, p->dlogits, p->row_loss, N, ctrl, p->ls_channel, s, head_part, xr));
   TF_CHECK(hdet_launch_loss_reduce(p->row_loss, M, ctrl, N, s));
 
   // ---- backward -----------------------------------------------------------------------
@@ -1322,8 +1302,9 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
     return launch_colsum<T, 1>(p, dy, d, x, mean, rstd, g_off, b_off, s);
   };
   auto wgrad = [&](const void* dy, int wy, const void* x, int wx, int64_t w_off) {      // dW[wy][wx] = dy^T x
-    return gemm<T>(p, TN, act(dy, wy), act(x, wx), grads + w_off, wx, plane, false, wy, wx, shared ? N * M : M, 1, 1, nullptr, 0, s,
-                   nullptr, shared);
+    const bool one = shared && tf_wgrad_one_product(wy, wx);
+    return gemm<T>(p, TN, act(dy, wy), act(x, wx), grads + w_off, wx, plane, false, wy, wx, one ? N * M : M, 1, 1, nullptr, 0, s,
+                   nullptr, one);
   };
 
   TF_CHECK(wgrad(p->dlogits, V, p->hf, d, p->w_head));
@@ -1424,9 +1405,6 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   }
   hipLaunchKernelGGL(pos_bwd_kernel<T>, dim3(grid_for((int64_t)S * d), N), dim3(256), 0, s, grads, ps, p->pos, B, S, d, (const T*)p->dxa);
   TF_CHECK(launch_colsum_final(p, s));
-  if (shared && N > 1)
-    hipLaunchKernelGGL(plane_sum_kernel, dim3(grid_for(p->vec_range_max), (unsigned)(p->vec_ranges.size() / 2)), dim3(256), 0, s, grads, ps, N,
-                       p->vec_ranges_dev);
   return hipGetLastError();
 }
 

@@ -139,6 +139,7 @@ __global__ __launch_bounds__(kThreads) void hdet_update_plane_kernel(const hdet_
   const int64_t off = (int64_t)r * a.stride + (i << 2);
   f4 th = ld<f4>(a.theta + off);
   f4 g = ld<f4>(a.grad + (int64_t)r * a.grad_stride + (i << 2));
+  if (a.grad_stride == 0) g = g * a.grad_scale;
   f4 m = ld<f4>(a.m + off);
   f4 v = splat<f4>(0.f);
   if (OPT == HDET_ADAMW) v = ld<f4>(a.v + off);
@@ -204,6 +205,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void hdet_update_wave_kernel(const 
   if (ok) {
     th = ld<f4>(a.theta + off);
     g = ld<f4>(a.grad + (int64_t)r * a.grad_stride + (i << 2));
+    if (a.grad_stride == 0) g = g * a.grad_scale;
   }
   if (mine) {
     m = ld<f4>(a.m + moff);
@@ -268,8 +270,12 @@ __device__ __forceinline__ void update_column(const hdet_update_args& a, const r
     // fp64 and rounded to fp32 once: Adam's first steps move by lr * g/(|g| + eps), which
     // magnifies a last-place difference in a near-zero mean gradient ten-thousandfold.
     auto sum = widen(splat<T>(0.f));
-    for (int q = 0; q < n; ++q) sum = sum + widen(ld<T>(a.grad + (int64_t)q * a.grad_stride + col));
-    gbar = narrow(sum * (1.0 / (double)n));
+    if (a.grad_stride == 0) {
+      gbar = ld<T>(a.grad + col) * a.grad_scale;
+    } else {
+      for (int q = 0; q < n; ++q) sum = sum + widen(ld<T>(a.grad + (int64_t)q * a.grad_stride + col));
+      gbar = narrow(sum * (1.0 / (double)n));
+    }
   }
   T ratio = splat<T>(0.f);
   if (SSTATE) {                        // one set of moments for all replicas
@@ -288,6 +294,7 @@ __device__ __forceinline__ void update_column(const hdet_update_args& a, const r
       adamw_apply<T>(th, ratio, s[r]);
     } else {
       T g = SHARED ? gbar : ld<T>(a.grad + (int64_t)r * a.grad_stride + col);
+      if (!SHARED && a.grad_stride == 0) g = g * a.grad_scale;
       T m = ld<T>(a.m + off);
       T v = splat<T>(0.f);
       if (OPT == HDET_ADAMW) v = ld<T>(a.v + off);

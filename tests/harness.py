@@ -57,7 +57,10 @@ def elem_err(a, b) -> float:
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
     if a.size == 0:
         return 0.0
-    rms = float(np.sqrt(np.mean(b * b)))
+    # the tensor's scale: rms over the entries that are not exactly zero (an embedding gradient has rows of zeros for
+    # the tokens that do not occur; they must not shrink the scale of the rows that do)
+    nz = int(np.count_nonzero(b))
+    rms = float(np.sqrt(np.sum(b * b) / nz)) if nz else 0.0
     return float(np.max(np.abs(a - b) / (np.abs(b) + max(rms, 1e-30))))
 
 

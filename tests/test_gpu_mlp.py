@@ -330,9 +330,10 @@ def test_label_smoothing_channel(widths, batch):
 @pytest.mark.parametrize("widths,batch,n,opt", [([64, 128, 10], 32, 4, O.SGDM), ([70, 200, 33], 50, 3, O.ADAMW), ([256, 384, 136], 160, 8, O.ADAMW)])
 def test_shared_gradient_mode_forms_the_replica_mean_in_one_plane(widths, batch, n, opt):
     """The paper's own mode (Algorithm 1: gradients are averaged over the ranks, every rank applies the mean at its own
-    rate): the model path writes only the replica mean, to plane 0 of the gradient buffer -- one weight-gradient product
-    over the rows of all replicas -- and the update reads that one plane.  Against the oracle's mean of its per-replica
-    gradients, entry by entry, and over a trajectory with converge and controller (also with one set of AdamW moments)."""
+    rate): the model path writes only the sum of the replicas' gradients, to plane 0 of the gradient buffer -- one
+    weight-gradient product over the rows of all replicas -- and the update applies that plane times 1 / N.  Against the
+    oracle's mean of its per-replica gradients, entry by entry, and over a trajectory with converge and controller (also
+    with one set of AdamW moments)."""
     for shared_state in ([False, True] if opt == O.ADAMW else [False]):
         d = cfg0(n_replicas=n, optimizer=opt, grad_mode=O.GRAD_SHARED, total_steps=12, warm_steps=4, lr_max=0.02 if opt == O.SGDM else 2e-3,
                  shared_opt_state=shared_state)
@@ -352,7 +353,7 @@ def test_shared_gradient_mode_forms_the_replica_mean_in_one_plane(widths, batch,
             gbar = O.shared_gradient(np.stack([o[1] for o in per_replica]))
             assert np.max(np.abs(np.array([out[r] for r in range(n)]) - losses)) <= 1e-5
             if min(o[2] for o in per_replica) >= run.relu_tau:
-                assert rel_err(run.g.cpu().numpy()[0, :run.P], gbar) <= TOL_GRAD, t
+                assert rel_err(run.g.cpu().numpy()[0, :run.P] / np.float32(n), gbar) <= TOL_GRAD, t
             assert torch.all(run.g[1:] == 7.0)                       # the other planes are not written
             # each step from the device's own state (the trajectories differ by up to the parameter tolerance)
             run.orc.theta = th_dev.copy()
@@ -384,7 +385,7 @@ def test_shared_gradient_mode_bf16():
     per_replica = [M.mlp_loss_and_grad(run.orc.theta[r], x[r], y[r], widths, bf16=True) for r in range(n)]
     gbar = O.shared_gradient(np.stack([o[1] for o in per_replica]))
     assert max(abs(out[r] - per_replica[r][0]) for r in range(n)) <= 2e-3
-    g0 = run.g.cpu().numpy()[0, :run.P]
+    g0 = run.g.cpu().numpy()[0, :run.P] / np.float32(n)
     off = 0
     for i in range(len(widths) - 1):
         for size in (widths[i + 1] * widths[i], widths[i + 1]):

@@ -357,11 +357,33 @@ def test_checkpoint_resume_is_bit_exact_on_the_transformer():
     a.close(); b.close()
 
 
-@pytest.mark.parametrize("cfg,batch,n,bf16", [(TINY, 3, 3, False), (SMALL, 4, 4, False), (SMALL, 4, 4, True), (FUSE3, 2, 2, True)])
-def test_shared_gradient_mode_forms_the_replica_mean_in_one_plane(cfg, batch, n, bf16):
-    """Algorithm 1's gradient exchange on the transformer: plane 0 of the gradient buffer receives the replica mean --
-    weight matrices as one product over the rows of all replicas, embeddings, LayerNorm parameters and biases as the
-    sum of the per-replica results -- and the update applies it to every replica at its own rate."""
+# a vocabulary wide enough that the head's weight gradient (128 tiles of 256 x 256) is formed as one product over the rows of all replicas
+BIGV = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=64, seq_len=32, vocab=32768)
+
+
+def device_mean_gradient(cfg, g, n):
+    """What the update applies in shared-gradient mode, rebuilt from the gradient buffer: a weight matrix of at least
+    128 tiles of 256 x 256 is left as the sum over the replicas in plane 0 (the other planes untouched), every other
+    tensor as one gradient per replica."""
+    out, off, summed = np.empty(g.shape[1], np.float32), 0, []
+    for name, shape in I.transformer_shapes(cfg):
+        k = int(np.prod(shape))
+        if len(shape) == 2 and -(-shape[0] // 256) * -(-shape[1] // 256) >= 128 and "emb" not in name:
+            assert np.all(g[1:, off:off + k] == 7.0), name
+            out[off:off + k] = (g[0, off:off + k].astype(np.float64) / n).astype(np.float32)
+            summed.append(name)
+        else:
+            out[off:off + k] = O.shared_gradient(g[:, off:off + k])
+        off += k
+    return out, summed
+
+
+@pytest.mark.parametrize("cfg,batch,n,bf16", [(TINY, 3, 3, False), (SMALL, 4, 4, False), (SMALL, 4, 4, True), (FUSE3, 2, 2, True),
+                                              (BIGV, 2, 3, False), (BIGV, 2, 3, True)])
+def test_shared_gradient_mode_applies_the_replica_mean(cfg, batch, n, bf16):
+    """Algorithm 1's gradient exchange on the transformer: a weight matrix large enough to fill the chip is formed as one
+    product over the rows of all replicas (their sum, in plane 0 of the gradient buffer), every other gradient per
+    replica, and the update applies the replica mean of either to every replica at its own rate."""
     d = base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, grad_mode=O.GRAD_SHARED)
     run = TfRun(d, cfg, batch, bf16=bf16)
     for t in range(1, 6):
@@ -373,7 +395,8 @@ def test_shared_gradient_mode_forms_the_replica_mean_in_one_plane(cfg, batch, n,
         losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, t)
         gbar = O.shared_gradient(grads)
         assert np.max(np.abs(gl - losses)) <= (1e-2 if bf16 else 2e-5)
-        g0 = run.g.cpu().numpy()[0, :run.P]
+        g0, summed = device_mean_gradient(cfg, run.g.cpu().numpy()[:, :run.P], n)
+        assert len(summed) == (1 if cfg is BIGV else 0), summed
         if bf16:
             check_bf16_gradients(cfg, g0, gbar, 4e-2, ("shared", cfg["d_model"], t))
         else:
