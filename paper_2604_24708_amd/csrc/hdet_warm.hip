@@ -53,27 +53,32 @@ __device__ __forceinline__ void box_muller_f32(uint32_t w0, uint32_t w1, float* 
   *z1 = rad * sn;
 }
 
-__global__ __launch_bounds__(256) void warm_noise_kernel(const float* theta0, float* theta, int64_t n, int64_t stride,
+// thread = one block of four elements in every replica: theta_0 comes from memory once
+__global__ __launch_bounds__(256) void warm_noise_kernel(const float* theta0, float* theta, int64_t n, int64_t stride, int n_replicas,
                                                          const double* sumsq, double nu, uint32_t seed_lo, uint32_t seed_hi) {
   typedef float f4 __attribute__((ext_vector_type(4)));
-  const int r = blockIdx.y;
   const float sigma = (float)(nu * sqrt(*sumsq / (double)n));
   const int64_t nblk = (n + 3) >> 2;
   for (int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x; b < nblk; b += (int64_t)gridDim.x * 256) {
-    const hdet_philox4 w = hdet_philox4x32_10((uint32_t)b, (uint32_t)r, 0u, kWarmStream, seed_lo, seed_hi);
-    float z[4];
-    box_muller_f32(w.x[0], w.x[1], &z[0], &z[1]);
-    box_muller_f32(w.x[2], w.x[3], &z[2], &z[3]);
     const int64_t i = b << 2;
-    if (i + 3 < n) {           // whole block of four: 16-byte accesses (theta0 and the planes are 16-byte aligned)
-      const f4 t0 = *reinterpret_cast<const f4*>(theta0 + i);
+    const bool whole = i + 3 < n;     // 16-byte accesses (theta0 and the planes are 16-byte aligned)
+    f4 t0 = {0.f, 0.f, 0.f, 0.f};
+    if (whole) t0 = __builtin_nontemporal_load(reinterpret_cast<const f4*>(theta0 + i));
+    else
+      for (int j = 0; j < 4; ++j)
+        if (i + j < n) t0[j] = theta0[i + j];
+    for (int r = 0; r < n_replicas; ++r) {
+      const hdet_philox4 w = hdet_philox4x32_10((uint32_t)b, (uint32_t)r, 0u, kWarmStream, seed_lo, seed_hi);
+      float z[4];
+      box_muller_f32(w.x[0], w.x[1], &z[0], &z[1]);
+      box_muller_f32(w.x[2], w.x[3], &z[2], &z[3]);
       const f4 o = {__builtin_fmaf(sigma, z[0], t0[0]), __builtin_fmaf(sigma, z[1], t0[1]), __builtin_fmaf(sigma, z[2], t0[2]),
                     __builtin_fmaf(sigma, z[3], t0[3])};
-      __builtin_nontemporal_store(o, reinterpret_cast<f4*>(theta + (int64_t)r * stride + i));
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (i + j < n) theta[(int64_t)r * stride + i + j] = __builtin_fmaf(sigma, z[j], theta0[i + j]);
+      float* dst = theta + (int64_t)r * stride + i;
+      if (whole) __builtin_nontemporal_store(o, reinterpret_cast<f4*>(dst));
+      else
+        for (int j = 0; j < 4; ++j)
+          if (i + j < n) dst[j] = o[j];
     }
   }
 }
@@ -90,9 +95,9 @@ hipError_t hdet_launch_warm_init(const float* theta0, float* theta, int64_t n_pa
   hipLaunchKernelGGL(sumsq_partial_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta0, n_params, partial);
   hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(1), 0, s, partial, (int)nb, sumsq);
   int64_t gb = ((n_params + 3) / 4 + 255) / 256;
-  if (gb > 65536) gb = 65536;
+  if (gb > 262144) gb = 262144;
   if (gb < 1) gb = 1;
-  hipLaunchKernelGGL(warm_noise_kernel, dim3((unsigned)gb, n_replicas), dim3(256), 0, s, theta0, theta, n_params, stride,
+  hipLaunchKernelGGL(warm_noise_kernel, dim3((unsigned)gb), dim3(256), 0, s, theta0, theta, n_params, stride, n_replicas,
                      sumsq, nu, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32));
   return hipGetLastError();
 }
