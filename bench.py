@@ -90,13 +90,14 @@ def oracle_baseline_all_cores(n, t_sync, p_sample, steps):
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def mlp_workload(args, shared=False):
+def mlp_workload(args, shared=False, one_call=False):
     """N = 8 replicas of the 4-layer MLP 1024-4096-4096-4096-1000, batch 256 per replica, bf16
     GEMMs with fp32 master weights, AdamW, one-cycle 1000 steps peak 3e-4, alpha 0.1, T = 16,
     auto-LR on.  A step = forward/backward + fan-out update (+ converge + controller on sync
     steps).  shared: the paper's own mode -- every replica applies the replica mean of the gradients
     (formed as one gradient plane by the model path) and AdamW's moments are kept once.
-    Returns a dict of measurements."""
+    one_call: hdet_train_step instead of hdet_forward_backward + hdet_fanout_step (the weight matrices' updates are
+    then applied inside the products that form their gradients).  Returns a dict of measurements."""
     import numpy as np
     import torch
     import hdet_inputs as I
@@ -133,10 +134,14 @@ def mlp_workload(args, shared=False):
         if timed:
             e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             e[0].record(stream)
-        H.hdet_forward_backward(h, x, y)
+        if one_call:
+            H.hdet_train_step(h, x, y, H.HDET_FUSE_CONVERGE)
+        else:
+            H.hdet_forward_backward(h, x, y)
         if timed:
             e[1].record(stream)
-        H.hdet_fanout_step(h, None, H.HDET_FUSE_CONVERGE)
+        if not one_call:
+            H.hdet_fanout_step(h, None, H.HDET_FUSE_CONVERGE)
         if timed:
             e[2].record(stream)
             ev.append(e)
@@ -164,10 +169,12 @@ def mlp_workload(args, shared=False):
     # replica (30 N), or one gradient plane and one set of moments (10 N + 20)
     upd_bytes = (10.0 * n + 20.0) * P if shared else 30.0 * n * P
     return {"workload": "N=8 x MLP 1024-4096-4096-4096-1000, batch 256/replica, bf16 GEMM + fp32 master, AdamW, T=16"
-                        + (", shared gradients (one gradient plane, one set of moments)" if shared else ""),
+                        + (", shared gradients (one gradient plane, one set of moments)" if shared else "")
+                        + (", one call per step (weight updates inside the weight-gradient products)" if one_call else ""),
             "replica_steps_per_s": n * args.steps / dt, "ms_per_step": dt / args.steps * 1e3,
+            # one call per step: the update is part of the first figure
             "forward_backward_ms": fb_ms, "update_ms": up_ms, "update_algorithmic_bytes": upd_bytes,
-            "update_GBps": upd_bytes / (up_ms * 1e-3) / 1e9,
+            "update_GBps": None if one_call else upd_bytes / (up_ms * 1e-3) / 1e9,
             "gemm_flop_per_step": gemm_flop, "forward_backward_TFLOPs": tflops,
             "mfma_frac_of_bf16_peak": tflops / MFMA_BF16_PEAK_TFLOPS,
             "loss_first_replica": float(st.l_step[0])}
@@ -198,6 +205,7 @@ def transformer_workload(args):
     theta[:, :P] = torch.from_numpy(I.transformer_init(1, cfg, I.SEED_INIT)).to(dev)
     m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.zeros_like(theta)
     shared = getattr(args, "model_grad_mode", "per_replica") == "shared"
+    one_call = bool(getattr(args, "one_call", False))
     if shared:
         m, v = m[:1], v[:1]
     shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
@@ -219,10 +227,14 @@ def transformer_workload(args):
         if timed:
             e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             e[0].record(stream)
-        H.hdet_forward_backward(h, ids, tgt)
+        if one_call:
+            H.hdet_train_step(h, ids, tgt, H.HDET_FUSE_CONVERGE)
+        else:
+            H.hdet_forward_backward(h, ids, tgt)
         if timed:
             e[1].record(stream)
-        H.hdet_fanout_step(h, None, H.HDET_FUSE_CONVERGE)
+        if not one_call:
+            H.hdet_fanout_step(h, None, H.HDET_FUSE_CONVERGE)
         if timed:
             e[2].record(stream)
             ev.append(e)
@@ -249,10 +261,12 @@ def transformer_workload(args):
     tflops = gemm_flop / (fb_ms * 1e-3) / 1e12
     return {"workload": f"N=8 x decoder-only transformer {L}L d{d} h{nh} ffn{ff} seq{S} vocab{V}, {B} seq/replica, "
                         f"bf16 GEMM + fp32 master, AdamW, T={T}, {1 + len(extra)} channel(s)"
-                        + (", shared gradients (one gradient plane, one set of moments)" if shared else ""),
+                        + (", shared gradients (one gradient plane, one set of moments)" if shared else "")
+                        + (", one call per step (weight updates inside the weight-gradient products)" if one_call else ""),
             "n_params": P, "replica_steps_per_s": n * args.steps / dt, "tokens_per_s": n * M * args.steps / dt,
             "ms_per_step": dt / args.steps * 1e3, "forward_backward_ms": fb_ms, "update_ms": up_ms,
-            "update_GBps": ((10.0 * n + 20.0) if shared else 30.0 * n) * P / (up_ms * 1e-3) / 1e9, "gemm_flop_per_step": gemm_flop,
+            "update_GBps": None if one_call else ((10.0 * n + 20.0) if shared else 30.0 * n) * P / (up_ms * 1e-3) / 1e9,
+            "gemm_flop_per_step": gemm_flop,
             "forward_backward_TFLOPs": tflops, "mfma_frac_of_bf16_peak": tflops / MFMA_BF16_PEAK_TFLOPS,
             "loss_first_replica": float(st.l_step[0])}
 
@@ -414,6 +428,8 @@ def main():
                          "MLP and transformer figures attached as `mlp_bf16` and `transformer_bf16`")
     ap.add_argument("--model-grad-mode", choices=["per_replica", "shared"], default="per_replica",
                     help="--workload mlp / transformer: shared = the replica mean of the gradients as one plane, one set of moments")
+    ap.add_argument("--one-call", action="store_true",
+                    help="--workload mlp / transformer: hdet_train_step (forward, backward and update in one call)")
     ap.add_argument("--tf-config", choices=["6L", "12L"], default="6L",
                     help="transformer workload: 6 layers d512 seq256 (default) or 12 layers d1024 seq512 with 3 channels")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -450,7 +466,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.workload == "mlp":
-        print(json.dumps(mlp_workload(args, shared=args.model_grad_mode == "shared")))
+        print(json.dumps(mlp_workload(args, shared=args.model_grad_mode == "shared", one_call=args.one_call)))
         return
     if args.workload == "transformer":
         print(json.dumps(transformer_workload(args)))
@@ -569,6 +585,8 @@ def main():
         torch.cuda.empty_cache()
         out["mlp_bf16_shared_gradient"] = mlp_workload(args, shared=True)
         torch.cuda.empty_cache()
+        out["mlp_bf16_one_call"] = mlp_workload(args, one_call=True)
+        torch.cuda.empty_cache()
         targs = argparse.Namespace(**vars(args))
         targs.steps, targs.warmup = min(args.steps, 16), min(args.warmup, 4)
         out["transformer_bf16"] = transformer_workload(targs)
@@ -577,8 +595,16 @@ def main():
         out["transformer_bf16_shared_gradient"] = transformer_workload(targs)
         targs.model_grad_mode = "per_replica"
         torch.cuda.empty_cache()
+        targs.one_call = True
+        out["transformer_bf16_one_call"] = transformer_workload(targs)
+        targs.one_call = False
+        torch.cuda.empty_cache()
         targs.tf_config, targs.steps, targs.warmup = "12L", min(args.steps, 8), min(args.warmup, 2)
         out["transformer_12L_bf16"] = transformer_workload(targs)
+        torch.cuda.empty_cache()
+        targs.one_call = True
+        out["transformer_12L_bf16_one_call"] = transformer_workload(targs)
+        targs.one_call = False
         torch.cuda.empty_cache()
         out["mlp_fp32_small"] = cfg0_leg()
     if cpu_baseline is not None:

@@ -9,6 +9,7 @@
  * One training step is (Algorithm 1 of the paper):
  *     hdet_forward_backward   loss and gradient of every replica          (model modes only)
  *     hdet_fanout_step        update t with per-replica rate eta_r        (Sec. 3.2, Eq. 1-2)
+ *   (or hdet_train_step for both in one call, which lets the library fuse them)
  *   and, when t mod T == 0,
  *     hdet_converge           replica mean of the parameters              (Sec. 3.3, Eq. 3)
  *     hdet_autolr_update      controller on the interval losses           (Sec. 3.4, Eq. 4-9)
@@ -49,7 +50,7 @@ enum { HDET_FLAT = 0, HDET_MLP = 1, HDET_TRANSFORMER = 2 };   /* model kind     
 enum { HDET_CH_LR = 0, HDET_CH_DROPOUT = 1, HDET_CH_WD = 2,      /* channel kinds (Remark 1)   */
        HDET_CH_LABEL_SMOOTH = 3, HDET_CH_ATTN_TEMP = 4 };
 
-/* flags of hdet_fanout_step */
+/* flags of hdet_fanout_step and hdet_train_step */
 #define HDET_FUSE_CONVERGE 1u  /* on a sync step, average inside the update kernel (Eq. 3)   */
 
 typedef struct hdet_handle hdet_handle;
@@ -241,6 +242,24 @@ int hdet_forward_backward(hdet_handle* h, const void* x_dev, const int32_t* y_de
  * parameters (Eq. 3) is written to all replicas by the same kernel, and the following
  * hdet_converge is a no-op.  HDET_ESTATE once t == total_steps.                             */
 int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags);
+
+/* One whole step of Algorithm 1's inner loop in a single call: forward, loss and backward on
+ * (x_dev, y_dev) as hdet_forward_backward does, then update t <- t+1 (Sec. 3.2, Eq. 1-2) as
+ * hdet_fanout_step(h, NULL, flags) does.  Parameters, optimizer state, bfloat16 copy, losses and
+ * schedule state after the call are those of the two separate calls, bit for bit.  The gradient
+ * buffer given at creation is still required but is NOT a defined output of this call: with
+ * HDET_BF16_GEMM_FP32_MASTER, HDET_ADAMW, HDET_GRAD_PER_REPLICA and per-replica moments the
+ * update of a weight matrix is applied inside the product that forms its gradient (every
+ * replica's tile of dW is complete in one block, so Eq. 2 can be applied to it at once), and
+ * that gradient is never written to memory: 26 instead of 30 + 4 bytes per weight and replica.
+ * Biases, LayerNorm parameters and embeddings, and every configuration outside the one named,
+ * take the ordinary update.  With HDET_FUSE_CONVERGE on a sync step the replica mean of Eq. 3
+ * is formed after all updates (by the update kernel, or by the converge kernel when some
+ * updates were applied inside products), and the following hdet_converge is a no-op.
+ * losses_host as for hdet_forward_backward.  HDET_ESTATE for HDET_FLAT handles and once
+ * t == total_steps.                                                                          */
+int hdet_train_step(hdet_handle* h, const void* x_dev, const int32_t* y_dev, uint32_t flags,
+                    float* losses_host);
 
 /* theta_r <- (1/N) sum_r' theta_r' for all r (Eq. 3), summed in the order r' = 0..N-1;
  * optimizer state is left per replica.  May be called at any t (Algorithm 1 calls it when

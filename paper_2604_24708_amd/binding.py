@@ -25,7 +25,7 @@ HDET_CH_LR, HDET_CH_DROPOUT, HDET_CH_WD, HDET_CH_LABEL_SMOOTH, HDET_CH_ATTN_TEMP
 HDET_FUSE_CONVERGE = 1
 
 EXPORTS = [
-    "hdet_workspace_bytes", "hdet_create", "hdet_warm_init", "hdet_warm_init_noalloc", "hdet_forward_backward", "hdet_fanout_step",
+    "hdet_workspace_bytes", "hdet_create", "hdet_warm_init", "hdet_warm_init_noalloc", "hdet_forward_backward", "hdet_fanout_step", "hdet_train_step",
     "hdet_converge", "hdet_autolr_update", "hdet_get_state", "hdet_set_state",
     "hdet_set_launch_shape", "hdet_last_error", "hdet_destroy",
 ]
@@ -121,6 +121,7 @@ def load_library(path: Optional[str] = None):
     lib.hdet_warm_init_noalloc.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, C.c_double, C.c_uint64, vp]
     lib.hdet_forward_backward.argtypes = [vp, vp, vp, C.POINTER(C.c_float)]
     lib.hdet_fanout_step.argtypes = [vp, vp, C.c_uint32]
+    lib.hdet_train_step.argtypes = [vp, vp, vp, C.c_uint32, C.POINTER(C.c_float)]
     lib.hdet_converge.argtypes = [vp]
     lib.hdet_autolr_update.argtypes = [vp, C.POINTER(C.c_double)]
     lib.hdet_get_state.argtypes = [vp, C.POINTER(hdet_state)]
@@ -232,6 +233,12 @@ def hdet_forward_backward(h, x, y, want_losses: bool = False):
 
 def hdet_fanout_step(h, grads=None, flags: int = 0):
     _check(load_library().hdet_fanout_step(h, _ptr(grads), flags), h)
+
+
+def hdet_train_step(h, x, y, flags: int = 0, want_losses: bool = False):
+    out = (C.c_float * HDET_MAX_REPLICAS)() if want_losses else None
+    _check(load_library().hdet_train_step(h, _ptr(x), _ptr(y), flags, out), h)
+    return out
 
 
 def hdet_converge(h):

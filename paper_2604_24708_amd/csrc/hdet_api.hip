@@ -315,16 +315,11 @@ int hdet_warm_init(hdet_handle* h, const float* theta0_dev, double nu, uint64_t 
   return write_shadow(h);
 }
 
-int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
-  if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
-  if (flags & ~HDET_FUSE_CONVERGE) return fail(h, HDET_EINVAL, "unknown flag");
-  const float* g = grads_dev ? grads_dev : h->buf.grads_dev;
-  if (!g) return fail(h, HDET_EINVAL, "no gradient buffer");
-  if (!aligned16(g)) return fail(h, HDET_EINVAL, "grads_dev must be 16-byte aligned");
-  const hdet_config& c = h->cfg;
-  if (h->t >= c.total_steps) return fail(h, HDET_ESTATE, "all total_steps updates are done");
-  const int64_t t = h->t + 1;
+namespace {
 
+// Arguments of update t (1-based) over the whole plane, with the gradients at g.
+void fill_update_args(const hdet_handle* h, int64_t t, const float* g, hdet_update_args* out) {
+  const hdet_config& c = h->cfg;
   hdet_update_args a;
   memset(&a, 0, sizeof(a));
   a.theta = h->buf.params_dev;
@@ -354,50 +349,50 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
   a.one_m_beta2 = (float)(1.0 - c.beta2);
   a.eps = (float)c.eps;
   a.momentum = (float)c.momentum;
+  *out = a;
+}
 
-  const bool fuse = (flags & HDET_FUSE_CONVERGE) && (t % c.sync_interval == 0);
-  // A model handle in shared-gradient mode leaves some slices of the plane as one sum over the replicas (plane 0 of its
-  // gradient buffer) and the rest as one gradient per replica; either way the kernel applies the replica mean.
-  std::vector<std::pair<int64_t, int64_t>> summed;
+enum slice_kind { kSummed, kDone };
+
+// One launch per parameter group and kind of slice: the slice of every plane with the group's rate channel.
+// `special` (ascending, disjoint): slices whose gradient is one plane holding the sum over the replicas (kSummed: read
+// with plane stride 0 and scaled by 1 / N), or whose update has already been applied (kDone: skipped).
+int launch_updates(hdet_handle* h, const hdet_update_args& a, const hdet_slices& special, slice_kind kind, bool fuse_converge) {
+  const hdet_config& c = h->cfg;
   const bool shared = c.grad_mode == HDET_GRAD_SHARED;
-  if (!grads_dev && shared && c.model_kind == HDET_MLP) summed.push_back({0, a.n_params});
-  if (!grads_dev && shared && c.model_kind == HDET_TRANSFORMER) hdet_tf_summed_slices(h->tf, &summed);
-  // one launch per parameter group and kind of slice: the slice of every plane with the group's rate channel
   int64_t begin = 0;
   size_t si = 0;
   for (int grp = 0; grp < h->n_lr; ++grp) {
     const int64_t gend = h->n_lr > 1 ? c.group_end[grp] : a.n_params;
     while (begin < gend) {
-      while (si < summed.size() && summed[si].first + summed[si].second <= begin) ++si;
-      const bool in_sum = si < summed.size() && summed[si].first <= begin;
+      while (si < special.size() && special[si].first + special[si].second <= begin) ++si;
+      const bool in_special = si < special.size() && special[si].first <= begin;
       int64_t end = gend;
-      if (in_sum) end = std::min(end, summed[si].first + summed[si].second);
-      else if (si < summed.size()) end = std::min(end, summed[si].first);
-      hdet_update_args ga = a;
-      ga.theta += begin; ga.grad += begin; ga.m += begin;
-      if (ga.v) ga.v += begin;
-      if (ga.shadow) ga.shadow += begin;
-      ga.n_params = end - begin;
-      ga.lr_channel = grp;
-      if (in_sum) {
-        ga.grad_stride = 0;
-        ga.grad_scale = (float)(1.0 / (double)c.n_replicas);
+      if (in_special) end = std::min(end, special[si].first + special[si].second);
+      else if (si < special.size()) end = std::min(end, special[si].first);
+      if (!(in_special && kind == kDone)) {
+        hdet_update_args ga = a;
+        ga.theta += begin; ga.grad += begin; ga.m += begin;
+        if (ga.v) ga.v += begin;
+        if (ga.shadow) ga.shadow += begin;
+        ga.n_params = end - begin;
+        ga.lr_channel = grp;
+        if (in_special) {
+          ga.grad_stride = 0;
+          ga.grad_scale = (float)(1.0 / (double)c.n_replicas);
+        }
+        // identical gradients need no mean over the replicas, except that one set of moments is built on that kernel
+        const bool mean = shared && (!in_special || c.shared_opt_state);
+        hipError_t e = hdet_launch_update(ga, c.optimizer, mean, fuse_converge, h->tune_variant, default_blocks(h), h->stream);
+        if (e != hipSuccess) return hip_fail(h, e, "update kernel");
       }
-      // identical gradients need no mean over the replicas, except that one set of moments is built on that kernel
-      const bool mean = shared && (!in_sum || c.shared_opt_state);
-      hipError_t e = hdet_launch_update(ga, c.optimizer, mean, fuse, h->tune_variant, default_blocks(h), h->stream);
-      if (e != hipSuccess) return hip_fail(h, e, "update kernel");
       begin = end;
     }
   }
-  h->t = t;
-  if (fuse) h->converged_at_t = t;
   return HDET_OK;
 }
 
-int hdet_converge(hdet_handle* h) {
-  if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
-  if (h->converged_at_t == h->t) return HDET_OK;     // already averaged by the fused update
+int launch_converge(hdet_handle* h) {
   hdet_converge_args a;
   a.theta = h->buf.params_dev;
   a.shadow = h->cfg.precision == HDET_BF16_GEMM_FP32_MASTER ? h->buf.params_bf16_dev : nullptr;
@@ -409,6 +404,86 @@ int hdet_converge(hdet_handle* h) {
   if (e != hipSuccess) return hip_fail(h, e, "converge kernel");
   h->converged_at_t = h->t;
   return HDET_OK;
+}
+
+}  // namespace
+
+int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags) {
+  if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
+  if (flags & ~HDET_FUSE_CONVERGE) return fail(h, HDET_EINVAL, "unknown flag");
+  const float* g = grads_dev ? grads_dev : h->buf.grads_dev;
+  if (!g) return fail(h, HDET_EINVAL, "no gradient buffer");
+  if (!aligned16(g)) return fail(h, HDET_EINVAL, "grads_dev must be 16-byte aligned");
+  const hdet_config& c = h->cfg;
+  if (h->t >= c.total_steps) return fail(h, HDET_ESTATE, "all total_steps updates are done");
+  const int64_t t = h->t + 1;
+  hdet_update_args a;
+  fill_update_args(h, t, g, &a);
+  const bool fuse = (flags & HDET_FUSE_CONVERGE) && (t % c.sync_interval == 0);
+  // A model handle in shared-gradient mode leaves some slices of the plane as one sum over the replicas (plane 0 of its
+  // gradient buffer) and the rest as one gradient per replica; either way the kernel applies the replica mean.
+  hdet_slices summed;
+  const bool shared = c.grad_mode == HDET_GRAD_SHARED;
+  if (!grads_dev && shared && c.model_kind == HDET_MLP) summed.push_back({0, a.n_params});
+  if (!grads_dev && shared && c.model_kind == HDET_TRANSFORMER) hdet_tf_summed_slices(h->tf, &summed);
+  if (int rc = launch_updates(h, a, summed, kSummed, fuse)) return rc;
+  h->t = t;
+  if (fuse) h->converged_at_t = t;
+  return HDET_OK;
+}
+
+int hdet_train_step(hdet_handle* h, const void* x_dev, const int32_t* y_dev, uint32_t flags, float* losses_host) {
+  if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
+  if (flags & ~HDET_FUSE_CONVERGE) return fail(h, HDET_EINVAL, "unknown flag");
+  const hdet_config& c = h->cfg;
+  if (c.model_kind == HDET_FLAT || (!h->mlp && !h->tf)) return fail(h, HDET_ESTATE, "flat handles have no forward/backward");
+  if (!x_dev || !y_dev) return fail(h, HDET_EINVAL, "x_dev and y_dev are required");
+  if (!aligned16(x_dev)) return fail(h, HDET_EINVAL, "x_dev must be 16-byte aligned");
+  if (!h->buf.grads_dev) return fail(h, HDET_EINVAL, "no gradient buffer");
+  if (h->t >= c.total_steps) return fail(h, HDET_ESTATE, "all total_steps updates are done");
+  const int64_t t = h->t + 1;
+  hdet_update_args a;
+  fill_update_args(h, t, h->buf.grads_dev, &a);
+  // the weight matrices' updates go into the products that form their gradients where the arithmetic allows it
+  const bool can_fuse = c.precision == HDET_BF16_GEMM_FP32_MASTER && c.optimizer == HDET_ADAMW &&
+                        c.grad_mode == HDET_GRAD_PER_REPLICA && !c.shared_opt_state;
+  hdet_slices done;
+  hipError_t e = h->tf ? hdet_tf_forward_backward(h->tf, (const int32_t*)x_dev, y_dev, h->ctrl_dev, (uint32_t)t, h->stream,
+                                                  can_fuse ? &a : nullptr, can_fuse ? &done : nullptr)
+                       : hdet_mlp_forward_backward(h->mlp, x_dev, y_dev, h->ctrl_dev, h->stream, can_fuse ? &a : nullptr,
+                                                   can_fuse ? &done : nullptr);
+  if (e != hipSuccess) return hip_fail(h, e, "forward/backward kernels");
+  std::sort(done.begin(), done.end());
+  const bool sync = (flags & HDET_FUSE_CONVERGE) && (t % c.sync_interval == 0);
+  int rc;
+  if (done.empty()) {
+    hdet_slices summed;
+    const bool shared = c.grad_mode == HDET_GRAD_SHARED;
+    if (shared && c.model_kind == HDET_MLP) summed.push_back({0, a.n_params});
+    if (shared && c.model_kind == HDET_TRANSFORMER) hdet_tf_summed_slices(h->tf, &summed);
+    rc = launch_updates(h, a, summed, kSummed, sync);
+    if (rc != HDET_OK) return rc;
+    h->t = t;
+    if (sync) h->converged_at_t = t;
+  } else {
+    // the rest of the plane; the converge of a sync step then runs over the whole plane on its own
+    rc = launch_updates(h, a, done, kDone, false);
+    if (rc != HDET_OK) return rc;
+    h->t = t;
+    if (sync && (rc = launch_converge(h)) != HDET_OK) return rc;
+  }
+  if (losses_host) {
+    e = hipMemcpyAsync(losses_host, h->ctrl_dev->l_step, sizeof(float) * c.n_replicas, hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "copy of the step losses");
+  }
+  return HDET_OK;
+}
+
+int hdet_converge(hdet_handle* h) {
+  if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
+  if (h->converged_at_t == h->t) return HDET_OK;     // already averaged by the fused update
+  return launch_converge(h);
 }
 
 int hdet_autolr_update(hdet_handle* h, const double* interval_losses_host) {

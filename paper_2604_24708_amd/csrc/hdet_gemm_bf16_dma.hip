@@ -35,6 +35,7 @@
 
 #include "hdet_internal.h"
 #include "hdet_elem.h"
+#include "hdet_update_math.h"
 
 namespace {
 
@@ -293,6 +294,15 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
     drop_thresh = (uint32_t)floor((double)p * 4294967296.0);
     drop_scale = 1.f / (1.f - p);
   }
+  // HDET_EPI_ADAMW: the tile is the replica's gradient of a weight matrix and is applied at once (Eq. 2 with the
+  // replica's rate); the matrix's parameters and moments of a strip are requested before the strip goes through LDS
+  constexpr bool kUpd = EPI == HDET_EPI_ADAMW;
+  hdet_um::rep_scalars us = {0.f, 0.f, 0.f, 0.f};
+  if (kUpd) {
+    us = hdet_um::replica_scalars(g.upd, z);
+    if (bx == 0 && by == 0 && tid == 0 && g.upd.lr_channel == 0) g.upd.ctrl_out->lr_used[z] = us.lr;
+  }
+  f4 uth[kUpd ? NIT : 1], um[kUpd ? NIT : 1], uv[kUpd ? NIT : 1];
   // column sums of the stored result over the wavefront's rows, for the columns this lane stores (per strip column group)
   constexpr bool kColsum = EPI == HDET_EPI_GELUGRAD_BF16 || EPI == HDET_EPI_MASK_BF16;
   f4 csum[WNT / JG];
@@ -309,6 +319,18 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
     for (int i = 0; i < WMT; ++i) {
       const int strip = jg * WMT + i;
       if (kGate && strip + 1 < NSTRIP) fetch_gate(strip + 1, gate[(strip + 1) & 1]);
+      if (kUpd) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+          const int row = m0 + wm + i * 32 + it * RPI + lr;
+          if (row < g.m && col_ok) {
+            const int64_t off = c_base + (int64_t)row * g.ldc + col;
+            uth[it] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g.upd.theta + off));
+            um[it] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g.upd.m + off));
+            uv[it] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g.upd.v + off));
+          }
+        }
+      }
       // accumulator element e of lane l is C(row, col) with row = (e / 4) * 8 + (l / 32) * 4 + e % 4,
       // col = l % 32 inside its 32x32 block
 #pragma unroll
@@ -356,7 +378,17 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = bf2f(f2bf(v[q])) * hdet_gelu_tanh_grad_fast(bf2f(a[q]));
           }
-          if (EPI == HDET_EPI_F32 || EPI == HDET_EPI_BIAS_F32) {
+          if (EPI == HDET_EPI_ADAMW) {
+            f4 th = uth[it], mm = um[it], vv = uv[it];
+            hdet_um::update_one<HDET_ADAMW, f4>(th, v, mm, vv, g.upd, us);
+            __builtin_nontemporal_store(mm, reinterpret_cast<f4*>(g.upd.m + off));
+            __builtin_nontemporal_store(vv, reinterpret_cast<f4*>(g.upd.v + off));
+            __builtin_nontemporal_store(th, reinterpret_cast<f4*>(g.upd.theta + off));
+            if (g.upd.shadow) {
+              const us4 o = {hdet_um::to_bf16(th[0]), hdet_um::to_bf16(th[1]), hdet_um::to_bf16(th[2]), hdet_um::to_bf16(th[3])};
+              __builtin_nontemporal_store(o, reinterpret_cast<us4*>(g.upd.shadow + off));
+            }
+          } else if (EPI == HDET_EPI_F32 || EPI == HDET_EPI_BIAS_F32) {
             *reinterpret_cast<f4*>(reinterpret_cast<float*>(g.c) + off) = v;
           } else if (EPI == HDET_EPI_BIAS_GELU_BF16) {
             const us4 pre = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
@@ -451,8 +483,9 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
   if ((long_k && blocks(256, 256) >= kCus) || (!gating && blocks(256, 256) >= 3 * kCus))
     HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);                                         // one block per CU, 128 KiB of stages
   else if (blocks(256, 128) >= kCus) {
-    if (long_k) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 64);                             // one block per CU, 144 KiB
-    else HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 32);                                    // two blocks per CU, 72 KiB each
+    // (the update epilogue holds a strip of theta, m and v in registers: too many for two blocks per CU)
+    if (long_k || EPI == HDET_EPI_ADAMW) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 64);    // one block per CU, 144 KiB
+    else if constexpr (EPI != HDET_EPI_ADAMW) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 32);   // two blocks per CU, 72 KiB each
   } else HDET_DMA_LAUNCH(128, 128, 2, 2, 2, 64);                                    // two blocks per CU, 64 KiB each
 #undef HDET_DMA_LAUNCH
   return hipGetLastError();
@@ -484,12 +517,17 @@ bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kma
       (!g.mask || (g.mask_ld & 3) || (g.mask_bs & 3) || (reinterpret_cast<uintptr_t>(g.mask) & 7)))
     return false;
   if (epi == HDET_EPI_BIAS_GELU_BF16 && (!g.c2 || (reinterpret_cast<uintptr_t>(g.c2) & 7))) return false;
+  if (epi == HDET_EPI_ADAMW &&
+      (g.n1 * g.n2 != 1 || !g.upd.theta || !g.upd.m || !g.upd.v || !g.upd.ctrl || !g.upd.ctrl_out ||
+       ((reinterpret_cast<uintptr_t>(g.upd.theta) | reinterpret_cast<uintptr_t>(g.upd.m) | reinterpret_cast<uintptr_t>(g.upd.v)) & 15) ||
+       (reinterpret_cast<uintptr_t>(g.upd.shadow) & 7)))
+    return false;
   // instantiated combinations: what the MLP and the transformer use
   if (a_kmajor && b_kmajor)
     return epi == HDET_EPI_BIAS_RELU_BF16 || epi == HDET_EPI_BIAS_F32 || epi == HDET_EPI_BIAS_BF16 || epi == HDET_EPI_F32 ||
            epi == HDET_EPI_BIAS_GELU_BF16 || epi == HDET_EPI_BIAS_RESID_BF16 || epi == HDET_EPI_BIAS_DROP_RESID_BF16;
   if (a_kmajor && !b_kmajor) return epi == HDET_EPI_MASK_BF16 || epi == HDET_EPI_BF16 || epi == HDET_EPI_GELUGRAD_BF16;
-  if (!a_kmajor && !b_kmajor) return epi == HDET_EPI_F32 || epi == HDET_EPI_BF16;
+  if (!a_kmajor && !b_kmajor) return epi == HDET_EPI_F32 || epi == HDET_EPI_BF16 || epi == HDET_EPI_ADAMW;
   return false;
 }
 
@@ -516,5 +554,6 @@ hipError_t hdet_launch_bgemm_dma(const hdet_bgemm_args& g_in, bool a_kmajor, boo
     return launch_shape<true, false, HDET_EPI_BF16>(g, batch, s);
   }
   if (epi == HDET_EPI_F32) return launch_shape<false, false, HDET_EPI_F32>(g, batch, s);   // wgrad
+  if (epi == HDET_EPI_ADAMW) return launch_shape<false, false, HDET_EPI_ADAMW>(g, batch, s);
   return launch_shape<false, false, HDET_EPI_BF16>(g, batch, s);
 }

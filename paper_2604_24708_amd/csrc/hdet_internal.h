@@ -10,6 +10,8 @@
 
 #include "hdet.h"
 
+typedef std::vector<std::pair<int64_t, int64_t>> hdet_slices;    // (offset, length) slices of a parameter plane
+
 // ---------------------------------------------------------------------------------------
 // Device-resident schedule / controller state (one per handle).  Kernels read the rates
 // from here, so no step needs a host round trip: the host only knows t.
@@ -150,7 +152,8 @@ enum { HDET_EPI_F32 = 0, HDET_EPI_BIAS_F32 = 1, HDET_EPI_BIAS_RELU_BF16 = 2, HDE
        HDET_EPI_BIAS_GELU_BF16 = 6,   // c = bf16(acc + bias), c2 = bf16(gelu(c)): pre-activation and activation
        HDET_EPI_GELUGRAD_BF16 = 7,    // c = bf16(bf16(acc) * gelu'(mask)): gradient through the GELU at pre-activation `mask`
        HDET_EPI_BIAS_RESID_BF16 = 8,  // c = bf16(mask + bf16(acc + bias)): a Linear layer added to its residual stream `mask`
-       HDET_EPI_BIAS_DROP_RESID_BF16 = 9 };   // the same with dropout of the layer's output before the sum
+       HDET_EPI_BIAS_DROP_RESID_BF16 = 9,     // the same with dropout of the layer's output before the sum
+       HDET_EPI_ADAMW = 10 };         // weight gradient that is applied at once: the AdamW update of `upd` on the tile (c is not written)
 
 struct hdet_bgemm_args {
   const uint16_t* a;       // bf16
@@ -172,7 +175,35 @@ struct hdet_bgemm_args {
   // sum of C as stored over that 128-row block of the column (stage 1 of the bias gradient of the layer whose
   // pre-activation gradient C is); colsum_bs is unused padding for alignment
   float* colsum;
+  // HDET_EPI_ADAMW (n1 = n2 = 1, batch item = replica): the product is the replica's gradient of a weight matrix;
+  // element (row, col) updates theta / m / v / shadow at [replica * c_s[0] + row * ldc + col] of upd's pointers,
+  // which point at the matrix inside plane 0, with the scalars of upd (Eq. 2; per-replica rate from upd.ctrl)
+  hdet_update_args upd;
 };
+
+// Parameter group that holds the slice [off, off + len) of a plane, or -1 if it lies in more than one.
+inline int hdet_group_of_slice(const hdet_config& c, int64_t off, int64_t len) {
+  if (c.n_groups <= 1) return 0;
+  int64_t begin = 0;
+  for (int g = 0; g < c.n_groups; ++g) {
+    if (off >= begin && off + len <= c.group_end[g]) return g;
+    begin = c.group_end[g];
+  }
+  return -1;
+}
+
+// A weight matrix whose update a model path may apply inside the weight-gradient product: `fuse` with its pointers
+// moved to the matrix and the matrix's rate channel, or false if the matrix spans parameter groups.
+inline bool hdet_fuse_args_for(const hdet_config& c, const hdet_update_args& fuse, int64_t off, int64_t len, hdet_update_args* out) {
+  const int grp = hdet_group_of_slice(c, off, len);
+  if (grp < 0) return false;
+  *out = fuse;
+  out->theta += off; out->m += off; out->v += off;
+  if (out->shadow) out->shadow += off;
+  out->n_params = len;
+  out->lr_channel = grp;
+  return true;
+}
 
 // a_kmajor: A(m,k) at a[m*lda + k], else at a[k*lda + m]; b_kmajor: B(k,n) at b[n*ldb + k], else
 // at b[k*ldb + n].  (true,true) forward, (true,false) dgrad, (false,false) wgrad.
@@ -192,8 +223,12 @@ struct hdet_mlp_plan;
 int hdet_mlp_workspace_bytes(const hdet_config& cfg, size_t* bytes, std::string* err);
 hdet_mlp_plan* hdet_mlp_create(const hdet_config& cfg, const hdet_buffers& buf, int ls_channel, std::string* err);
 void hdet_mlp_destroy(hdet_mlp_plan* p);
+// fuse != nullptr (mixed precision, AdamW, per-replica gradients and moments): the update described by *fuse (pointers at
+// plane 0, scalars of this step) is applied to a weight matrix inside the product that forms its gradient where
+// that product can; the slices (offset, length) updated that way are appended to *fused and their gradients are not
+// written.
 hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
-                                     hipStream_t stream);
+                                     hipStream_t stream, const hdet_update_args* fuse = nullptr, hdet_slices* fused = nullptr);
 
 // ---------------------------------------------------------------------------------------
 // Transformer forward/backward (hdet_transformer.hip)
@@ -211,8 +246,10 @@ void hdet_tf_set_fused_attention(hdet_tf_plan* p, bool on);   // on by default w
 // sum over the replicas in plane 0 of the gradient buffer; everywhere else it leaves one gradient plane per replica.
 void hdet_tf_summed_slices(const hdet_tf_plan* p, std::vector<std::pair<int64_t, int64_t>>* out);
 // `step`: the update this gradient is for (keys the dropout masks)
+// fuse, fused: as for hdet_mlp_forward_backward
 hipError_t hdet_tf_forward_backward(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl,
-                                    uint32_t step, hipStream_t stream);
+                                    uint32_t step, hipStream_t stream, const hdet_update_args* fuse = nullptr,
+                                    hdet_slices* fused = nullptr);
 
 // ---------------------------------------------------------------------------------------
 // Fused causal attention, bf16 (hdet_attention.hip)

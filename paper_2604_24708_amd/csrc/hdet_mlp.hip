@@ -404,7 +404,7 @@ static hipError_t forward_backward_f32(hdet_mlp_plan* p, const void* x, const in
 }
 
 static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
-                                        hipStream_t s) {
+                                        hipStream_t s, const hdet_update_args* fuse, hdet_slices* fused) {
   const hdet_config& c = p->cfg;
   const int N = c.n_replicas, B = c.dims.batch, L = p->n_layers;
   const int* w = c.dims.widths;
@@ -435,13 +435,6 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
   if (hipError_t e = hdet_launch_xent(true, p->logits, y, B, w[L], dz, p->row_loss, N, ctrl, p->ls_channel, s, nullptr, 0, B)) return e;
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(N), dim3(256), 0, s, p->row_loss, B, ctrl);
   for (int i = L - 1; i >= 0; --i) {
-    hdet_bgemm_args g = {};                          // dW = dZ^T X
-    g.a = dz; g.lda = w[i + 1]; g.a_s[0] = (int64_t)B * w[i + 1];               // A(o,b) = dZ[b][o]
-    g.b = (const uint16_t*)p->act[i]; g.ldb = w[i]; g.b_s[0] = (int64_t)B * w[i];   // B(b,k) = X[b][k]
-    g.c = grads + p->w_off[i]; g.ldc = w[i]; g.c_s[0] = ps;
-    g.m = w[i + 1]; g.n = w[i]; g.k = shared ? N * B : B;
-    e = hdet_launch_bgemm(g, false, false, HDET_EPI_F32, shared ? 1 : N, s);
-    if (e != hipSuccess) return e;
     // db = column sums of dZ: from the 128-row partial sums when the product that formed dZ left them, else from dZ itself
     if (have_part)
       hipLaunchKernelGGL(bias_grad_kernel<float>, dim3((w[i + 1] + 63) / 64, shared ? 1 : N), dim3(256), 0, s, p->colsum_part,
@@ -450,7 +443,8 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
       hipLaunchKernelGGL(bias_grad_kernel<uint16_t>, dim3((w[i + 1] + 63) / 64, shared ? 1 : N), dim3(256), 0, s, dz, shared ? N * B : B, w[i + 1],
                          (int64_t)B * w[i + 1], grads + p->b_off[i], ps);
     have_part = false;
-    if (i > 0) {                                     // dX = dZ W, through the ReLU below
+    const uint16_t* dz_cur = dz;
+    if (i > 0) {                                     // dX = dZ W, through the ReLU below (before W is touched by a fused update)
       hdet_bgemm_args d = {};
       d.a = dz; d.lda = w[i + 1]; d.a_s[0] = (int64_t)B * w[i + 1];
       d.b = wbf + p->w_off[i]; d.ldb = w[i]; d.b_s[0] = ps;                       // B(o,k) = W[o][k]
@@ -466,11 +460,28 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
       if (e != hipSuccess) return e;
       uint16_t* t = dz; dz = dz_next; dz_next = t;
     }
+    hdet_bgemm_args g = {};                          // dW = dZ^T X
+    g.a = dz_cur; g.lda = w[i + 1]; g.a_s[0] = (int64_t)B * w[i + 1];           // A(o,b) = dZ[b][o]
+    g.b = (const uint16_t*)p->act[i]; g.ldb = w[i]; g.b_s[0] = (int64_t)B * w[i];   // B(b,k) = X[b][k]
+    g.c = grads + p->w_off[i]; g.ldc = w[i]; g.c_s[0] = ps;
+    g.m = w[i + 1]; g.n = w[i]; g.k = shared ? N * B : B;
+    g.n1 = g.n2 = 1;
+    const int64_t wlen = (int64_t)w[i + 1] * w[i];
+    // the update of W applied by the product that forms its gradient (Eq. 2): dW never goes to memory
+    if (fuse && !shared && hdet_fuse_args_for(c, *fuse, p->w_off[i], wlen, &g.upd) &&
+        hdet_bgemm_dma_eligible(g, false, false, HDET_EPI_ADAMW)) {
+      e = hdet_launch_bgemm_dma(g, false, false, HDET_EPI_ADAMW, N, s);
+      if (e != hipSuccess) return e;
+      fused->push_back({p->w_off[i], wlen});
+      continue;
+    }
+    e = hdet_launch_bgemm(g, false, false, HDET_EPI_F32, shared ? 1 : N, s);
+    if (e != hipSuccess) return e;
   }
   return hipGetLastError();
 }
 
 hipError_t hdet_mlp_forward_backward(hdet_mlp_plan* p, const void* x, const int32_t* y, hdet_ctrl* ctrl,
-                                     hipStream_t s) {
-  return p->bf16 ? forward_backward_bf16(p, x, y, ctrl, s) : forward_backward_f32(p, x, y, ctrl, s);
+                                     hipStream_t s, const hdet_update_args* fuse, hdet_slices* fused) {
+  return p->bf16 ? forward_backward_bf16(p, x, y, ctrl, s, fused ? fuse : nullptr, fused) : forward_backward_f32(p, x, y, ctrl, s);
 }

@@ -1195,7 +1195,8 @@ hipError_t gemm(const hdet_tf_plan* pl, int form, mat A, mat B, void* c, int64_t
 #define TF_CHECK(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
 template <typename T>
-hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl, uint32_t step, hipStream_t s) {
+hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl, uint32_t step, hipStream_t s,
+               const hdet_update_args* fuse, hdet_slices* fused) {
   const int N = p->N, M = p->M, S = p->S, d = p->d, ff = p->ff, V = p->V, L = p->L, nh = p->nh, dh = p->dh, B = p->B;
   const int64_t ps = p->buf.plane_stride;
   const float* theta = p->buf.params_dev;
@@ -1301,15 +1302,28 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
   auto ln_params = [&](const void* dy, const void* x, const float* mean, const float* rstd, int64_t g_off, int64_t b_off) {
     return launch_colsum<T, 1>(p, dy, d, x, mean, rstd, g_off, b_off, s);
   };
-  auto wgrad = [&](const void* dy, int wy, const void* x, int wx, int64_t w_off) {      // dW[wy][wx] = dy^T x
+  // Every weight gradient is formed after the input gradient of its layer (which reads the weights): with `fuse` the
+  // product applies the update of W at once (Eq. 2) and dW never goes to memory.
+  auto wgrad = [&](const void* dy, int wy, const void* x, int wx, int64_t w_off) -> hipError_t {      // dW[wy][wx] = dy^T x
     const bool one = shared && tf_wgrad_one_product(wy, wx);
+    if (sizeof(T) == 2 && fuse && !shared) {
+      hdet_bgemm_args g = {};
+      g.a = (const uint16_t*)dy; g.lda = wy; g.a_s[0] = (int64_t)M * wy;
+      g.b = (const uint16_t*)x; g.ldb = wx; g.b_s[0] = (int64_t)M * wx;
+      g.ldc = wx; g.c_s[0] = ps;
+      g.m = wy; g.n = wx; g.k = M; g.n1 = g.n2 = 1;
+      if (hdet_fuse_args_for(p->cfg, *fuse, w_off, (int64_t)wy * wx, &g.upd) && hdet_bgemm_dma_eligible(g, false, false, HDET_EPI_ADAMW)) {
+        fused->push_back({w_off, (int64_t)wy * wx});
+        return hdet_launch_bgemm_dma(g, false, false, HDET_EPI_ADAMW, N, s);
+      }
+    }
     return gemm<T>(p, TN, act(dy, wy), act(x, wx), grads + w_off, wx, plane, false, wy, wx, one ? N * M : M, 1, 1, nullptr, 0, s,
                    nullptr, one);
   };
 
-  TF_CHECK(wgrad(p->dlogits, V, p->hf, d, p->w_head));
   if (!head_part) TF_CHECK(colsum(p->dlogits, V, p->b_head));
   TF_CHECK(gemm<T>(p, NN, act(p->dlogits, V), wt(p->w_head, d), p->dtmp, d, act_d, true, M, d, V, 1, 1, nullptr, 0, s));
+  TF_CHECK(wgrad(p->dlogits, V, p->hf, d, p->w_head));
   // With a dropout channel, the gradient that enters a residual branch is the stream's gradient passed
   // through that branch's dropout; the LayerNorm backward kernel that produces the stream's gradient
   // writes it as a second output where it can (dropped_done), else a separate pass does.
@@ -1328,7 +1342,6 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
         hipLaunchKernelGGL((dropout_kernel<T, false>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)nullptr, (const T*)p->dxa, (T*)p->dtmp2, nd, da);
       dy = p->dtmp2;
     }
-    TF_CHECK(wgrad(dy, d, p->f[l], ff, o.w_2));
     if (!b2_done) TF_CHECK(colsum(dy, d, o.b_2));
     bool b1_done = false;
     {
@@ -1343,9 +1356,10 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
         hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for((int64_t)N * nff)), dim3(256), 0, s, (const T*)p->dff, (const T*)p->z[l], (T*)p->dff, (int64_t)N * nff);
       b1_done = fused && b1_part;
     }
-    TF_CHECK(wgrad(p->dff, ff, p->h2[l], d, o.w_1));
+    TF_CHECK(wgrad(dy, d, p->f[l], ff, o.w_2));
     if (!b1_done) TF_CHECK(colsum(p->dff, ff, o.b_1));
     TF_CHECK(gemm<T>(p, NN, act(p->dff, ff), wt(o.w_1, d), p->dtmp, d, act_d, true, M, d, ff, 1, 1, nullptr, 0, s));
+    TF_CHECK(wgrad(p->dff, ff, p->h2[l], d, o.w_1));
     dropped_done = false;
     da.site = 2 * l;
     bo_done = false;
@@ -1359,9 +1373,9 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
         hipLaunchKernelGGL((dropout_kernel<T, false>), dim3(grid_for(nd / 4), N), dim3(256), 0, s, (const T*)nullptr, (const T*)p->dxb, (T*)p->dtmp2, nd, da);
       dob = p->dtmp2;
     }
-    TF_CHECK(wgrad(dob, d, p->a[l], d, o.w_o));
     if (!bo_done) TF_CHECK(colsum(dob, d, o.b_o));
     TF_CHECK(gemm<T>(p, NN, act(dob, d), wt(o.w_o, d), p->dtmp, d, act_d, true, M, d, d, 1, 1, nullptr, 0, s));   // da
+    TF_CHECK(wgrad(dob, d, p->a[l], d, o.w_o));
     if (p->fused_attn) {
       hdet_attn_desc ad = attn_desc(l);
       TF_CHECK(hdet_launch_attn_bwd(ad, s));
@@ -1377,9 +1391,9 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       TF_CHECK(gemm<T>(p, NN, head_sq(p->ds), qkv_part(p->qkv[l], 1), (void*)dq.p, 3 * d, dq.s, true, S, dh, S, B, nh, nullptr, 0, s));
       TF_CHECK(gemm<T>(p, TN, head_sq(p->ds), qkv_part(p->qkv[l], 0), (void*)dk.p, 3 * d, dk.s, true, S, dh, S, B, nh, nullptr, 0, s));
     }
-    TF_CHECK(wgrad(p->dqkv, 3 * d, p->h1[l], d, o.w_qkv));
     TF_CHECK(colsum(p->dqkv, 3 * d, o.b_qkv));
     TF_CHECK(gemm<T>(p, NN, act(p->dqkv, 3 * d), wt(o.w_qkv, d), p->dtmp, d, act_d, true, M, d, 3 * d, 1, 1, nullptr, 0, s));
+    TF_CHECK(wgrad(p->dqkv, 3 * d, p->h1[l], d, o.w_qkv));
     dropped_done = false;
     da.site = 2 * (l - 1) + 1;                     // the MLP branch of the block below
     b2_done = false;
@@ -1411,6 +1425,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
 }  // namespace
 
 hipError_t hdet_tf_forward_backward(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet_ctrl* ctrl,
-                                    uint32_t step, hipStream_t s) {
-  return p->bf16 ? run<uint16_t>(p, ids, targets, ctrl, step, s) : run<float>(p, ids, targets, ctrl, step, s);
+                                    uint32_t step, hipStream_t s, const hdet_update_args* fuse, hdet_slices* fused) {
+  if (!fused) fuse = nullptr;
+  return p->bf16 ? run<uint16_t>(p, ids, targets, ctrl, step, s, fuse, fused) : run<float>(p, ids, targets, ctrl, step, s, nullptr, nullptr);
 }

@@ -186,3 +186,70 @@ def test_transformer_block_at_the_12_layer_shapes():
         off += k
     assert torch.all(g[:, P:] == 7.0) if stride > P else True
     H.hdet_destroy(h)
+
+
+def _model_run(kind, dims, batch, d, stride, th0, P, dev="cuda:0"):
+    n = d["n_replicas"]
+    theta = torch.zeros((n, stride), dtype=torch.float32, device=dev)
+    theta[:, :P] = torch.from_numpy(th0).to(dev)
+    m, v, g = torch.zeros_like(theta), torch.zeros_like(theta), torch.full_like(theta, 7.0)
+    shadow = torch.zeros((n, stride), dtype=torch.bfloat16, device=dev)
+    lc = library_config(d, model_kind=kind, batch=batch, precision=H.HDET_BF16_GEMM_FP32_MASTER, **dims)
+    _, _, ws = H.hdet_workspace_bytes(lc, stride)
+    wsb = torch.empty(ws, dtype=torch.uint8, device=dev)
+    h = H.hdet_create(lc, theta, m, v, grads=g, params_bf16=shadow, workspace=wsb, plane_stride=stride)
+    return dict(h=h, theta=theta, m=m, v=v, g=g, shadow=shadow, ws=wsb)
+
+
+@pytest.mark.parametrize("which", ["mlp", "transformer"])
+def test_one_call_step_at_the_benchmark_shapes_equals_the_two_calls(which):
+    """hdet_train_step in the launch configuration bench.py times (N = 8, the MLP and the 6-layer transformer at full
+    size): parameters, moments and the bfloat16 copy after three steps, the last one a sync step with the fused
+    converge, are those of hdet_forward_backward + hdet_fanout_step bit for bit, and no weight gradient was written.
+    (The two-call sequence is what the other tests of this file hold against the oracle.)"""
+    n = 8
+    if which == "mlp":
+        widths, batch = [1024, 4096, 4096, 4096, 1000], 256
+        P = I.mlp_param_count(widths)
+        th0 = I.mlp_init(1, widths, I.SEED_INIT)[0]
+        d = base(sync_interval=3)
+        kind, dims = H.HDET_MLP, dict(widths=widths)
+        x, y = I.mlp_batch(n, batch, widths[0], I.SEED_DATA, 1, widths, I.SEED_TEACHER)
+        off, mats = 0, []
+        for i in range(len(widths) - 1):
+            mats.append((off, widths[i + 1] * widths[i]))
+            off += widths[i + 1] * widths[i] + widths[i + 1]
+    else:
+        cfg = dict(n_blocks=6, d_model=512, n_heads=8, d_ff=2048, seq_len=256, vocab=32000)
+        batch = 16
+        P = I.transformer_param_count(cfg)
+        th0 = I.transformer_init(1, cfg, I.SEED_INIT)[0]
+        d = base(total_steps=2000, sync_interval=3, warm_steps=600, lr_max=6e-4, alpha=0.15)
+        kind, dims = H.HDET_TRANSFORMER, cfg
+        x, y = I.zipf_tokens(n, batch, cfg["seq_len"], cfg["vocab"], I.SEED_DATA, 1)
+        off, mats = 0, []
+        for name, shape in I.transformer_shapes(cfg):
+            k = int(np.prod(shape))
+            if name.startswith("w_"):
+                mats.append((off, k))
+            off += k
+    stride = (P + 63) // 64 * 64
+    two = _model_run(kind, dims, batch, d, stride, th0, P)
+    one = _model_run(kind, dims, batch, d, stride, th0, P)
+    xd, yd = torch.from_numpy(x).to("cuda:0"), torch.from_numpy(y).to("cuda:0")
+    for t in range(1, 4):
+        l2 = H.hdet_forward_backward(two["h"], xd, yd, want_losses=True)
+        H.hdet_fanout_step(two["h"], None, H.HDET_FUSE_CONVERGE)
+        l1 = H.hdet_train_step(one["h"], xd, yd, H.HDET_FUSE_CONVERGE, want_losses=True)
+        assert [l1[r] for r in range(n)] == [l2[r] for r in range(n)], t
+        for r in (two, one):
+            if t % 3 == 0:
+                H.hdet_converge(r["h"])
+                H.hdet_autolr_update(r["h"], None)
+        for name in ("theta", "m", "v"):
+            assert torch.equal(two[name].view(torch.int32), one[name].view(torch.int32)), (t, name)
+        assert torch.equal(two["shadow"].view(torch.int16), one["shadow"].view(torch.int16)), t
+    for off, k in mats:      # sampled: the first and last 4096 entries of every matrix in every plane
+        assert torch.all(one["g"][:, off:off + 4096] == 7.0) and torch.all(one["g"][:, off + k - 4096:off + k] == 7.0), off
+    assert torch.all(one["theta"][0, :P] == one["theta"][7, :P])          # the sync step averaged the replicas
+    H.hdet_destroy(two["h"]); H.hdet_destroy(one["h"])
