@@ -31,18 +31,20 @@ CONVERGE_BYTES = 8        # standalone converge: 4 read + 4 written
 # HBM bytes per launch of the update kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain 4e9-byte copy: x2.000 and x1.000), measured on the
 # default workload; valid only for the kernel source it was taken with.
-TRAFFIC_KERNEL_SHA = "27c4de97d1e28446"
-TRAFFIC_BYTES_PER_REPLICA_ELEMENT = 224.000e9 / 8e9
+TRAFFIC_KERNEL_SHA = "86fe73c12446da6d"
+TRAFFIC_BYTES_PER_REPLICA_ELEMENT = 223.998e9 / 8e9
 TRAFFIC_SOURCE = "profiles/update_kernels_flat_N8_P1e9_hbm_counters.txt"
 
 
 def measured_traffic(n, p):
     import hashlib
-    src = os.path.join(ROOT, "paper_2604_24708_amd", "csrc", "hdet_update.hip")
+    h = hashlib.sha256()
     try:
-        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+        for name in ("hdet_update.hip", "hdet_update_math.h"):      # the kernels and their arithmetic
+            h.update(open(os.path.join(ROOT, "paper_2604_24708_amd", "csrc", name), "rb").read())
     except OSError:
         return None
+    sha = h.hexdigest()[:16]
     if sha != TRAFFIC_KERNEL_SHA or (n, p) != (8, 1_000_000_000):
         return None      # kernel or workload changed since the counters were taken
     return TRAFFIC_BYTES_PER_REPLICA_ELEMENT * n * p
