@@ -252,8 +252,9 @@ int hdet_fanout_step(hdet_handle* h, const float* grads_dev, uint32_t flags);
  * update of a weight matrix is applied inside the product that forms its gradient (every
  * replica's tile of dW is complete in one block, so Eq. 2 can be applied to it at once), and
  * that gradient is never written to memory: 26 instead of 30 + 4 bytes per weight and replica.
- * Biases, LayerNorm parameters and embeddings, and every configuration outside the one named,
- * take the ordinary update.  With HDET_FUSE_CONVERGE on a sync step the replica mean of Eq. 3
+ * Biases, LayerNorm parameters, embeddings and matrices too small for this to pay (see
+ * hdet_set_launch_shape), and every configuration outside the one named, take the ordinary
+ * update.  With HDET_FUSE_CONVERGE on a sync step the replica mean of Eq. 3
  * is formed after all updates (by the update kernel, or by the converge kernel when some
  * updates were applied inside products), and the following hdet_converge is a no-op.
  * losses_host as for hdet_forward_backward.  HDET_ESTATE for HDET_FLAT handles and once
@@ -288,7 +289,10 @@ int hdet_set_state(hdet_handle* h, const hdet_state* in);
  * exchange); variant 1: the general kernel in which one thread walks the replica axis (any
  * N).  `blocks` > 0 sets the grid of the grid-stride kernels (0: library default).
  * variant | 2: the transformer's attention runs as separate batched GEMMs and softmax
- * kernels (scores and probabilities in device memory) also where the fused kernels apply.    */
+ * kernels (scores and probabilities in device memory) also where the fused kernels apply.
+ * variant | 4: hdet_train_step applies the update inside every weight-gradient product that
+ * can carry it; by default only inside products with at least one 256 x 256 tile per
+ * compute unit (the update of a smaller matrix is faster as part of the plane-wide launch).  */
 int hdet_set_launch_shape(hdet_handle* h, int32_t variant, int32_t blocks);
 
 /* Message of the last failure on this handle (or of the last failed hdet_create if h is

@@ -231,6 +231,7 @@ int hdet_create(const hdet_config* cfg, const hdet_buffers* b, hdet_handle** out
   h->converged_at_t = -1;
   h->gamma = decay_gamma(*cfg);
   h->tune_variant = 0;
+  h->fuse_everything = false;
   h->tune_blocks = 0;
   h->mlp = nullptr;
   h->tf = nullptr;
@@ -444,6 +445,7 @@ int hdet_train_step(hdet_handle* h, const void* x_dev, const int32_t* y_dev, uin
   const int64_t t = h->t + 1;
   hdet_update_args a;
   fill_update_args(h, t, h->buf.grads_dev, &a);
+  a.fuse_min_tiles = h->fuse_everything ? 0 : h->n_cu;
   // the weight matrices' updates go into the products that form their gradients where the arithmetic allows it
   const bool can_fuse = c.precision == HDET_BF16_GEMM_FP32_MASTER && c.optimizer == HDET_ADAMW &&
                         c.grad_mode == HDET_GRAD_PER_REPLICA && !c.shared_opt_state;
@@ -593,9 +595,10 @@ int hdet_set_state(hdet_handle* h, const hdet_state* in) {
 
 int hdet_set_launch_shape(hdet_handle* h, int32_t variant, int32_t blocks) {
   if (!h) return fail(nullptr, HDET_EINVAL, "handle is NULL");
-  if (variant < 0 || variant > 3) return fail(h, HDET_EINVAL, "variant must be 0..3");
+  if (variant < 0 || variant > 7) return fail(h, HDET_EINVAL, "variant must be 0..7");
   if (blocks < 0) return fail(h, HDET_EINVAL, "negative block count");
   h->tune_variant = variant & 1;
+  h->fuse_everything = (variant & 4) != 0;
   h->tune_blocks = blocks;
   if (h->tf) hdet_tf_set_fused_attention(h->tf, (variant & 2) == 0);
   return HDET_OK;

@@ -72,6 +72,7 @@ struct hdet_update_args {
   double inv_bc1;          // 1 / (1 - beta1^t)
   float inv_sqrt_bc2;      // 1 / sqrt(1 - beta2^t)
   float beta1, beta2, one_m_beta1, one_m_beta2, eps, momentum;
+  int32_t fuse_min_tiles;  // host only: a weight-gradient product carries the update if it has at least this many 256 x 256 tiles
 };
 
 struct hdet_converge_args {
@@ -192,11 +193,15 @@ inline int hdet_group_of_slice(const hdet_config& c, int64_t off, int64_t len) {
   return -1;
 }
 
-// A weight matrix whose update a model path may apply inside the weight-gradient product: `fuse` with its pointers
-// moved to the matrix and the matrix's rate channel, or false if the matrix spans parameter groups.
-inline bool hdet_fuse_args_for(const hdet_config& c, const hdet_update_args& fuse, int64_t off, int64_t len, hdet_update_args* out) {
+// A weight matrix [rows][cols] at `off` whose update a model path may apply inside the weight-gradient product: `fuse`
+// with its pointers moved to the matrix and the matrix's rate channel; false if the matrix spans parameter groups or
+// the product (one per replica) has too few tiles to keep the chip's memory system busy during its epilogues -- a small
+// product's update is faster as part of the plane-wide update launch.
+inline bool hdet_fuse_args_for(const hdet_config& c, const hdet_update_args& fuse, int64_t off, int rows, int cols, hdet_update_args* out) {
+  const int64_t len = (int64_t)rows * cols;
   const int grp = hdet_group_of_slice(c, off, len);
   if (grp < 0) return false;
+  if ((int64_t)((rows + 255) / 256) * ((cols + 255) / 256) * c.n_replicas < fuse.fuse_min_tiles) return false;
   *out = fuse;
   out->theta += off; out->m += off; out->v += off;
   if (out->shadow) out->shadow += off;
@@ -289,6 +294,7 @@ struct hdet_handle {
   hdet_channel channels[HDET_MAX_CH];
   int wd_channel;
   int32_t tune_variant, tune_blocks;
+  bool fuse_everything;       // hdet_train_step: also small weight-gradient products carry their update
   int n_cu;
   hdet_mlp_plan* mlp;
   hdet_tf_plan* tf;

@@ -468,7 +468,7 @@ static hipError_t forward_backward_bf16(hdet_mlp_plan* p, const void* x, const i
     g.n1 = g.n2 = 1;
     const int64_t wlen = (int64_t)w[i + 1] * w[i];
     // the update of W applied by the product that forms its gradient (Eq. 2): dW never goes to memory
-    if (fuse && !shared && hdet_fuse_args_for(c, *fuse, p->w_off[i], wlen, &g.upd) &&
+    if (fuse && !shared && hdet_fuse_args_for(c, *fuse, p->w_off[i], w[i + 1], w[i], &g.upd) &&
         hdet_bgemm_dma_eligible(g, false, false, HDET_EPI_ADAMW)) {
       e = hdet_launch_bgemm_dma(g, false, false, HDET_EPI_ADAMW, N, s);
       if (e != hipSuccess) return e;

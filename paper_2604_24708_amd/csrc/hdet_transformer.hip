@@ -1312,7 +1312,7 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       g.b = (const uint16_t*)x; g.ldb = wx; g.b_s[0] = (int64_t)M * wx;
       g.ldc = wx; g.c_s[0] = ps;
       g.m = wy; g.n = wx; g.k = M; g.n1 = g.n2 = 1;
-      if (hdet_fuse_args_for(p->cfg, *fuse, w_off, (int64_t)wy * wx, &g.upd) && hdet_bgemm_dma_eligible(g, false, false, HDET_EPI_ADAMW)) {
+      if (hdet_fuse_args_for(p->cfg, *fuse, w_off, wy, wx, &g.upd) && hdet_bgemm_dma_eligible(g, false, false, HDET_EPI_ADAMW)) {
         fused->push_back({w_off, (int64_t)wy * wx});
         return hdet_launch_bgemm_dma(g, false, false, HDET_EPI_ADAMW, N, s);
       }

@@ -70,6 +70,7 @@ def test_mlp_one_call_equals_two_calls_bit_for_bit(widths, batch, n, extra, grou
         split = 0
         d["group_end"] = [widths[1] * widths[0] // 2, I.mlp_param_count(widths)]
     two, one = MlpRun(d, widths, batch, bf16=True), MlpRun(d, widths, batch, bf16=True)
+    H.hdet_set_launch_shape(one.h, 4, 0)       # products of any size carry their update (by default only chip-filling ones)
     for t in range(1, 13):
         x, y = I.mlp_batch(n, batch, widths[0], I.SEED_DATA, t, widths, I.SEED_TEACHER)
         xd, yd = torch.from_numpy(x).to("cuda:0"), torch.from_numpy(y).to("cuda:0")
@@ -102,6 +103,7 @@ def test_mlp_one_call_against_the_oracle_from_the_device_state():
     widths, batch, n = [256, 384, 136], 160, 4
     d = cfg0(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, total_steps=8, warm_steps=4, weight_decay=0.01)
     run = MlpRun(d, widths, batch, bf16=True)
+    H.hdet_set_launch_shape(run.h, 4, 0)
     P = run.P
     for t in range(1, 9):
         x, y = I.mlp_batch(n, batch, widths[0], I.SEED_DATA, t, widths, I.SEED_TEACHER)
@@ -128,6 +130,7 @@ def test_mlp_one_call_against_the_oracle_from_the_device_state():
 def test_transformer_one_call_equals_two_calls_bit_for_bit(cfg, batch, n, extra):
     d = base(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, weight_decay=0.01, extra=extra)
     two, one = TfRun(d, cfg, batch, bf16=True), TfRun(d, cfg, batch, bf16=True)
+    H.hdet_set_launch_shape(one.h, 4, 0)
     shapes, off, mats = I.transformer_shapes(cfg), 0, []
     for name, shape in shapes:
         k = int(np.prod(shape))
@@ -190,3 +193,25 @@ def test_argument_errors():
     with pytest.raises(H.HdetError):
         H.hdet_train_step(run.h, xd, yd, 0)                 # all total_steps updates are done
     run.close()
+
+
+def test_small_products_keep_the_separate_update_by_default():
+    """Without the tuning flag a product with fewer 256 x 256 tiles than the chip has compute units is not worth fusing:
+    its gradient is written and the plane-wide update applies it -- same bits either way."""
+    widths, batch, n = [256, 384, 136], 160, 4
+    d = cfg0(n_replicas=n, optimizer=O.ADAMW, lr_max=2e-3, total_steps=4, warm_steps=2, weight_decay=0.01)
+    forced, default = MlpRun(d, widths, batch, bf16=True), MlpRun(d, widths, batch, bf16=True)
+    H.hdet_set_launch_shape(forced.h, 4, 0)
+    for t in range(1, 5):
+        x, y = I.mlp_batch(n, batch, widths[0], I.SEED_DATA, t, widths, I.SEED_TEACHER)
+        xd, yd = torch.from_numpy(x).to("cuda:0"), torch.from_numpy(y).to("cuda:0")
+        default.g.fill_(7.0)
+        H.hdet_train_step(forced.h, xd, yd, 0)
+        H.hdet_train_step(default.h, xd, yd, 0)
+        assert not torch.any(default.g[:, :default.P] == 7.0), t
+        for r in (forced, default):
+            if t % d["sync_interval"] == 0:
+                H.hdet_converge(r.h)
+                H.hdet_autolr_update(r.h, None)
+        assert_same_bits(forced, default, t)
+    forced.close(); default.close()
