@@ -480,7 +480,8 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
   } while (0)
   // short-K products with plenty of tiles also take the largest tile, unless the epilogue reads a second
   // operand: those do better with two blocks per CU, whose epilogues and main loops overlap
-  if ((long_k && blocks(256, 256) >= kCus) || (!gating && blocks(256, 256) >= 3 * kCus))
+  // (a single round of the largest tile on nine tenths of the chip beats two rounds of the next one)
+  if ((long_k && blocks(256, 256) * 10 >= (int64_t)kCus * 9) || (!gating && blocks(256, 256) >= 3 * kCus))
     HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);                                         // one block per CU, 128 KiB of stages
   else if (blocks(256, 128) >= kCus) {
     // (the update epilogue holds a strip of theta, m and v in registers: too many for two blocks per CU)

@@ -230,7 +230,7 @@ def test_call_order_and_argument_errors():
         H.hdet_forward_backward(run.h, run.g, run.g)            # flat handle
     assert e.value.code == H.HDET_ESTATE
     with pytest.raises(H.HdetError) as e:
-        H.hdet_set_launch_shape(run.h, 4, 0)                    # no such kernel variant
+        H.hdet_set_launch_shape(run.h, 8, 0)                    # no such kernel variant
     assert e.value.code == H.HDET_EINVAL
     assert "variant" in H.hdet_last_error(run.h)
     run.close()
