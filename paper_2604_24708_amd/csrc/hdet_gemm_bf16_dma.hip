@@ -480,10 +480,16 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
   } while (0)
   // short-K products with plenty of tiles also take the largest tile, unless the epilogue reads a second
   // operand: those do better with two blocks per CU, whose epilogues and main loops overlap
-  // (a single round of the largest tile on nine tenths of the chip beats two rounds of the next one)
-  if ((long_k && blocks(256, 256) * 10 >= (int64_t)kCus * 9) || (!gating && blocks(256, 256) >= 3 * kCus))
+  // (a single round of the largest tile on nine tenths of the chip beats two rounds of the next one; but when the
+  // largest tiles make between one and two rounds and leave the last one under 80 % full, the half-size tiles, which
+  // the CUs take up two at a time and one by one, finish sooner: 3072 x 1024 x 8 replicas at K = 8192 by 5-12 %)
+  const int64_t big = blocks(256, 256);
+  const bool ragged_rounds = big > kCus && big < 2 * (int64_t)kCus && big * 10 < 2 * (int64_t)kCus * 8;
+  if (((long_k && big * 10 >= (int64_t)kCus * 9) || (!gating && big >= 3 * kCus)) && !(long_k && ragged_rounds))
     HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);                                         // one block per CU, 128 KiB of stages
-  else if (blocks(256, 128) >= kCus) {
+  else if (long_k && ragged_rounds && EPI != HDET_EPI_ADAMW) {
+    if constexpr (EPI != HDET_EPI_ADAMW) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 32);    // two blocks per CU, 72 KiB each
+  } else if (blocks(256, 128) >= kCus) {
     // (the update epilogue holds a strip of theta, m and v in registers: too many for two blocks per CU)
     if (long_k || EPI == HDET_EPI_ADAMW) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 64);    // one block per CU, 144 KiB
     else if constexpr (EPI != HDET_EPI_ADAMW) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 32);   // two blocks per CU, 72 KiB each
