@@ -2,8 +2,8 @@
 // eps_r ~ N(0, nu^2 ||theta0||^2 / d), independent per replica and element.
 //
 // Two passes over HBM: a deterministic fp64 sum of squares of the checkpoint (per-block
-// partials added in block order), then one kernel that reads theta0 once per replica plane and
-// writes the N perturbed planes.  The noise is a pure function of (seed, replica, index):
+// partials added in block order), then one kernel that reads theta0 once and writes the N
+// perturbed planes.  The noise is a pure function of (seed, replica, index):
 // elements 4b..4b+3 come from philox(counter = (b, replica, 0, "WARM"), key = seed) through
 // two Box-Muller pairs (see box_muller_f32).
 
@@ -17,11 +17,23 @@ namespace {
 
 constexpr uint32_t kWarmStream = 0x5741524Du;   // "WARM"
 
+// Each thread walks 16-byte columns with a grid stride and keeps one fp64 sum per component (four independent
+// chains); components, lanes, wavefronts and blocks are then added in a fixed order.
 __global__ __launch_bounds__(256) void sumsq_partial_kernel(const float* theta0, int64_t n, double* partial) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
   __shared__ double red[4];
-  double s = 0.0;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const double v = (double)theta0[i];
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+  const int64_t nvec = n >> 2;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+    const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4*>(theta0) + i);
+    s0 += (double)v[0] * (double)v[0];
+    s1 += (double)v[1] * (double)v[1];
+    s2 += (double)v[2] * (double)v[2];
+    s3 += (double)v[3] * (double)v[3];
+  }
+  double s = (s0 + s1) + (s2 + s3);
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {          // the n mod 4 trailing elements
+    const double v = (double)theta0[(nvec << 2) + threadIdx.x];
     s += v * v;
   }
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
