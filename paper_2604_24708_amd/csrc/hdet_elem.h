@@ -123,19 +123,23 @@ __device__ __forceinline__ float hdet_gelu_tanh_grad(float z) {
   return 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * z * z);
 }
 
-// The same two functions with tanh(u) = 1 - 2 / (exp(2u) + 1) on the hardware exp2 and
-// reciprocal (absolute error of a few 1e-7): for results that are rounded to bfloat16 anyway.
-__device__ __forceinline__ float hdet_tanh_fast(float u) {
-  return 1.f - 2.f * __builtin_amdgcn_rcpf(__expf(2.f * u) + 1.f);
+// The same two functions for results that are rounded to bfloat16 anyway, on the hardware exp2 and reciprocal
+// (absolute error of a few 1e-7).  With u = c (z + 0.044715 z^3):  0.5 (1 + tanh u) = sigma(2u) = 1 / (1 + exp(-2u)), so
+//   gelu(z)  = z sigma(2u),        exp(-2u) = exp2(z (k1 + k2 z^2)),  k1 = -2 c log2(e),  k2 = 0.044715 k1
+//   gelu'(z) = sigma + z sigma (1 - sigma) 2 u'(z) = sigma (1 + z (1 - sigma) (k3 + k4 z^2)),  k3 = 2 c,  k4 = 6 c 0.044715
+// z -> -inf gives exp2 = inf, sigma = 0 and the limits 0 and 0; z -> +inf gives sigma = 1 and the limits z and 1.
+__device__ __forceinline__ float hdet_gelu_sigma_fast(float z, float z2) {
+  const float k1 = -2.302208198144325f, k2 = -0.1029432395800235f;
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(z * __builtin_fmaf(k2, z2, k1)));
 }
 __device__ __forceinline__ float hdet_gelu_tanh_fast(float z) {
-  const float c = 0.7978845608028654f;
-  return 0.5f * z * (1.f + hdet_tanh_fast(c * (z + 0.044715f * z * z * z)));
+  return z * hdet_gelu_sigma_fast(z, z * z);
 }
 __device__ __forceinline__ float hdet_gelu_tanh_grad_fast(float z) {
-  const float c = 0.7978845608028654f;
-  const float t = hdet_tanh_fast(c * (z + 0.044715f * z * z * z));
-  return 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * z * z);
+  const float k3 = 1.5957691216057308f, k4 = 0.21406444881780076f;
+  const float z2 = z * z;
+  const float sg = hdet_gelu_sigma_fast(z, z2);
+  return __builtin_fmaf(sg, (z * (1.f - sg)) * __builtin_fmaf(k4, z2, k3), sg);
 }
 
 // Philox-4x32 with 10 rounds (Salmon et al., SC'11); used for dropout masks.
