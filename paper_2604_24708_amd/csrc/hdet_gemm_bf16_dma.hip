@@ -486,8 +486,12 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
   const int64_t big = blocks(256, 256);
   const bool ragged_rounds = big > kCus && big < 2 * (int64_t)kCus && big * 10 < 2 * (int64_t)kCus * 8;
   if (((long_k && big * 10 >= (int64_t)kCus * 9) || (!gating && big >= 3 * kCus)) && !(long_k && ragged_rounds))
-    HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);                                         // one block per CU, 128 KiB of stages
-  else if (long_k && ragged_rounds && EPI != HDET_EPI_ADAMW) {
+  {
+    // weight gradients (both operands read with the transposing LDS loads) run 2-5 % faster on three stages of
+    // K = 32 than on two of 64; the forward and input-gradient products 1-6 % slower
+    if constexpr (!AK && !BK) HDET_DMA_LAUNCH(256, 256, 2, 4, 3, 32);                         // one block per CU, 96 KiB of stages
+    else HDET_DMA_LAUNCH(256, 256, 2, 4, 2, 64);                                    // one block per CU, 128 KiB of stages
+  } else if (long_k && ragged_rounds && EPI != HDET_EPI_ADAMW) {
     if constexpr (EPI != HDET_EPI_ADAMW) HDET_DMA_LAUNCH(256, 128, 4, 2, 3, 32);    // two blocks per CU, 72 KiB each
   } else if (blocks(256, 128) >= kCus) {
     // (the update epilogue holds a strip of theta, m and v in registers: too many for two blocks per CU)
