@@ -31,7 +31,8 @@
 //  * Epilogue through LDS: accumulators (lane = column, 4 consecutive rows) are transposed via a
 //    per-wavefront staging strip so that every global store writes whole rows, 4 columns per
 //    lane; bias / ReLU / ReLU-gate / bf16 rounding (hardware round-to-nearest-even) fused.
-//  * Launch order is remapped so that each XCD (own L2) works on a contiguous range of tiles.
+//  * Launch order is remapped so that each XCD (own L2) works on a contiguous range of tiles, walked in groups
+//    of tile rows so that concurrent blocks share operand tiles of both kinds.
 
 #include "hdet_internal.h"
 #include "hdet_elem.h"
@@ -151,16 +152,24 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
   typedef lds_tile<B_KMAJOR, TN, THREADS, TK> tb;
   constexpr int LPT = ta::NI + tb::NI;            // load instructions per thread and stage
 
-  int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  int bx, by, bz;
   {
+    // Launch order -> tile: each XCD (own L2; blocks are dealt to the XCDs round-robin) works through a contiguous
+    // range of tiles, and inside a batch item consecutive tiles walk groups of tile_group tile rows column by column,
+    // so that the blocks an XCD runs at one time share operand tiles of both kinds in its L2.
     const unsigned total = gridDim.x * gridDim.y * gridDim.z;
-    if ((total & 7u) == 0u) {
-      const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-      const unsigned t = (lin & 7u) * (total >> 3) + (lin >> 3);
-      bx = t % gridDim.x;
-      by = (t / gridDim.x) % gridDim.y;
-      bz = t / (gridDim.x * gridDim.y);
-    }
+    unsigned t = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    if ((total & 7u) == 0u) t = (t & 7u) * (total >> 3) + (t >> 3);
+    const unsigned per = gridDim.x * gridDim.y;
+    bz = t / per;
+    const unsigned r = t - bz * per;
+    const unsigned gm = g.tile_group > 1 ? (unsigned)g.tile_group : 1u;
+    const unsigned gsz = gm * gridDim.x;
+    const unsigned grp = r / gsz, first = grp * gm;
+    const unsigned rows = gridDim.y - first < gm ? gridDim.y - first : gm;
+    const unsigned q = r - grp * gsz;
+    by = first + q % rows;
+    bx = q / rows;
   }
   const hdet_batch_index bi = hdet_split_batch(bz, g.n1, g.n2);
   const int z = bi.z0;            // replica: bias and mask are per replica
@@ -473,10 +482,15 @@ hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {
   // a gating epilogue is long enough to want a second block on the CU up to K = 1024
   constexpr bool gating = EPI == HDET_EPI_MASK_BF16 || EPI == HDET_EPI_GELUGRAD_BF16;
   const bool long_k = g.k >= (gating ? 2048 : 1024);
+  // Tile order inside a batch item: with many tile columns, the 32 blocks an XCD runs at a time would share one
+  // operand tile of A and none of B; walking groups of 4 (2) tile rows column by column cuts the operand bytes its L2
+  // has to fetch by up to two thirds (head product of the transformer, 125 tile columns: 9-11 % faster).
 #define HDET_DMA_LAUNCH(TM, TN, WGM, WGN, NST, TK)                                                            \
   do {                                                                                                        \
     const dim3 grid((g.n + TN - 1) / TN, (g.m + TM - 1) / TM, batch);                                          \
-    hipLaunchKernelGGL((hdet_bgemm_dma_kernel<AK, BK, EPI, TM, TN, WGM, WGN, NST, TK>), grid, dim3(64 * WGM * WGN), 0, s, g); \
+    hdet_bgemm_args ga = g;                                                                                   \
+    ga.tile_group = grid.x >= 64 ? 4 : grid.x >= 12 ? 2 : 1;                                                  \
+    hipLaunchKernelGGL((hdet_bgemm_dma_kernel<AK, BK, EPI, TM, TN, WGM, WGN, NST, TK>), grid, dim3(64 * WGM * WGN), 0, s, ga); \
   } while (0)
   // short-K products with plenty of tiles also take the largest tile, unless the epilogue reads a second
   // operand: those do better with two blocks per CU, whose epilogues and main loops overlap

@@ -176,6 +176,7 @@ struct hdet_bgemm_args {
   // sum of C as stored over that 128-row block of the column (stage 1 of the bias gradient of the layer whose
   // pre-activation gradient C is); colsum_bs is unused padding for alignment
   float* colsum;
+  int tile_group;          // LDS-direct kernel: consecutive blocks walk groups of this many tile rows column by column (0, 1: row by row)
   // HDET_EPI_ADAMW (n1 = n2 = 1, batch item = replica): the product is the replica's gradient of a weight matrix;
   // element (row, col) updates theta / m / v / shadow at [replica * c_s[0] + row * ldc + col] of upd's pointers,
   // which point at the matrix inside plane 0, with the scalars of upd (Eq. 2; per-replica rate from upd.ctrl)
