@@ -159,7 +159,10 @@ void hdet_bgemm_dma_kernel(const hdet_bgemm_args g) {
     // so that the blocks an XCD runs at one time share operand tiles of both kinds in its L2.
     const unsigned total = gridDim.x * gridDim.y * gridDim.z;
     unsigned t = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    if ((total & 7u) == 0u) t = (t & 7u) * (total >> 3) + (t >> 3);
+    {   // XCD x = launch index mod 8 takes the x-th of eight contiguous ranges (the first total mod 8 ranges one tile longer)
+      const unsigned x = t & 7u, rem = total & 7u;
+      t = x * (total >> 3) + (x < rem ? x : rem) + (t >> 3);
+    }
     const unsigned per = gridDim.x * gridDim.y;
     bz = t / per;
     const unsigned r = t - bz * per;
