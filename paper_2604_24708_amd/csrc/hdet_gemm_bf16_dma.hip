@@ -467,7 +467,11 @@ bool chunk_regular(const void* base, int64_t ld, const int64_t* bs, int chunk_ex
 }
 
 // compute units of the current device (queried once per device; 256 on MI355X)
-int compute_units() {
+int compute_units() { return hdet_compute_units(); }
+
+}  // namespace
+
+int hdet_compute_units() {
   static int cached[64] = {0};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
@@ -477,6 +481,8 @@ int compute_units() {
   }
   return cached[dev];
 }
+
+namespace {
 
 template <bool AK, bool BK, int EPI>
 hipError_t launch_shape(const hdet_bgemm_args& g, int batch, hipStream_t s) {

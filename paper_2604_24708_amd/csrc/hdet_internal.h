@@ -219,6 +219,7 @@ hipError_t hdet_launch_bgemm(const hdet_bgemm_args& g, bool a_kmajor, bool b_kma
 // whole, 16-byte aligned chunks; C, bias and mask addressable 4 columns at a time; batch-item extents
 // below 2 GiB); n1, n2 >= 1 on entry.
 bool hdet_bgemm_dma_eligible(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi);
+int hdet_compute_units();     // compute units of the current device (queried once per device; 256 on MI355X)
 hipError_t hdet_launch_bgemm_dma(const hdet_bgemm_args& g, bool a_kmajor, bool b_kmajor, int epi, int batch,
                                  hipStream_t stream);
 

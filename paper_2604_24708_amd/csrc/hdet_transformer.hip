@@ -196,6 +196,19 @@ __global__ __launch_bounds__(256) void pos_bwd_kernel(float* grads, int64_t ps, 
   }
 }
 
+// Weight gradient formed in `splits` pieces along the contraction (the rows of the batch): dW = sum of the pieces in
+// the order 0 .. splits-1.  part[(replica * splits + piece) * len + i], len a multiple of 4.
+__global__ __launch_bounds__(256) void wgrad_sum_kernel(const float* part, int splits, int64_t len, float* grads, int64_t ps, int64_t w_off) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const int r = blockIdx.y;
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= len) return;
+  const float* src = part + (int64_t)r * splits * len + i;
+  f4 acc = *reinterpret_cast<const f4*>(src);
+  for (int sidx = 1; sidx < splits; ++sidx) acc += *reinterpret_cast<const f4*>(src + sidx * len);
+  *reinterpret_cast<f4*>(grads + (int64_t)r * ps + w_off + i) = acc;
+}
+
 __global__ __launch_bounds__(256) void zero_kernel(float* p, int64_t ps, int64_t off, int64_t n) {
   float* q = p + (int64_t)blockIdx.y * ps + off;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) q[i] = 0.f;
@@ -1315,6 +1328,25 @@ hipError_t run(hdet_tf_plan* p, const int32_t* ids, const int32_t* targets, hdet
       if (hdet_fuse_args_for(p->cfg, *fuse, w_off, wy, wx, &g.upd) && hdet_bgemm_dma_eligible(g, false, false, HDET_EPI_ADAMW)) {
         fused->push_back({w_off, (int64_t)wy * wx});
         return hdet_launch_bgemm_dma(g, false, false, HDET_EPI_ADAMW, N, s);
+      }
+    }
+    // A small matrix's product has too few tiles for the chip (d x d at d = 512: 128 tiles of 128 x 128 on 256 CUs,
+    // each with the whole K = M to walk): it is formed in 2 or 4 pieces along the contraction, as extra batch items into
+    // the logits buffer (dead since the loss kernel ran), and the pieces are added in a fixed order.
+    if (sizeof(T) == 2 && !one) {
+      const int64_t len = (int64_t)wy * wx, tiles = (int64_t)((wy + 127) / 128) * ((wx + 127) / 128) * N;
+      const int cus = hdet_compute_units();
+      int splits = 1;
+      for (int c = 4; c >= 2; c >>= 1)
+        if (tiles * c <= 2 * (int64_t)cus && M % (c * 64) == 0 && M / c >= 512) { splits = c; break; }
+      if (splits > 1 && tiles < cus && (len & 3) == 0 && (w_off & 3) == 0 && (ps & 3) == 0 &&
+          (int64_t)N * splits * len <= (int64_t)N * M * V) {
+        const int kc = M / splits;
+        const mat a = {dy, wy, {(int64_t)M * wy, (int64_t)kc * wy, 0}}, b = {x, wx, {(int64_t)M * wx, (int64_t)kc * wx, 0}};
+        const int64_t cs[3] = {splits * len, len, 0};
+        TF_CHECK(gemm<T>(p, TN, a, b, p->logits, wx, cs, false, wy, wx, kc, splits, 1, nullptr, 0, s));
+        hipLaunchKernelGGL(wgrad_sum_kernel, dim3((unsigned)((len / 4 + 255) / 256), N), dim3(256), 0, s, p->logits, splits, len, grads, ps, w_off);
+        return hipGetLastError();
       }
     }
     return gemm<T>(p, TN, act(dy, wy), act(x, wx), grads + w_off, wx, plane, false, wy, wx, one ? N * M : M, 1, 1, nullptr, 0, s,

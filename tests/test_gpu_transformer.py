@@ -195,6 +195,25 @@ def test_bf16_loss_curve_within_1e2(cfg, batch, n, steps):
     run.close()
 
 
+def test_bf16_weight_gradients_formed_in_pieces_along_the_batch():
+    """1024 rows per replica and matrices of one or two tiles: every weight gradient is formed in two pieces along the
+    contraction (as extra batch items) and the pieces are added in a fixed order.  Against the oracle entry by entry,
+    and bit-reproducible from run to run."""
+    cfg = dict(n_blocks=1, d_model=64, n_heads=1, d_ff=128, seq_len=64, vocab=56)
+    d = base(n_replicas=2, optimizer=O.ADAMW, lr_max=2e-3)
+    run = TfRun(d, cfg, 16, bf16=True)
+    ids, tgt, gl = run.forward_backward(1)
+    losses, grads = run.oracle_grads(run.orc.theta, ids, tgt, 1)
+    assert np.max(np.abs(gl - losses)) <= 1e-2
+    g1 = run.g.clone()
+    for r in range(2):
+        check_bf16_gradients(cfg, g1[r, :run.P].cpu().numpy(), grads[r], 4e-2, ("pieces", r))
+    run.g.fill_(7.0)
+    run.forward_backward(1)
+    assert torch.equal(g1[:, :run.P], run.g[:, :run.P])
+    run.close()
+
+
 def test_bf16_dropout_loss_matches():
     extra = [(O.CH_DROPOUT, 0.1, 1.0, 0.5, 0.0, 0.45)]
     d = base(n_replicas=4, optimizer=O.ADAMW, lr_max=2e-3, extra=extra)
